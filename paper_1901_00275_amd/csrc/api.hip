@@ -1,0 +1,690 @@
+// C ABI of libvlq: argument checks, memory ownership, kernel sequencing.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+// ---------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIPCHK(expr)                                                                                   \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess)                                                                          \
+            return fail(e_ == hipErrorOutOfMemory ? VLQ_ENOMEM : VLQ_EHIP, "%s: %s (%s:%d)", #expr,    \
+                        hipGetErrorString(e_), __FILE__, __LINE__);                                    \
+    } while (0)
+
+#define LAUNCHCHK() HIPCHK(hipGetLastError())
+
+extern "C" const char *vlq_last_error(void) { return g_err; }
+extern "C" int vlq_version(void) { return VLQ_VERSION; }
+
+// ---------------------------------------------------------------------------
+// index object
+// ---------------------------------------------------------------------------
+struct ProfRec {
+    int stage;
+    hipEvent_t t0, t1;
+};
+
+struct vlq_index {
+    vlq_params_t p;
+    float lam_step, lam_zero;
+    // codebooks and graph
+    float *C = nullptr, *cn = nullptr, *P = nullptr, *E = nullptr;
+    int32_t *S = nullptr;
+    // staged points, in insertion order
+    int64_t ntotal = 0, cap = 0;
+    int32_t *st_label = nullptr, *st_ids = nullptr;
+    uint8_t *st_lam = nullptr, *st_codes = nullptr;
+    // inverted lists
+    bool finalized = false;
+    int64_t lists_cap = 0;
+    int64_t *off = nullptr;
+    int32_t *ids = nullptr;
+    uint8_t *codes = nullptr, *lam = nullptr;
+    // scratch
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    // profiling
+    bool prof = false;
+    std::vector<ProfRec> recs;
+};
+
+struct Bump {
+    char *base;
+    size_t off = 0;
+    explicit Bump(void *b) : base((char *)b) {}
+    template <typename T>
+    T *take(size_t count)
+    {
+        off = (off + 255) & ~(size_t)255;
+        T *p = base ? (T *)(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+static int ws_reserve(vlq_index *idx, size_t bytes)
+{
+    if (bytes <= idx->ws_bytes) return VLQ_OK;
+    if (idx->ws) {
+        HIPCHK(hipDeviceSynchronize()); // queued kernels may still use the old block
+        HIPCHK(hipFree(idx->ws));
+        idx->ws = nullptr;
+        idx->ws_bytes = 0;
+    }
+    bytes += bytes / 8;
+    HIPCHK(hipMalloc(&idx->ws, bytes));
+    idx->ws_bytes = bytes;
+    return VLQ_OK;
+}
+
+struct StageTimer {
+    vlq_index *idx;
+    hipStream_t st;
+    int stage;
+    hipEvent_t t0 = nullptr;
+    StageTimer(vlq_index *i, hipStream_t s, int g) : idx(i), st(s), stage(g)
+    {
+        if (idx->prof && hipEventCreate(&t0) == hipSuccess) (void)hipEventRecord(t0, st);
+    }
+    ~StageTimer()
+    {
+        if (!t0) return;
+        hipEvent_t t1;
+        if (hipEventCreate(&t1) != hipSuccess) {
+            (void)hipEventDestroy(t0);
+            return;
+        }
+        (void)hipEventRecord(t1, st);
+        idx->recs.push_back({stage, t0, t1});
+    }
+};
+
+extern "C" void vlq_index_free(vlq_index_t *idx)
+{
+    if (!idx) return;
+    (void)hipDeviceSynchronize();
+    void *ptrs[] = {idx->C, idx->cn, idx->P, idx->E, idx->S, idx->st_label, idx->st_ids, idx->st_lam,
+                    idx->st_codes, idx->off, idx->ids, idx->codes, idx->lam, idx->ws};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    for (auto &r : idx->recs) {
+        (void)hipEventDestroy(r.t0);
+        (void)hipEventDestroy(r.t1);
+    }
+    delete idx;
+}
+
+// ---------------------------------------------------------------------------
+// build
+// ---------------------------------------------------------------------------
+static int check_params(const vlq_params_t *p, float *step, float *zero)
+{
+    if (!p) return fail(VLQ_EINVAL, "params is NULL");
+    if (p->d < 1 || p->d > VLQ_MAX_DIM) return fail(VLQ_EINVAL, "d = %d outside [1, %d]", p->d, VLQ_MAX_DIM);
+    if (p->m < 1 || p->m > VLQ_MAX_M) return fail(VLQ_EINVAL, "m = %d outside [1, %d]", p->m, VLQ_MAX_M);
+    if (p->d % p->m) return fail(VLQ_EINVAL, "d = %d is not a multiple of m = %d", p->d, p->m);
+    if (p->n_edges < 1 || p->n_edges > VLQ_MAX_EDGES)
+        return fail(VLQ_EINVAL, "n_edges = %d outside [1, %d]", p->n_edges, VLQ_MAX_EDGES);
+    if (p->nlist <= p->n_edges) return fail(VLQ_EINVAL, "nlist = %d must exceed n_edges = %d", p->nlist, p->n_edges);
+    if ((int64_t)p->nlist * p->n_edges > 0x7FFFFFFF) return fail(VLQ_EINVAL, "nlist * n_edges overflows int32");
+    double lo = p->lambda_lo, hi = p->lambda_hi;
+    if (lo == 0.0 && hi == 0.0) {
+        lo = -0.25;
+        hi = 0.5;
+    }
+    if (!(lo <= 0.0 && hi > 0.0 && hi > lo)) return fail(VLQ_EINVAL, "lambda grid [%g, %g] must contain 0", lo, hi);
+    const double s = (hi - lo) / 255.0, z = -lo / s;
+    if (fabs(z - rint(z)) > 1e-6) return fail(VLQ_EINVAL, "lambda_lo * 255 / (lambda_hi - lambda_lo) is not an integer");
+    *step = (float)s;
+    *zero = (float)rint(z);
+    return VLQ_OK;
+}
+
+static int build_graph(vlq_index *idx, hipStream_t st)
+{
+    const int k = idx->p.nlist, D = idx->p.d, n = idx->p.n_edges;
+    int64_t TR = ((int64_t)256 << 20) / ((int64_t)4 * k);
+    if (TR < 128) TR = 128;
+    if (TR > k) TR = k;
+    Bump plan(nullptr);
+    plan.take<float>((size_t)TR * k);
+    int rc = ws_reserve(idx, plan.off + 256);
+    if (rc) return rc;
+    Bump b(idx->ws);
+    float *dist = b.take<float>((size_t)TR * k);
+    for (int64_t r0 = 0; r0 < k; r0 += TR) {
+        const int rows = (int)(k - r0 < TR ? k - r0 : TR);
+        launch_coarse_gemm_full(idx->C + r0 * D, rows, idx->C, k, D, idx->cn + r0, idx->cn, dist, k, st);
+        LAUNCHCHK();
+        launch_select_cells(dist, k, rows, k, idx->C + r0 * D, D, idx->cn + r0, idx->C, idx->cn, n, (int)r0,
+                            idx->S + r0 * n, idx->E + r0 * n, st);
+        LAUNCHCHK();
+    }
+    return VLQ_OK;
+}
+
+extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centroids, const float *d_pq,
+                               const float *d_base, int64_t N, const int32_t *d_ids, void *stream,
+                               vlq_index_t **out)
+{
+    float step, zero;
+    int rc = check_params(params, &step, &zero);
+    if (rc) return rc;
+    if (!d_centroids || !d_pq || !out) return fail(VLQ_EINVAL, "d_centroids, d_pq and out must not be NULL");
+    if (N < 0 || N > 0x7FFFFFFF) return fail(VLQ_EINVAL, "N = %lld outside [0, 2^31)", (long long)N);
+    if (N > 0 && !d_base) return fail(VLQ_EINVAL, "d_base is NULL with N > 0");
+    hipStream_t st = (hipStream_t)stream;
+    vlq_index *idx = new (std::nothrow) vlq_index();
+    if (!idx) return fail(VLQ_ENOMEM, "host allocation failed");
+    idx->p = *params;
+    idx->lam_step = step;
+    idx->lam_zero = zero;
+    if (params->lambda_lo == 0.f && params->lambda_hi == 0.f) {
+        idx->p.lambda_lo = -0.25f;
+        idx->p.lambda_hi = 0.5f;
+    }
+    const int k = params->nlist, D = params->d, n = params->n_edges, m = params->m;
+    auto body = [&]() -> int {
+        HIPCHK(hipMalloc(&idx->C, (size_t)k * D * 4));
+        HIPCHK(hipMalloc(&idx->cn, (size_t)k * 4));
+        HIPCHK(hipMalloc(&idx->P, (size_t)256 * D * 4));
+        HIPCHK(hipMalloc(&idx->S, (size_t)k * n * 4));
+        HIPCHK(hipMalloc(&idx->E, (size_t)k * n * 4));
+        HIPCHK(hipMalloc(&idx->off, ((size_t)k * n + 1) * 8));
+        HIPCHK(hipMemcpyAsync(idx->C, d_centroids, (size_t)k * D * 4, hipMemcpyDeviceToDevice, st));
+        HIPCHK(hipMemcpyAsync(idx->P, d_pq, (size_t)256 * D * 4, hipMemcpyDeviceToDevice, st));
+        HIPCHK(hipMemsetAsync(idx->off, 0, ((size_t)k * n + 1) * 8, st));
+        launch_row_norms(idx->C, k, D, idx->cn, st);
+        LAUNCHCHK();
+        int r = build_graph(idx, st);
+        if (r) return r;
+        idx->finalized = true; // an empty index is searchable
+        if (N > 0) {
+            r = vlq_index_add(idx, d_base, N, d_ids, stream);
+            if (r) return r;
+            r = vlq_index_finalize(idx, stream);
+            if (r) return r;
+        }
+        HIPCHK(hipStreamSynchronize(st));
+        return VLQ_OK;
+    };
+    (void)m;
+    rc = body();
+    if (rc) {
+        char keep[sizeof(g_err)];
+        memcpy(keep, g_err, sizeof(keep));
+        vlq_index_free(idx);
+        memcpy(g_err, keep, sizeof(keep));
+        return rc;
+    }
+    *out = idx;
+    return VLQ_OK;
+}
+
+extern "C" int64_t vlq_index_ntotal(const vlq_index_t *idx) { return idx ? idx->ntotal : -1; }
+extern "C" int vlq_index_is_finalized(const vlq_index_t *idx) { return idx ? (idx->finalized ? 1 : 0) : 0; }
+extern "C" int vlq_index_params(const vlq_index_t *idx, vlq_params_t *out)
+{
+    if (!idx || !out) return fail(VLQ_EINVAL, "NULL argument");
+    *out = idx->p;
+    return VLQ_OK;
+}
+
+// ---------------------------------------------------------------------------
+// encode / add
+// ---------------------------------------------------------------------------
+#define ENC_CHUNK ((int64_t)1 << 18)
+
+static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_cell, int32_t *d_edge,
+                       uint8_t *d_lambda, uint8_t *d_codes, int32_t *d_label, hipStream_t st)
+{
+    const int k = idx->p.nlist, D = idx->p.d, n = idx->p.n_edges, m = idx->p.m;
+    const int64_t chunk = nb < ENC_CHUNK ? nb : ENC_CHUNK;
+    const int nsplit = coarse_gemm_nn_splits((int)chunk, k);
+    float *xn;
+    uint64_t *cand;
+    int32_t *tcell, *tedge, *flag;
+    auto carve = [&](Bump &b) {
+        xn = b.take<float>((size_t)chunk);
+        cand = b.take<uint64_t>((size_t)chunk * nsplit * VLQ_NN_CANDS);
+        tcell = b.take<int32_t>((size_t)chunk);
+        tedge = b.take<int32_t>((size_t)chunk);
+        flag = b.take<int32_t>(64);
+    };
+    Bump plan(nullptr);
+    carve(plan);
+    int rc = ws_reserve(idx, plan.off + 256);
+    if (rc) return rc;
+    Bump b(idx->ws);
+    carve(b);
+    for (int64_t s = 0; s < nb; s += chunk) {
+        const int64_t cnt = nb - s < chunk ? nb - s : chunk;
+        const float *x = d_x + s * D;
+        // the split count is fixed by the buffer; a short tail only leaves less work per split
+        launch_row_norms(x, cnt, D, xn, st);
+        LAUNCHCHK();
+        launch_coarse_gemm_nn(x, (int)cnt, idx->C, k, D, xn, idx->cn, cand, nsplit, st);
+        LAUNCHCHK();
+        EncodeArgs a;
+        a.X = x;
+        a.nb = cnt;
+        a.D = D;
+        a.k = k;
+        a.n = n;
+        a.m = m;
+        a.C = idx->C;
+        a.S = idx->S;
+        a.E = idx->E;
+        a.P = idx->P;
+        a.lam_step = idx->lam_step;
+        a.lam_zero = idx->lam_zero;
+        a.cand = cand;
+        a.nsplit = nsplit;
+        a.cell = d_cell ? d_cell + s : (d_label ? tcell : nullptr);
+        a.edge = d_edge ? d_edge + s : (d_label ? tedge : nullptr);
+        a.lamq = d_lambda ? d_lambda + s : nullptr;
+        a.codes = d_codes ? d_codes + s * m : nullptr;
+        launch_encode_finish(a, st);
+        LAUNCHCHK();
+        if (d_label) {
+            launch_pack_labels(a.cell, a.edge, n, k, d_label + s, cnt, flag, st);
+            LAUNCHCHK();
+        }
+    }
+    return VLQ_OK;
+}
+
+extern "C" int vlq_encode(const vlq_index_t *cidx, const float *d_x, int64_t nb, int32_t *d_cell,
+                          int32_t *d_edge, uint8_t *d_lambda, uint8_t *d_codes, void *stream)
+{
+    vlq_index *idx = const_cast<vlq_index *>(cidx);
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (nb < 0) return fail(VLQ_EINVAL, "nb = %lld is negative", (long long)nb);
+    if (nb == 0) return VLQ_OK;
+    if (!d_x) return fail(VLQ_EINVAL, "d_x is NULL");
+    return encode_impl(idx, d_x, nb, d_cell, d_edge, d_lambda, d_codes, nullptr, (hipStream_t)stream);
+}
+
+static int grow_staging(vlq_index *idx, int64_t need, hipStream_t st)
+{
+    if (need <= idx->cap) return VLQ_OK;
+    int64_t ncap = idx->cap * 2;
+    if (ncap < need) ncap = need;
+    if (ncap < 1024) ncap = 1024;
+    const int m = idx->p.m;
+    int32_t *nl = nullptr, *ni = nullptr;
+    uint8_t *nlam = nullptr, *nc = nullptr;
+    HIPCHK(hipMalloc(&nl, (size_t)ncap * 4));
+    HIPCHK(hipMalloc(&ni, (size_t)ncap * 4));
+    HIPCHK(hipMalloc(&nlam, (size_t)ncap));
+    HIPCHK(hipMalloc(&nc, (size_t)ncap * m));
+    if (idx->ntotal > 0) {
+        HIPCHK(hipMemcpyAsync(nl, idx->st_label, (size_t)idx->ntotal * 4, hipMemcpyDeviceToDevice, st));
+        HIPCHK(hipMemcpyAsync(ni, idx->st_ids, (size_t)idx->ntotal * 4, hipMemcpyDeviceToDevice, st));
+        HIPCHK(hipMemcpyAsync(nlam, idx->st_lam, (size_t)idx->ntotal, hipMemcpyDeviceToDevice, st));
+        HIPCHK(hipMemcpyAsync(nc, idx->st_codes, (size_t)idx->ntotal * m, hipMemcpyDeviceToDevice, st));
+    }
+    HIPCHK(hipDeviceSynchronize());
+    void *old[] = {idx->st_label, idx->st_ids, idx->st_lam, idx->st_codes};
+    for (void *p : old)
+        if (p) HIPCHK(hipFree(p));
+    idx->st_label = nl;
+    idx->st_ids = ni;
+    idx->st_lam = nlam;
+    idx->st_codes = nc;
+    idx->cap = ncap;
+    return VLQ_OK;
+}
+
+extern "C" int vlq_index_reserve(vlq_index_t *idx, int64_t total)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (total < 0 || total > 0x7FFFFFFF) return fail(VLQ_EINVAL, "total outside [0, 2^31)");
+    return grow_staging(idx, total, nullptr);
+}
+
+static int stage_ids(vlq_index *idx, const int32_t *d_ids, int64_t nb, hipStream_t st)
+{
+    if (d_ids) {
+        HIPCHK(hipMemcpyAsync(idx->st_ids + idx->ntotal, d_ids, (size_t)nb * 4, hipMemcpyDeviceToDevice, st));
+    } else {
+        launch_iota_i32(idx->st_ids + idx->ntotal, nb, (int32_t)idx->ntotal, st);
+        LAUNCHCHK();
+    }
+    return VLQ_OK;
+}
+
+extern "C" int vlq_index_add(vlq_index_t *idx, const float *d_x, int64_t nb, const int32_t *d_ids, void *stream)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (nb < 0) return fail(VLQ_EINVAL, "nb is negative");
+    if (nb == 0) return VLQ_OK;
+    if (!d_x) return fail(VLQ_EINVAL, "d_x is NULL");
+    if (idx->ntotal + nb > 0x7FFFFFFF) return fail(VLQ_EINVAL, "more than 2^31 - 1 points");
+    hipStream_t st = (hipStream_t)stream;
+    int rc = grow_staging(idx, idx->ntotal + nb, st);
+    if (rc) return rc;
+    rc = encode_impl(idx, d_x, nb, nullptr, nullptr, idx->st_lam + idx->ntotal,
+                     idx->st_codes + idx->ntotal * idx->p.m, idx->st_label + idx->ntotal, st);
+    if (rc) return rc;
+    rc = stage_ids(idx, d_ids, nb, st);
+    if (rc) return rc;
+    idx->ntotal += nb;
+    idx->finalized = false;
+    return VLQ_OK;
+}
+
+extern "C" int vlq_index_add_encoded(vlq_index_t *idx, const int32_t *d_cell, const int32_t *d_edge,
+                                     const uint8_t *d_lambda, const uint8_t *d_codes, const int32_t *d_ids,
+                                     int64_t nb, void *stream)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (nb < 0) return fail(VLQ_EINVAL, "nb is negative");
+    if (nb == 0) return VLQ_OK;
+    if (!d_cell || !d_edge || !d_lambda || !d_codes) return fail(VLQ_EINVAL, "encoded fields must not be NULL");
+    if (idx->ntotal + nb > 0x7FFFFFFF) return fail(VLQ_EINVAL, "more than 2^31 - 1 points");
+    hipStream_t st = (hipStream_t)stream;
+    int rc = grow_staging(idx, idx->ntotal + nb, st);
+    if (rc) return rc;
+    rc = ws_reserve(idx, 256);
+    if (rc) return rc;
+    int32_t *bad = (int32_t *)idx->ws;
+    HIPCHK(hipMemsetAsync(bad, 0, 4, st));
+    launch_pack_labels(d_cell, d_edge, idx->p.n_edges, idx->p.nlist, idx->st_label + idx->ntotal, nb, bad, st);
+    LAUNCHCHK();
+    int32_t hbad = 0;
+    HIPCHK(hipMemcpyAsync(&hbad, bad, 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(hipStreamSynchronize(st));
+    if (hbad) return fail(VLQ_EINVAL, "a cell or edge index is out of range");
+    const int m = idx->p.m;
+    HIPCHK(hipMemcpyAsync(idx->st_lam + idx->ntotal, d_lambda, (size_t)nb, hipMemcpyDeviceToDevice, st));
+    HIPCHK(hipMemcpyAsync(idx->st_codes + idx->ntotal * m, d_codes, (size_t)nb * m, hipMemcpyDeviceToDevice, st));
+    rc = stage_ids(idx, d_ids, nb, st);
+    if (rc) return rc;
+    idx->ntotal += nb;
+    idx->finalized = false;
+    return VLQ_OK;
+}
+
+// ---------------------------------------------------------------------------
+// finalize
+// ---------------------------------------------------------------------------
+#define MAX_LONG 1024
+
+extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    const int m = idx->p.m;
+    const int64_t nl = (int64_t)idx->p.nlist * idx->p.n_edges;
+    const int64_t N = idx->ntotal;
+    if (N > idx->lists_cap) {
+        HIPCHK(hipDeviceSynchronize());
+        void *old[] = {idx->ids, idx->codes, idx->lam};
+        for (void *p : old)
+            if (p) HIPCHK(hipFree(p));
+        idx->ids = nullptr;
+        idx->codes = nullptr;
+        idx->lam = nullptr;
+        idx->lists_cap = 0;
+        HIPCHK(hipMalloc(&idx->ids, (size_t)N * 4));
+        HIPCHK(hipMalloc(&idx->codes, (size_t)N * m + 16));
+        HIPCHK(hipMalloc(&idx->lam, (size_t)N + 16));
+        idx->lists_cap = N;
+    }
+    Bump plan(nullptr);
+    plan.take<int32_t>((size_t)nl);
+    plan.take<int32_t>((size_t)nl);
+    plan.take<int32_t>(MAX_LONG + 1);
+    int rc = ws_reserve(idx, plan.off + 256);
+    if (rc) return rc;
+    Bump b(idx->ws);
+    int32_t *cnt = b.take<int32_t>((size_t)nl);
+    int32_t *cursor = b.take<int32_t>((size_t)nl);
+    int32_t *longs = b.take<int32_t>(MAX_LONG + 1);
+    int32_t *n_long = longs + MAX_LONG;
+    HIPCHK(hipMemsetAsync(cnt, 0, (size_t)nl * 4, st));
+    HIPCHK(hipMemsetAsync(cursor, 0, (size_t)nl * 4, st));
+    launch_list_histogram(idx->st_label, N, cnt, st);
+    LAUNCHCHK();
+    launch_exclusive_scan(cnt, nl, idx->off, st);
+    LAUNCHCHK();
+    launch_list_scatter(idx->st_label, idx->st_ids, idx->st_codes, idx->st_lam, N, m, idx->off, cursor, idx->ids,
+                        idx->codes, idx->lam, st);
+    LAUNCHCHK();
+    for (int round = 0; round < 1 << 20; ++round) {
+        HIPCHK(hipMemsetAsync(n_long, 0, 4, st));
+        launch_list_sort(idx->off, nl, m, idx->ids, idx->codes, idx->lam, longs, n_long, MAX_LONG, st);
+        LAUNCHCHK();
+        int32_t hn = 0;
+        HIPCHK(hipMemcpyAsync(&hn, n_long, 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipStreamSynchronize(st));
+        if (hn == 0) break;
+        const int take = hn < MAX_LONG ? hn : MAX_LONG;
+        std::vector<int32_t> hl(take);
+        HIPCHK(hipMemcpy(hl.data(), longs, (size_t)take * 4, hipMemcpyDeviceToHost));
+        for (int i = 0; i < take; ++i) {
+            int64_t be[2];
+            HIPCHK(hipMemcpy(be, idx->off + hl[i], 16, hipMemcpyDeviceToHost));
+            const int64_t len = be[1] - be[0];
+            int64_t sz = 1;
+            while (sz < len) sz <<= 1;
+            uint64_t *skeys = nullptr;
+            uint8_t *spay = nullptr;
+            HIPCHK(hipMalloc(&skeys, (size_t)sz * 8));
+            HIPCHK(hipMalloc(&spay, (size_t)len * (m + 1)));
+            launch_long_list_sort_at(be[0], len, m, idx->ids, idx->codes, idx->lam, skeys, spay, st);
+            LAUNCHCHK();
+            HIPCHK(hipStreamSynchronize(st));
+            HIPCHK(hipFree(skeys));
+            HIPCHK(hipFree(spay));
+        }
+        if (hn <= MAX_LONG) break;
+    }
+    HIPCHK(hipStreamSynchronize(st));
+    idx->finalized = true;
+    return VLQ_OK;
+}
+
+// ---------------------------------------------------------------------------
+// search
+// ---------------------------------------------------------------------------
+static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2, int32_t K,
+                       float *d_out_dist, int32_t *d_out_ids, int32_t *d_cells, float *d_cell_dist,
+                       int32_t *d_sub, float *d_sub_score, hipStream_t st)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    const int k = idx->p.nlist, D = idx->p.d, n = idx->p.n_edges, m = idx->p.m;
+    if (nq < 0) return fail(VLQ_EINVAL, "nq is negative");
+    if (w1 < 1 || w1 > k || w1 > VLQ_MAX_W1)
+        return fail(VLQ_EINVAL, "w1 = %d outside [1, min(nlist, %d)]", w1, VLQ_MAX_W1);
+    if ((int64_t)w1 * n > VLQ_MAX_SUBREGIONS)
+        return fail(VLQ_EINVAL, "w1 * n_edges = %lld exceeds %d", (long long)w1 * n, VLQ_MAX_SUBREGIONS);
+    if (w2 < 1 || w2 > w1 * n || w2 > VLQ_MAX_W2)
+        return fail(VLQ_EINVAL, "w2 = %d outside [1, min(w1 * n_edges, %d)]", w2, VLQ_MAX_W2);
+    if (K < 1 || K > VLQ_MAX_K) return fail(VLQ_EINVAL, "K = %d outside [1, %d]", K, VLQ_MAX_K);
+    if (!idx->finalized) return fail(VLQ_EINVAL, "index has staged points: call vlq_index_finalize first");
+    if (nq == 0) return VLQ_OK;
+    if (!d_q || !d_out_dist || !d_out_ids) return fail(VLQ_EINVAL, "d_q, d_out_dist and d_out_ids must not be NULL");
+
+    int64_t TQ = ((int64_t)512 << 20) / ((int64_t)4 * k);
+    if (TQ < 128) TQ = 128;
+    if (TQ > nq) TQ = nq;
+    const int nsplit = scan_pick_nsplit(nq, w2, K);
+
+    auto carve = [&](Bump &b, float **qn, float **dist, int32_t **cells, float **cell_dist, int32_t **slab,
+                     float **sg, uint64_t **partial) {
+        *qn = b.take<float>((size_t)nq);
+        *dist = b.take<float>((size_t)TQ * k);
+        *cells = b.take<int32_t>((size_t)nq * w1);
+        *cell_dist = b.take<float>((size_t)nq * w1);
+        *slab = b.take<int32_t>((size_t)nq * w2);
+        *sg = b.take<float>((size_t)nq * w2);
+        *partial = nsplit > 1 ? b.take<uint64_t>((size_t)nq * nsplit * K) : nullptr;
+    };
+    float *qn, *dist, *cell_dist, *sg;
+    int32_t *cells, *slab;
+    uint64_t *partial;
+    Bump plan(nullptr);
+    carve(plan, &qn, &dist, &cells, &cell_dist, &slab, &sg, &partial);
+    int rc = ws_reserve(idx, plan.off + 256);
+    if (rc) return rc;
+    Bump b(idx->ws);
+    carve(b, &qn, &dist, &cells, &cell_dist, &slab, &sg, &partial);
+
+    launch_row_norms(d_q, nq, D, qn, st);
+    LAUNCHCHK();
+    for (int64_t q0 = 0; q0 < nq; q0 += TQ) {
+        const int rows = (int)(nq - q0 < TQ ? nq - q0 : TQ);
+        {
+            StageTimer t(idx, st, VLQ_STAGE_COARSE);
+            launch_coarse_gemm_full(d_q + q0 * D, rows, idx->C, k, D, qn + q0, idx->cn, dist, k, st);
+        }
+        LAUNCHCHK();
+        {
+            StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS);
+            launch_select_cells(dist, k, rows, k, d_q + q0 * D, D, qn + q0, idx->C, idx->cn, w1, -1,
+                                cells + q0 * w1, cell_dist + q0 * w1, st);
+        }
+        LAUNCHCHK();
+    }
+    {
+        StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS);
+        launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, cells, cell_dist, w1, w2, d_sub, d_sub_score, slab,
+                          sg, st);
+    }
+    LAUNCHCHK();
+    ScanArgs a;
+    a.Q = d_q;
+    a.nq = nq;
+    a.D = D;
+    a.n = n;
+    a.m = m;
+    a.w2 = w2;
+    a.K = K;
+    a.nsplit = nsplit;
+    a.C = idx->C;
+    a.S = idx->S;
+    a.E = idx->E;
+    a.P = idx->P;
+    a.off = idx->off;
+    a.ids = idx->ids;
+    a.codes = idx->codes;
+    a.lam = idx->lam;
+    a.lam_step = idx->lam_step;
+    a.lam_zero = idx->lam_zero;
+    a.scan_label = slab;
+    a.scan_g = sg;
+    a.partial = partial;
+    a.out_dist = d_out_dist;
+    a.out_ids = d_out_ids;
+    {
+        StageTimer t(idx, st, VLQ_STAGE_SCAN);
+        launch_scan(a, st);
+    }
+    LAUNCHCHK();
+    if (nsplit > 1) {
+        StageTimer t(idx, st, VLQ_STAGE_MERGE);
+        launch_merge(partial, nq, nsplit, K, d_out_dist, d_out_ids, st);
+    }
+    LAUNCHCHK();
+    if (d_cells) HIPCHK(hipMemcpyAsync(d_cells, cells, (size_t)nq * w1 * 4, hipMemcpyDeviceToDevice, st));
+    if (d_cell_dist) HIPCHK(hipMemcpyAsync(d_cell_dist, cell_dist, (size_t)nq * w1 * 4, hipMemcpyDeviceToDevice, st));
+    return VLQ_OK;
+}
+
+extern "C" int vlq_search(const vlq_index_t *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2,
+                          int32_t K, float *d_out_dist, int32_t *d_out_ids, void *stream)
+{
+    return search_impl(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, nullptr, nullptr,
+                       nullptr, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int vlq_search_debug(const vlq_index_t *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2,
+                                int32_t K, float *d_out_dist, int32_t *d_out_ids, int32_t *d_cells,
+                                float *d_cell_dist, int32_t *d_sub, float *d_sub_score, void *stream)
+{
+    return search_impl(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, d_cells, d_cell_dist,
+                       d_sub, d_sub_score, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------
+// copies out
+// ---------------------------------------------------------------------------
+extern "C" int vlq_index_get_graph(const vlq_index_t *idx, int32_t *d_S, float *d_E, void *stream)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    const size_t cnt = (size_t)idx->p.nlist * idx->p.n_edges;
+    if (d_S) HIPCHK(hipMemcpyAsync(d_S, idx->S, cnt * 4, hipMemcpyDeviceToDevice, st));
+    if (d_E) HIPCHK(hipMemcpyAsync(d_E, idx->E, cnt * 4, hipMemcpyDeviceToDevice, st));
+    return VLQ_OK;
+}
+
+extern "C" int vlq_index_get_lists(const vlq_index_t *idx, int64_t *d_off, int32_t *d_ids, uint8_t *d_codes,
+                                   uint8_t *d_lambda, void *stream)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (!idx->finalized) return fail(VLQ_EINVAL, "index is not finalised");
+    hipStream_t st = (hipStream_t)stream;
+    const size_t nl = (size_t)idx->p.nlist * idx->p.n_edges, N = (size_t)idx->ntotal;
+    if (d_off) HIPCHK(hipMemcpyAsync(d_off, idx->off, (nl + 1) * 8, hipMemcpyDeviceToDevice, st));
+    if (N > 0) {
+        if (d_ids) HIPCHK(hipMemcpyAsync(d_ids, idx->ids, N * 4, hipMemcpyDeviceToDevice, st));
+        if (d_codes) HIPCHK(hipMemcpyAsync(d_codes, idx->codes, N * idx->p.m, hipMemcpyDeviceToDevice, st));
+        if (d_lambda) HIPCHK(hipMemcpyAsync(d_lambda, idx->lam, N, hipMemcpyDeviceToDevice, st));
+    }
+    return VLQ_OK;
+}
+
+// ---------------------------------------------------------------------------
+// profiling
+// ---------------------------------------------------------------------------
+extern "C" int vlq_profile_enable(vlq_index_t *idx, int enable)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    idx->prof = enable != 0;
+    return VLQ_OK;
+}
+
+extern "C" int vlq_profile_read(vlq_index_t *idx, float *ms, int32_t *launches)
+{
+    if (!idx || !ms) return fail(VLQ_EINVAL, "NULL argument");
+    for (int s = 0; s < VLQ_STAGE_COUNT; ++s) {
+        ms[s] = 0.f;
+        if (launches) launches[s] = 0;
+    }
+    int rc = VLQ_OK;
+    for (auto &r : idx->recs) {
+        float t = 0.f;
+        hipError_t e = hipEventSynchronize(r.t1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.t0, r.t1);
+        if (e != hipSuccess) rc = fail(VLQ_EHIP, "event timing failed: %s", hipGetErrorString(e));
+        ms[r.stage] += t;
+        if (launches) launches[r.stage] += 1;
+        (void)hipEventDestroy(r.t0);
+        (void)hipEventDestroy(r.t1);
+    }
+    idx->recs.clear();
+    return rc;
+}

@@ -1,0 +1,426 @@
+// First-level quantiser on the GPU: distances between vectors and centroids
+// (Eq. 2; Alg. 3, first loop) as a dense contraction on the fp32 matrix cores,
+// and the selection of the nearest centroids.
+//
+// The contraction uses ||a||^2 + ||b||^2 - 2<a,b>, whose fp32 rounding error is
+// relative to the norms rather than to the distance.  Every decision taken from
+// it is therefore re-taken from direct sums of squared differences over a
+// shortlist that contains everything within the rounding band of the cut.
+#include "common.h"
+
+// ---------------------------------------------------------------------------
+// row norms
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_row_norms(const float *__restrict__ X, int64_t rows, int D,
+                                                   float *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float *x = X + row * D;
+    float s = 0.f;
+    for (int d = lane; d < D; d += 64) s = fmaf(x[d], x[d], s);
+    s = wave_sum(s);
+    if (lane == 0) out[row] = s;
+}
+
+void launch_row_norms(const float *X, int64_t rows, int D, float *out, hipStream_t st)
+{
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, X, rows, D, out);
+}
+
+// ---------------------------------------------------------------------------
+// GEMM-form distances on v_mfma_f32_32x32x2_f32
+//
+// Workgroup = 256 threads = 4 waves, tile 128 (rows of A) x 128 (rows of B),
+// each wave owns a 64 x 64 quadrant = 2 x 2 MFMA blocks.  Both operands are
+// "row-major with the contraction index contiguous", so they are staged the
+// same way: a [128 x 32] slab in LDS with a row stride of 33 floats (the 32
+// lanes that read one k of 32 consecutive rows hit 32 different banks).
+// Operand layout of the instruction: lane l supplies A[i = l % 32][k = l / 32]
+// and B[k = l / 32][j = l % 32]; accumulator register r of lane l is
+// D[i = 8 (r / 4) + 4 (l / 32) + r % 4][j = l % 32].
+// ---------------------------------------------------------------------------
+#define GT 128
+#define GK 32
+#define GLD 33
+
+__device__ __forceinline__ void load_slab(float (*dst)[GLD], const float *__restrict__ src, int64_t row0,
+                                          int64_t nrows, int D, int k0, int tid, bool vec)
+{
+    const int c4 = (tid & 7) * 4;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int r = pass * 32 + (tid >> 3);
+        const int64_t gr = row0 + r;
+        float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+        if (gr < nrows) {
+            const float *p = src + gr * D + k0 + c4;
+            if (vec) {
+                if (k0 + c4 < D) {
+                    f32x4 t = *(const f32x4 *)p;
+                    v0 = t.x; v1 = t.y; v2 = t.z; v3 = t.w;
+                }
+            } else {
+                if (k0 + c4 + 0 < D) v0 = p[0];
+                if (k0 + c4 + 1 < D) v1 = p[1];
+                if (k0 + c4 + 2 < D) v2 = p[2];
+                if (k0 + c4 + 3 < D) v3 = p[3];
+            }
+        }
+        dst[r][c4 + 0] = v0;
+        dst[r][c4 + 1] = v1;
+        dst[r][c4 + 2] = v2;
+        dst[r][c4 + 3] = v3;
+    }
+}
+
+__device__ __forceinline__ void tile_product(float (*As)[GLD], float (*Bs)[GLD], const float *__restrict__ A,
+                                             int64_t m0, int M, const float *__restrict__ B, int64_t n0, int N,
+                                             int D, bool vec, int tid, int wm, int wn, int lane,
+                                             f32x16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    for (int k0 = 0; k0 < D; k0 += GK) {
+        __syncthreads();
+        load_slab(As, A, m0, M, D, k0, tid, vec);
+        load_slab(Bs, B, n0, N, D, k0, tid, vec);
+        __syncthreads();
+        const int kl = lane >> 5, rl = lane & 31;
+#pragma unroll
+        for (int kk = 0; kk < GK; kk += 2) {
+            float a0 = As[wm + rl][kk + kl], a1 = As[wm + 32 + rl][kk + kl];
+            float b0 = Bs[wn + rl][kk + kl], b1 = Bs[wn + 32 + rl][kk + kl];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_coarse_gemm_full(const float *__restrict__ A, int M,
+                                                          const float *__restrict__ B, int N, int D,
+                                                          const float *__restrict__ an,
+                                                          const float *__restrict__ bn, float *__restrict__ out,
+                                                          int64_t ldo, int vec)
+{
+    __shared__ float As[GT][GLD];
+    __shared__ float Bs[GT][GLD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    // blockIdx.x walks the tiles of B (centroids) fastest so that concurrently
+    // resident workgroups share the same slab of A.
+    const int64_t n0 = (int64_t)blockIdx.x * GT, m0 = (int64_t)blockIdx.y * GT;
+    f32x16 acc[2][2];
+    tile_product(As, Bs, A, m0, M, B, n0, N, D, vec != 0, tid, wm, wn, lane, acc);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (row >= M) continue;
+            const float ra = an[row];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int64_t col = n0 + wn + 32 * j + (lane & 31);
+                if (col < N) out[row * ldo + col] = fmaxf(ra + bn[col] - 2.f * acc[i][j][r], 0.f) + 0.f; // +0: never -0
+            }
+        }
+}
+
+void launch_coarse_gemm_full(const float *A, int M, const float *B, int N, int D, const float *an,
+                             const float *bn, float *out, int64_t ldo, hipStream_t st)
+{
+    if (M <= 0 || N <= 0) return;
+    const int vec = (D % 4 == 0) && (((uintptr_t)A | (uintptr_t)B) % 16 == 0);
+    dim3 grid((unsigned)((N + GT - 1) / GT), (unsigned)((M + GT - 1) / GT));
+    hipLaunchKernelGGL(k_coarse_gemm_full, grid, dim3(256), 0, st, A, M, B, N, D, an, bn, out, ldo, vec);
+}
+
+// Nearest-row variant: a workgroup owns 128 rows of A and a contiguous range of
+// tiles of B; every lane keeps, for each of its 32 accumulator rows, the two
+// smallest keys it has seen.  At the end the row minimum over the workgroup is
+// formed in LDS and every kept key within the rounding band of it is emitted.
+__global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict__ A, int M,
+                                                        const float *__restrict__ B, int N, int D,
+                                                        const float *__restrict__ an,
+                                                        const float *__restrict__ bn,
+                                                        uint64_t *__restrict__ cand, int nsplit,
+                                                        int tiles_per_split, int vec)
+{
+    __shared__ float As[GT][GLD];
+    __shared__ float Bs[GT][GLD];
+    __shared__ unsigned long long rowmin[GT];
+    __shared__ int rowcnt[GT];
+    __shared__ unsigned long long rowcand[GT][VLQ_NN_CANDS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int64_t m0 = (int64_t)blockIdx.x * GT;
+    const int split = blockIdx.y;
+    const int ntiles = (N + GT - 1) / GT;
+    const int t0 = split * tiles_per_split;
+    const int t1 = min(ntiles, t0 + tiles_per_split);
+
+    uint64_t b1[2][16], b2[2][16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) b1[i][r] = b2[i][r] = KEY_MAX;
+    float ra[2][16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            ra[i][r] = row < M ? an[row] : 0.f;
+        }
+
+    for (int t = t0; t < t1; ++t) {
+        const int64_t n0 = (int64_t)t * GT;
+        f32x16 acc[2][2];
+        tile_product(As, Bs, A, m0, M, B, n0, N, D, vec != 0, tid, wm, wn, lane, acc);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t col = n0 + wn + 32 * j + (lane & 31);
+            if (col >= N) continue;
+            const float cb = bn[col];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float d = fmaxf(ra[i][r] + cb - 2.f * acc[i][j][r], 0.f) + 0.f; // +0: never -0
+                    const uint64_t key = ((uint64_t)__float_as_uint(d) << 32) | (uint32_t)col;
+                    if (key < b1[i][r]) {
+                        b2[i][r] = b1[i][r];
+                        b1[i][r] = key;
+                    } else if (key < b2[i][r]) {
+                        b2[i][r] = key;
+                    }
+                }
+        }
+    }
+
+    if (tid < GT) {
+        rowmin[tid] = KEY_MAX;
+        rowcnt[tid] = 1; // slot 0 is the minimum itself
+#pragma unroll
+        for (int s = 0; s < VLQ_NN_CANDS; ++s) rowcand[tid][s] = KEY_MAX;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rl = wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (b1[i][r] != KEY_MAX) atomicMin(&rowmin[rl], (unsigned long long)b1[i][r]);
+        }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rl = wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            const uint64_t mn = rowmin[rl];
+            if (mn == KEY_MAX) continue;
+            const float dmin = __uint_as_float((uint32_t)(mn >> 32));
+            // rounding band of the GEMM form: a few ulp of ||a||^2 + ||b||^2 <= 3||a||^2 + 2 d
+            const float band = dmin + 4e-6f * (3.f * ra[i][r] + 2.f * dmin);
+            uint64_t ks[2] = {b1[i][r], b2[i][r]};
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                if (ks[s] == KEY_MAX || ks[s] == mn) continue;
+                if (__uint_as_float((uint32_t)(ks[s] >> 32)) <= band) {
+                    int pos = atomicAdd(&rowcnt[rl], 1);
+                    if (pos < VLQ_NN_CANDS) rowcand[rl][pos] = ks[s];
+                }
+            }
+        }
+    __syncthreads();
+    if (tid < GT && m0 + tid < M) {
+        uint64_t *dst = cand + ((m0 + tid) * nsplit + split) * VLQ_NN_CANDS;
+        dst[0] = rowmin[tid];
+#pragma unroll
+        for (int s = 1; s < VLQ_NN_CANDS; ++s) dst[s] = rowcand[tid][s];
+    }
+}
+
+int coarse_gemm_nn_splits(int M, int N)
+{
+    // enough workgroups to fill 256 CUs twice over, but never split B finer than 4 tiles
+    const int strips = (M + GT - 1) / GT;
+    const int ntiles = (N + GT - 1) / GT;
+    int want = (512 + strips - 1) / strips;
+    int maxs = ntiles / 4 > 1 ? ntiles / 4 : 1;
+    if (want > maxs) want = maxs;
+    if (want < 1) want = 1;
+    if (want > 64) want = 64;
+    // make the split count exact for the tile partition
+    const int per = (ntiles + want - 1) / want;
+    return (ntiles + per - 1) / per;
+}
+
+void launch_coarse_gemm_nn(const float *A, int M, const float *B, int N, int D, const float *an,
+                           const float *bn, uint64_t *cand, int nsplit, hipStream_t st)
+{
+    if (M <= 0 || N <= 0) return;
+    const int vec = (D % 4 == 0) && (((uintptr_t)A | (uintptr_t)B) % 16 == 0);
+    const int ntiles = (N + GT - 1) / GT;
+    const int per = (ntiles + nsplit - 1) / nsplit;
+    dim3 grid((unsigned)((M + GT - 1) / GT), (unsigned)nsplit);
+    hipLaunchKernelGGL(k_coarse_gemm_nn, grid, dim3(256), 0, st, A, M, B, N, D, an, bn, cand, nsplit, per, vec);
+}
+
+// ---------------------------------------------------------------------------
+// w nearest centroids of a row (Alg. 3, "w1-argmin"; also the n-NN graph rows)
+//
+// 1. radix select (4 passes of 8 bits over the float bit patterns, all
+//    non-negative) finds the value v of the w-th smallest GEMM-form distance;
+// 2. every column within the rounding band of v is collected;
+// 3. each collected column gets its distance again as a direct sum of squared
+//    differences (one wave per column);
+// 4. the collected set is sorted by (direct distance, index) and cut at w.
+// If more columns fall into the band than the shortlist holds (only possible
+// with many exactly or almost coinciding centroids) the band is dropped and
+// ties at v are resolved by index.
+// ---------------------------------------------------------------------------
+#define SEL_CAP 1024
+
+__global__ __launch_bounds__(256) void k_select_cells(const float *__restrict__ dist, int64_t ld, int k,
+                                                      const float *__restrict__ Q, int D,
+                                                      const float *__restrict__ qn,
+                                                      const float *__restrict__ C,
+                                                      const float *__restrict__ cn, int w, int self0,
+                                                      int32_t *__restrict__ cells,
+                                                      float *__restrict__ cell_dist)
+{
+    extern __shared__ float yv[]; // [D]
+    __shared__ int hist[256];
+    __shared__ uint64_t keys[SEL_CAP];
+    __shared__ int sh_cnt, sh_prefix, sh_rank, sh_eq_taken;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = blockIdx.x;
+    const float *drow = dist + (int64_t)row * ld;
+    const int self = self0 >= 0 ? self0 + row : -1;
+    const int want = w + (self >= 0 ? 1 : 0); // the row itself is among its own nearest
+
+    for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)row * D + d];
+
+    // ---- 1. radix select ----
+    uint32_t prefix = 0;
+    int rank = want - 1; // 0-based rank inside the current prefix bucket
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < k; i += 256) {
+            const uint32_t b = __float_as_uint(drow[i]);
+            const bool match = pass == 0 || (b >> (shift + 8)) == (prefix >> (shift + 8));
+            if (match) atomicAdd(&hist[(b >> shift) & 255], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int acc = 0, bin = 0;
+            for (; bin < 256; ++bin) {
+                if (acc + hist[bin] > rank) break;
+                acc += hist[bin];
+            }
+            sh_prefix = bin;
+            sh_rank = rank - acc;
+        }
+        __syncthreads();
+        prefix |= (uint32_t)sh_prefix << shift;
+        rank = sh_rank;
+        __syncthreads();
+    }
+    const float v = __uint_as_float(prefix);
+    const float rq = qn[row];
+
+    // ---- 2. collect the band ----
+    if (tid == 0) sh_cnt = 0;
+    __syncthreads();
+    for (int i = tid; i < k; i += 256) {
+        const float d = drow[i];
+        if (d <= v + 4e-6f * (rq + cn[i])) {
+            int pos = atomicAdd(&sh_cnt, 1);
+            if (pos < SEL_CAP) keys[pos] = (uint64_t)(uint32_t)i;
+        }
+    }
+    __syncthreads();
+    int cnt = sh_cnt;
+    if (cnt > SEL_CAP) {
+        // degenerate: redo without the band; ties at v go to the smallest indices
+        __syncthreads();
+        if (tid == 0) {
+            sh_cnt = 0;
+            sh_eq_taken = 0;
+        }
+        __syncthreads();
+        for (int i = tid; i < k; i += 256) {
+            if (__float_as_uint(drow[i]) < prefix) {
+                int pos = atomicAdd(&sh_cnt, 1);
+                keys[pos] = (uint64_t)(uint32_t)i; // fewer than `want` such entries
+            }
+        }
+        __syncthreads();
+        const int need_eq = want - sh_cnt;
+        __syncthreads();
+        for (int base = 0; base < k; base += 256) {
+            const int i = base + tid;
+            const bool eq = i < k && __float_as_uint(drow[i]) == prefix;
+            // rank of this thread among the equal entries of the chunk, in index order
+            hist[tid] = eq ? 1 : 0;
+            __syncthreads();
+            if (tid == 0) {
+                int acc = sh_eq_taken;
+                for (int t = 0; t < 256; ++t) {
+                    int f = hist[t];
+                    hist[t] = acc;
+                    acc += f;
+                }
+                sh_eq_taken = acc;
+            }
+            __syncthreads();
+            if (eq && hist[tid] < need_eq) keys[sh_cnt + hist[tid]] = (uint64_t)(uint32_t)i;
+            __syncthreads();
+            if (sh_eq_taken >= need_eq) break;
+        }
+        __syncthreads();
+        cnt = want;
+    }
+
+    // ---- 3. direct distances ----
+    for (int c = wave; c < cnt; c += 4) {
+        const int i = (int)(uint32_t)keys[c];
+        const float d = wave_sqdist(yv, C + (int64_t)i * D, D, lane);
+        if (lane == 0) keys[c] = (i == self) ? KEY_MAX : make_key(d, (uint32_t)i);
+    }
+    const int sz = next_pow2_dev(cnt);
+    for (int c = cnt + tid; c < sz; c += 256) keys[c] = KEY_MAX;
+    __syncthreads();
+
+    // ---- 4. order and cut ----
+    block_bitonic_sort<256>(keys, sz, tid);
+    for (int e = tid; e < w; e += 256) {
+        const uint64_t key = keys[e];
+        const bool ok = e < cnt && key != KEY_MAX;
+        cells[(int64_t)row * w + e] = ok ? (int32_t)(uint32_t)key : -1;
+        if (cell_dist) cell_dist[(int64_t)row * w + e] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+    }
+}
+
+void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const float *Q, int D,
+                         const float *qn, const float *C, const float *cn, int w, int self0,
+                         int32_t *cells, float *cell_dist, hipStream_t st)
+{
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(k_select_cells, dim3((unsigned)rows), dim3(256), (size_t)D * sizeof(float), st, dist, ld,
+                       k, Q, D, qn, C, cn, w, self0, cells, cell_dist);
+}

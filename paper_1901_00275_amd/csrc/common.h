@@ -1,0 +1,208 @@
+// Shared device helpers and internal declarations of libvlq (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/vlq.h"
+
+#define VLQ_WAVE 64
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define KEY_MAX 0xFFFFFFFFFFFFFFFFull
+
+// ---- order-preserving float <-> uint32 map (all finite floats, -0 < +0) ----
+__device__ __forceinline__ uint32_t f2ord(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ord2f(uint32_t o)
+{
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+}
+__device__ __forceinline__ uint64_t make_key(float d, uint32_t lo) { return ((uint64_t)f2ord(d) << 32) | lo; }
+
+// ---- wave-wide sum, identical in every lane ----
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o)
+{
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = __shfl_xor(lo, o, 64);
+    hi = __shfl_xor(hi, o, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        uint64_t w = shfl_xor_u64(v, o);
+        v = w < v ? w : v;
+    }
+    return v;
+}
+
+// ||x - c||^2 by one wave: x in LDS (or any memory), c a global row.  Lanes
+// stride over the dimensions, partial sums are combined by a butterfly, so the
+// result is the same in all lanes and independent of the launch shape.
+__device__ __forceinline__ float wave_sqdist(const float *x, const float *__restrict__ c, int D, int lane)
+{
+    float s = 0.f;
+    for (int d = lane; d < D; d += VLQ_WAVE) {
+        float t = x[d] - c[d];
+        s = fmaf(t, t, s);
+    }
+    return wave_sum(s);
+}
+
+// ---- block-wide bitonic sort of sz (power of two) u64 keys in LDS, ascending ----
+template <int NT>
+__device__ __forceinline__ void block_bitonic_sort(uint64_t *a, int sz, int tid)
+{
+    for (int k = 2; k <= sz; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < (sz >> 1); i += NT) {
+                int l = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                int r = l | j;
+                uint64_t x = a[l], y = a[r];
+                bool asc = (l & k) == 0;
+                if ((x > y) == asc) {
+                    a[l] = y;
+                    a[r] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// same, carrying a 16-bit payload
+template <int NT>
+__device__ __forceinline__ void block_bitonic_sort_kv(uint64_t *a, uint16_t *v, int sz, int tid)
+{
+    for (int k = 2; k <= sz; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < (sz >> 1); i += NT) {
+                int l = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                int r = l | j;
+                uint64_t x = a[l], y = a[r];
+                bool asc = (l & k) == 0;
+                if ((x > y) == asc) {
+                    a[l] = y;
+                    a[r] = x;
+                    uint16_t t = v[l];
+                    v[l] = v[r];
+                    v[r] = t;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__device__ __forceinline__ int next_pow2_dev(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+static inline int next_pow2(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+// ---------------------------------------------------------------------------
+// Kernel launchers (one per .hip file).  All pointers are device pointers.
+// ---------------------------------------------------------------------------
+
+// Squared norms of the rows of X [rows x D].
+void launch_row_norms(const float *X, int64_t rows, int D, float *out, hipStream_t st);
+
+// GEMM-form squared distances between rows of A [M x D] and rows of B [N x D]
+// on the fp32 matrix cores: out[i*ldo + j] = max(an[i] + bn[j] - 2 <A_i, B_j>, 0).
+void launch_coarse_gemm_full(const float *A, int M, const float *B, int N, int D, const float *an,
+                             const float *bn, float *out, int64_t ldo, hipStream_t st);
+
+// Same product, but only nearest-row candidates are kept: for every row of A
+// up to VLQ_NN_CANDS keys (distance bits << 32 | column) per column split that lie
+// within the rounding band of the row minimum.  cand [M x nsplit x VLQ_NN_CANDS].
+#define VLQ_NN_CANDS 4
+int coarse_gemm_nn_splits(int M, int N);
+void launch_coarse_gemm_nn(const float *A, int M, const float *B, int N, int D, const float *an,
+                           const float *bn, uint64_t *cand, int nsplit, hipStream_t st);
+
+// w smallest entries of each row of dist [rows x k] (GEMM-form values), re-evaluated
+// as direct sums of squared differences and ordered by (distance, index).
+// self0 >= 0: row r must not select column self0 + r (graph construction).
+void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const float *Q, int D,
+                         const float *qn, const float *C, const float *cn, int w, int self0,
+                         int32_t *cells, float *cell_dist, hipStream_t st);
+
+// Line scores of the w1*n sub-regions of the probed cells and the w2 best of them.
+void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
+                       int n, const int32_t *cells, const float *cell_dist, int w1, int w2,
+                       int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
+                       hipStream_t st);
+
+struct ScanArgs {
+    const float *Q;
+    int nq, D, n, m, w2, K, nsplit;
+    const float *C;
+    const int32_t *S;
+    const float *E;
+    const float *P;
+    const int64_t *off;
+    const int32_t *ids;
+    const uint8_t *codes;
+    const uint8_t *lam;
+    float lam_step, lam_zero;
+    const int32_t *scan_label;
+    const float *scan_g;
+    uint64_t *partial; // [nq x nsplit x K] when nsplit > 1
+    float *out_dist;
+    int32_t *out_ids;
+};
+void launch_scan(const ScanArgs &a, hipStream_t st);
+void launch_merge(const uint64_t *partial, int nq, int nsplit, int K, float *out_dist, int32_t *out_ids,
+                  hipStream_t st);
+int scan_pick_nsplit(int nq, int w2, int K);
+
+struct EncodeArgs {
+    const float *X;
+    int64_t nb;
+    int D, k, n, m;
+    const float *C;
+    const int32_t *S;
+    const float *E;
+    const float *P;
+    float lam_step, lam_zero;
+    const uint64_t *cand;
+    int nsplit;
+    int32_t *cell, *edge;
+    uint8_t *lamq, *codes;
+};
+void launch_encode_finish(const EncodeArgs &a, hipStream_t st);
+
+// inverted lists
+void launch_iota_i32(int32_t *p, int64_t n, int32_t start, hipStream_t st);
+void launch_pack_labels(const int32_t *cell, const int32_t *edge, int n, int k, int32_t *label, int64_t nb,
+                        int32_t *bad, hipStream_t st);
+void launch_list_histogram(const int32_t *label, int64_t N, int32_t *cnt, hipStream_t st);
+void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStream_t st);
+void launch_list_scatter(const int32_t *label, const int32_t *st_ids, const uint8_t *st_codes,
+                         const uint8_t *st_lam, int64_t N, int m, const int64_t *off, int32_t *cursor,
+                         int32_t *ids, uint8_t *codes, uint8_t *lam, hipStream_t st);
+void launch_list_sort(const int64_t *off, int64_t nl, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
+                      int32_t *long_lists, int32_t *n_long, int max_long, hipStream_t st);
+void launch_long_list_sort_at(int64_t beg, int64_t len, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
+                              uint64_t *scratch_keys, uint8_t *scratch_payload, hipStream_t st);

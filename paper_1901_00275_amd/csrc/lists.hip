@@ -1,0 +1,214 @@
+// Inverted lists (Sec. 4): list lengths (as offsets), ids, codes and lambda
+// bytes of the k*n sub-regions, list l = cell * n + edge, ascending id inside a
+// list.  Built by a counting sort of the staged points.
+#include "common.h"
+
+__global__ void k_iota_i32(int32_t *p, int64_t n, int32_t start)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = start + (int32_t)i;
+}
+void launch_iota_i32(int32_t *p, int64_t n, int32_t start, hipStream_t st)
+{
+    if (n <= 0) return;
+    hipLaunchKernelGGL(k_iota_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, start);
+}
+
+__global__ void k_pack_labels(const int32_t *__restrict__ cell, const int32_t *__restrict__ edge, int n, int k,
+                              int32_t *__restrict__ label, int64_t nb, int32_t *__restrict__ bad)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nb) return;
+    const int c = cell[i], e = edge[i];
+    if (c < 0 || c >= k || e < 0 || e >= n) {
+        label[i] = -1;
+        atomicOr(bad, 1);
+    } else {
+        label[i] = c * n + e;
+    }
+}
+void launch_pack_labels(const int32_t *cell, const int32_t *edge, int n, int k, int32_t *label, int64_t nb,
+                        int32_t *bad, hipStream_t st)
+{
+    if (nb <= 0) return;
+    hipLaunchKernelGGL(k_pack_labels, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, cell, edge, n, k,
+                       label, nb, bad);
+}
+
+__global__ void k_list_histogram(const int32_t *__restrict__ label, int64_t N, int32_t *__restrict__ cnt)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride) {
+        const int l = label[i];
+        if (l >= 0) atomicAdd(&cnt[l], 1);
+    }
+}
+void launch_list_histogram(const int32_t *label, int64_t N, int32_t *cnt, hipStream_t st)
+{
+    if (N <= 0) return;
+    int64_t blocks = (N + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_list_histogram, dim3((unsigned)blocks), dim3(256), 0, st, label, N, cnt);
+}
+
+// off[i] = sum of cnt[0..i), off[nl] = total; one workgroup.
+__global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restrict__ cnt, int64_t nl,
+                                                         int64_t *__restrict__ off)
+{
+    __shared__ int64_t part[1024];
+    const int tid = threadIdx.x;
+    const int64_t chunk = (nl + 1023) / 1024;
+    const int64_t b = tid * chunk, e = min(nl, b + chunk);
+    int64_t s = 0;
+    for (int64_t i = b; i < e; ++i) s += cnt[i];
+    part[tid] = s;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        int64_t v = tid >= o ? part[tid - o] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int64_t run = part[tid] - s;
+    for (int64_t i = b; i < e; ++i) {
+        off[i] = run;
+        run += cnt[i];
+    }
+    if (tid == 1023) off[nl] = part[1023];
+}
+void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, cnt, nl, off);
+}
+
+__global__ void k_list_scatter(const int32_t *__restrict__ label, const int32_t *__restrict__ st_ids,
+                               const uint8_t *__restrict__ st_codes, const uint8_t *__restrict__ st_lam,
+                               int64_t N, int m, const int64_t *__restrict__ off,
+                               int32_t *__restrict__ cursor, int32_t *__restrict__ ids,
+                               uint8_t *__restrict__ codes, uint8_t *__restrict__ lam)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride) {
+        const int l = label[i];
+        if (l < 0) continue;
+        const int64_t pos = off[l] + atomicAdd(&cursor[l], 1);
+        ids[pos] = st_ids[i];
+        lam[pos] = st_lam[i];
+        if ((m & 3) == 0) {
+            const uint32_t *s = (const uint32_t *)(st_codes + i * m);
+            uint32_t *d = (uint32_t *)(codes + pos * m);
+            for (int p = 0; p < m / 4; ++p) d[p] = s[p];
+        } else {
+            for (int p = 0; p < m; ++p) codes[pos * m + p] = st_codes[i * m + p];
+        }
+    }
+}
+void launch_list_scatter(const int32_t *label, const int32_t *st_ids, const uint8_t *st_codes,
+                         const uint8_t *st_lam, int64_t N, int m, const int64_t *off, int32_t *cursor,
+                         int32_t *ids, uint8_t *codes, uint8_t *lam, hipStream_t st)
+{
+    if (N <= 0) return;
+    int64_t blocks = (N + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_list_scatter, dim3((unsigned)blocks), dim3(256), 0, st, label, st_ids, st_codes, st_lam,
+                       N, m, off, cursor, ids, codes, lam);
+}
+
+// The scatter places the points of a list in arbitrary order; this pass orders
+// every list by id.  One 64-thread workgroup per list sorts lists of up to
+// SORT_MAX points in LDS; longer unsorted lists are reported to the host.
+#define SORT_MAX 1024
+
+__global__ __launch_bounds__(64) void k_list_sort(const int64_t *__restrict__ off, int64_t nl, int m,
+                                                  int32_t *__restrict__ ids, uint8_t *__restrict__ codes,
+                                                  uint8_t *__restrict__ lam, int32_t *__restrict__ long_lists,
+                                                  int32_t *__restrict__ n_long, int max_long)
+{
+    extern __shared__ unsigned char smem[];
+    uint64_t *keys = (uint64_t *)smem;            // [SORT_MAX]
+    uint8_t *pay = (uint8_t *)(keys + SORT_MAX);  // [SORT_MAX * (m + 1)]
+    __shared__ int unsorted;
+    const int tid = threadIdx.x;
+    const int64_t l = blockIdx.x;
+    const int64_t beg = off[l];
+    const int64_t len = off[l + 1] - beg;
+    if (len <= 1) return;
+    if (tid == 0) unsorted = 0;
+    __syncthreads();
+    for (int64_t i = tid; i + 1 < len; i += 64)
+        if (ids[beg + i] > ids[beg + i + 1]) unsorted = 1;
+    __syncthreads();
+    if (!unsorted) return;
+    if (len > SORT_MAX) {
+        if (tid == 0) {
+            const int p = atomicAdd(n_long, 1);
+            if (p < max_long) long_lists[p] = (int32_t)l;
+        }
+        return;
+    }
+    const int sz = next_pow2_dev((int)len);
+    for (int i = tid; i < sz; i += 64)
+        keys[i] = i < len ? (((uint64_t)(uint32_t)ids[beg + i] << 32) | (uint32_t)i) : KEY_MAX;
+    for (int64_t i = tid; i < len * m; i += 64) pay[i] = codes[beg * m + i];
+    for (int i = tid; i < len; i += 64) pay[len * m + i] = lam[beg + i];
+    __syncthreads();
+    block_bitonic_sort<64>(keys, sz, tid);
+    for (int i = tid; i < len; i += 64) {
+        const uint64_t key = keys[i];
+        const int src = (int)(uint32_t)key;
+        ids[beg + i] = (int32_t)(uint32_t)(key >> 32);
+        lam[beg + i] = pay[len * m + src];
+        for (int p = 0; p < m; ++p) codes[(beg + i) * m + p] = pay[src * m + p];
+    }
+}
+void launch_list_sort(const int64_t *off, int64_t nl, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
+                      int32_t *long_lists, int32_t *n_long, int max_long, hipStream_t st)
+{
+    if (nl <= 0) return;
+    const size_t smem = (size_t)SORT_MAX * 8 + (size_t)SORT_MAX * (m + 1);
+    (void)hipFuncSetAttribute((const void *)k_list_sort, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(k_list_sort, dim3((unsigned)nl), dim3(64), smem, st, off, nl, m, ids, codes, lam, long_lists,
+                       n_long, max_long);
+}
+
+// A list too long for LDS: bitonic sort of (id, position) keys in global memory
+// by a single workgroup, then the payload is permuted through a scratch copy.
+__global__ __launch_bounds__(1024) void k_long_list_sort(int64_t beg, int64_t len, int64_t sz, int m,
+                                                         int32_t *__restrict__ ids, uint8_t *__restrict__ codes,
+                                                         uint8_t *__restrict__ lam, uint64_t *__restrict__ keys,
+                                                         uint8_t *__restrict__ pay)
+{
+    const int tid = threadIdx.x;
+    for (int64_t i = tid; i < sz; i += 1024)
+        keys[i] = i < len ? (((uint64_t)(uint32_t)ids[beg + i] << 32) | (uint32_t)i) : KEY_MAX;
+    for (int64_t i = tid; i < len * m; i += 1024) pay[i] = codes[beg * m + i];
+    for (int64_t i = tid; i < len; i += 1024) pay[len * m + i] = lam[beg + i];
+    __syncthreads();
+    for (int64_t k = 2; k <= sz; k <<= 1)
+        for (int64_t j = k >> 1; j > 0; j >>= 1) {
+            for (int64_t i = tid; i < (sz >> 1); i += 1024) {
+                const int64_t lo = ((i & ~(j - 1)) << 1) | (i & (j - 1)), hi = lo | j;
+                const uint64_t x = keys[lo], y = keys[hi];
+                if ((x > y) == ((lo & k) == 0)) {
+                    keys[lo] = y;
+                    keys[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    for (int64_t i = tid; i < len; i += 1024) {
+        const uint64_t key = keys[i];
+        const int64_t src = (int64_t)(uint32_t)key;
+        ids[beg + i] = (int32_t)(uint32_t)(key >> 32);
+        lam[beg + i] = pay[len * m + src];
+        for (int p = 0; p < m; ++p) codes[(beg + i) * m + p] = pay[src * m + p];
+    }
+}
+void launch_long_list_sort_at(int64_t beg, int64_t len, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
+                              uint64_t *scratch_keys, uint8_t *scratch_payload, hipStream_t st)
+{
+    int64_t sz = 1;
+    while (sz < len) sz <<= 1;
+    hipLaunchKernelGGL(k_long_list_sort, dim3(1), dim3(1024), 0, st, beg, len, sz, m, ids, codes, lam, scratch_keys,
+                       scratch_payload);
+}

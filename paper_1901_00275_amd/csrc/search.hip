@@ -1,0 +1,341 @@
+// Second-level traversal, lookup tables, list scan and K-selection (Alg. 3).
+#include "common.h"
+
+// ---------------------------------------------------------------------------
+// Sub-region scores (Sec. 3.3.1): the query is line-quantised against every edge
+// l(c_i, s_ij) of every probed cell.  With a = ||y-c_i||^2, b = ||y-s_ij||^2 and
+// c = ||s_ij-c_i||^2, Eq. 8 gives the query's own lambda and Eq. 7 evaluated at
+// that lambda collapses to a - c lambda^2.  a and b are direct sums of squared
+// differences.  The w2 smallest by (score, label i*n+j) are kept.
+//
+// Outputs per query: the visited labels in (score, label) order (for callers
+// that want the traversal) and the same set ordered by label, so that the
+// sub-regions of one cell are adjacent, with g = <y-c_i, s_ij-c_i> = (a+c-b)/2
+// for the scan.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q, int D,
+                                                    const float *__restrict__ C,
+                                                    const int32_t *__restrict__ S,
+                                                    const float *__restrict__ E, int n,
+                                                    const int32_t *__restrict__ cells,
+                                                    const float *__restrict__ cell_dist, int w1, int w2,
+                                                    int sz, int32_t *__restrict__ sub,
+                                                    float *__restrict__ sub_score,
+                                                    int32_t *__restrict__ scan_label,
+                                                    float *__restrict__ scan_g)
+{
+    extern __shared__ unsigned char smem[];
+    uint64_t *keys = (uint64_t *)smem;          // [sz]
+    float *bval = (float *)(keys + sz);          // [sz]
+    float *yv = bval + sz;                       // [D]
+    uint16_t *pos = (uint16_t *)(yv + D);        // [sz]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = blockIdx.x;
+    const int total = w1 * n;
+
+    for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)q * D + d];
+    __syncthreads();
+
+    for (int t = wave; t < total; t += 4) {
+        const int e = t / n, j = t - e * n;
+        const int i = cells[(int64_t)q * w1 + e];
+        uint64_t key = KEY_MAX;
+        float b = 0.f;
+        if (i >= 0) {
+            const int s = S[(int64_t)i * n + j];
+            b = wave_sqdist(yv, C + (int64_t)s * D, D, lane);
+            const float a = cell_dist[(int64_t)q * w1 + e];
+            const float c = E[(int64_t)i * n + j];
+            const float lam = c > 0.f ? 0.5f * (a + c - b) / c : 0.f;
+            const float score = a - c * lam * lam;
+            key = make_key(score, (uint32_t)(i * n + j));
+        }
+        if (lane == 0) {
+            keys[t] = key;
+            bval[t] = b;
+            pos[t] = (uint16_t)t;
+        }
+    }
+    for (int t = total + tid; t < sz; t += 256) {
+        keys[t] = KEY_MAX;
+        pos[t] = 0;
+    }
+    __syncthreads();
+    block_bitonic_sort_kv<256>(keys, pos, sz, tid);
+
+    // (score, label) order for the caller; then re-key the visited ones by label
+    uint64_t mine[8]; // w2 <= 2048 = 8 * 256
+    int cnt = 0;
+    for (int r = tid; r < w2; r += 256, ++cnt) {
+        const uint64_t key = keys[r];
+        const bool ok = key != KEY_MAX;
+        const int label = ok ? (int)(uint32_t)key : -1;
+        if (sub) sub[(int64_t)q * w2 + r] = label;
+        if (sub_score) sub_score[(int64_t)q * w2 + r] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+        uint64_t k2 = KEY_MAX;
+        if (ok) {
+            const int p = pos[r];
+            const int e = p / n;
+            const float a = cell_dist[(int64_t)q * w1 + e];
+            const float c = E[label];
+            const float g = 0.5f * (a + c - bval[p]);
+            k2 = ((uint64_t)(uint32_t)label << 32) | __float_as_uint(g);
+        }
+        mine[cnt] = k2;
+    }
+    __syncthreads();
+    const int sz2 = next_pow2_dev(w2);
+    cnt = 0;
+    for (int r = tid; r < w2; r += 256, ++cnt) keys[r] = mine[cnt];
+    for (int r = w2 + tid; r < sz2; r += 256) keys[r] = KEY_MAX;
+    __syncthreads();
+    block_bitonic_sort<256>(keys, sz2, tid);
+    for (int r = tid; r < w2; r += 256) {
+        const uint64_t key = keys[r];
+        const bool ok = key != KEY_MAX;
+        scan_label[(int64_t)q * w2 + r] = ok ? (int32_t)(uint32_t)(key >> 32) : -1;
+        scan_g[(int64_t)q * w2 + r] = ok ? __uint_as_float((uint32_t)key) : 0.f;
+    }
+}
+
+void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
+                       int n, const int32_t *cells, const float *cell_dist, int w1, int w2,
+                       int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
+                       hipStream_t st)
+{
+    if (nq <= 0) return;
+    int sz = next_pow2(w1 * n);
+    if (sz < next_pow2(w2)) sz = next_pow2(w2);
+    if (sz < 2) sz = 2;
+    size_t smem = (size_t)sz * (8 + 4 + 2) + (size_t)D * 4;
+    (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
+                       cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g);
+}
+
+// ---------------------------------------------------------------------------
+// Lookup tables + list scan + K-selection (Sec. 3.3.2 - 3.3.3).
+//
+// For a point x of sub-region (i, j) with code (t_1..t_m) and lambda byte value
+// l, Eq. 14 is || (y - c_i) - l e - q2 ||^2 with e = s_ij - c_i and q2 the
+// concatenation of the codewords.  Expanding around z = y - c_i gives
+//
+//   dist = sum_p A[p][t_p]  +  l * ( 2 sum_p B[p][t_p] - 2 g )  +  l^2 c
+//   A[p][t] = || z^p - P[p][t] ||^2       per (query, cell)
+//   B[p][t] = < e^p , P[p][t] >           per sub-region
+//   g = <z, e>,  c = ||e||^2
+//
+// which is Eq. 16-17 with term2, term3 and term5 folded into A and
+// term4 - term3 into B: 2m lookups per point, as counted in Sec. 3.3.2, but
+// no large cancelling terms.  A and B are interleaved in LDS so that one
+// 64-bit read serves both.
+//
+// A workgroup handles one (query, split) pair: a contiguous range of the
+// query's visited sub-regions in label order.  Candidates below the current
+// K-th key go to an LDS buffer that is merged into the sorted top-K by a
+// bitonic sort whenever it fills.
+// ---------------------------------------------------------------------------
+#define SCAN_NT 256
+#define SCAN_PTS 4 // points per thread between two buffer checks
+
+template <int NT>
+__device__ __forceinline__ void topk_merge(uint64_t *keys, int KP, int SZ, int K, int *cnt_p, uint64_t *thr_p,
+                                           int tid)
+{
+    // keys[0..KP) current result (sorted, padded), keys[KP..KP+cnt) new candidates
+    __syncthreads();
+    const int cnt = *cnt_p;
+    for (int i = KP + cnt + tid; i < SZ; i += NT) keys[i] = KEY_MAX;
+    __syncthreads();
+    block_bitonic_sort<NT>(keys, SZ, tid);
+    for (int i = K + tid; i < KP; i += NT) keys[i] = KEY_MAX;
+    if (tid == 0) {
+        *cnt_p = 0;
+        *thr_p = keys[K - 1];
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(SCAN_NT) void k_scan(ScanArgs a, int KP, int SZ)
+{
+    extern __shared__ unsigned char smem[];
+    const int m = a.m, D = a.D, ds = D / m;
+    uint64_t *keys = (uint64_t *)smem;                 // [SZ]
+    float2 *AB = (float2 *)(keys + SZ);                // [m * 256]
+    float *yv = (float *)(AB + m * 256);               // [D]
+    float *zv = yv + D;                                // [D]
+    float *ev = zv + D;                                // [D]
+    __shared__ int sh_cnt;
+    __shared__ uint64_t sh_thr;
+
+    const int tid = threadIdx.x;
+    const int q = blockIdx.x / a.nsplit, split = blockIdx.x - q * a.nsplit;
+    const int CB = SZ - KP;
+    const int r0 = (int)((int64_t)a.w2 * split / a.nsplit), r1 = (int)((int64_t)a.w2 * (split + 1) / a.nsplit);
+
+    for (int d = tid; d < D; d += SCAN_NT) yv[d] = a.Q[(int64_t)q * D + d];
+    for (int i = tid; i < KP; i += SCAN_NT) keys[i] = KEY_MAX;
+    if (tid == 0) {
+        sh_cnt = 0;
+        sh_thr = KEY_MAX;
+    }
+    __syncthreads();
+
+    int cur_cell = -1;
+    for (int r = r0; r < r1; ++r) {
+        const int label = a.scan_label[(int64_t)q * a.w2 + r];
+        if (label < 0) continue; // uniform over the workgroup
+        const int64_t beg = a.off[label], end = a.off[label + 1];
+        if (beg == end) continue;
+        const int i = label / a.n, j = label - i * a.n;
+        const bool new_cell = i != cur_cell;
+        cur_cell = i;
+        const float *ci = a.C + (int64_t)i * D;
+        const float *sj = a.C + (int64_t)a.S[(int64_t)i * a.n + j] * D;
+        __syncthreads(); // previous list fully scanned before the tables change
+        for (int d = tid; d < D; d += SCAN_NT) {
+            const float c = ci[d];
+            zv[d] = yv[d] - c;
+            ev[d] = sj[d] - c;
+        }
+        __syncthreads();
+        // lookup tables
+        for (int idx = tid; idx < m * 256; idx += SCAN_NT) {
+            const int p = idx >> 8;
+            const float *w = a.P + (int64_t)idx * ds;
+            const float *zp = zv + p * ds, *ep = ev + p * ds;
+            float sb = 0.f;
+            for (int d = 0; d < ds; ++d) sb = fmaf(ep[d], w[d], sb);
+            if (new_cell) {
+                float sa = 0.f;
+                for (int d = 0; d < ds; ++d) {
+                    const float t = zp[d] - w[d];
+                    sa = fmaf(t, t, sa);
+                }
+                AB[idx] = make_float2(sa, sb);
+            } else {
+                AB[idx].y = sb;
+            }
+        }
+        const float cc = a.E[label];
+        const float g = a.scan_g[(int64_t)q * a.w2 + r];
+        __syncthreads();
+
+        // scan the list
+        for (int64_t base = beg; base < end; base += SCAN_NT * SCAN_PTS) {
+            // the fill level is read between two barriers with no appends in between,
+            // so every thread takes the same decision
+            const int fill = sh_cnt;
+            __syncthreads();
+            if (fill > CB - SCAN_NT * SCAN_PTS) topk_merge<SCAN_NT>(keys, KP, SZ, a.K, &sh_cnt, &sh_thr, tid);
+            const uint64_t thr = sh_thr;
+#pragma unroll
+            for (int u = 0; u < SCAN_PTS; ++u) {
+                const int64_t t = base + u * SCAN_NT + tid;
+                if (t < end) {
+                    const uint8_t *code = a.codes + t * m;
+                    float sa = 0.f, sb = 0.f;
+                    if ((m & 3) == 0) {
+                        const uint32_t *cw = (const uint32_t *)code;
+                        for (int p4 = 0; p4 < m; p4 += 4) {
+                            const uint32_t wv = cw[p4 >> 2];
+#pragma unroll
+                            for (int b = 0; b < 4; ++b) {
+                                const float2 ab = AB[(p4 + b) * 256 + ((wv >> (8 * b)) & 255u)];
+                                sa += ab.x;
+                                sb += ab.y;
+                            }
+                        }
+                    } else {
+                        for (int p = 0; p < m; ++p) {
+                            const float2 ab = AB[p * 256 + code[p]];
+                            sa += ab.x;
+                            sb += ab.y;
+                        }
+                    }
+                    const float l = ((float)a.lam[t] - a.lam_zero) * a.lam_step;
+                    const float dist = fmaf(l, fmaf(l, cc, 2.f * (sb - g)), sa);
+                    const uint64_t key = make_key(dist, (uint32_t)a.ids[t]);
+                    if (key < thr) {
+                        const int pos = atomicAdd(&sh_cnt, 1);
+                        keys[KP + pos] = key;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    topk_merge<SCAN_NT>(keys, KP, SZ, a.K, &sh_cnt, &sh_thr, tid);
+    if (a.nsplit > 1) {
+        uint64_t *dst = a.partial + ((int64_t)q * a.nsplit + split) * a.K;
+        for (int i = tid; i < a.K; i += SCAN_NT) dst[i] = keys[i];
+    } else {
+        for (int i = tid; i < a.K; i += SCAN_NT) {
+            const uint64_t key = keys[i];
+            const bool ok = key != KEY_MAX;
+            a.out_dist[(int64_t)q * a.K + i] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+            a.out_ids[(int64_t)q * a.K + i] = ok ? (int32_t)(uint32_t)key : -1;
+        }
+    }
+}
+
+static void scan_sizes(int K, int *KP, int *SZ)
+{
+    *KP = next_pow2(K);
+    int sz = 2 * *KP;
+    if (sz < 2048) sz = 2048;
+    *SZ = sz;
+}
+
+int scan_pick_nsplit(int nq, int w2, int K)
+{
+    // aim at >= 4 workgroups per compute unit (256 CUs); never more splits than lists
+    int ns = (1024 + nq - 1) / nq;
+    if (ns > w2) ns = w2;
+    const int kp = next_pow2(K);
+    const int cap = 8192 / kp; // merge sorts nsplit * KP keys in LDS
+    if (ns > cap) ns = cap;
+    if (ns > 16) ns = 16;
+    if (ns < 1) ns = 1;
+    return ns;
+}
+
+void launch_scan(const ScanArgs &a, hipStream_t st)
+{
+    if (a.nq <= 0) return;
+    int KP, SZ;
+    scan_sizes(a.K, &KP, &SZ);
+    size_t smem = (size_t)SZ * 8 + (size_t)a.m * 256 * 8 + (size_t)a.D * 4 * 3;
+    (void)hipFuncSetAttribute((const void *)k_scan, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(k_scan, dim3((unsigned)(a.nq * a.nsplit)), dim3(SCAN_NT), smem, st, a, KP, SZ);
+}
+
+// Merge of the per-split partial results of one query (second pass of the
+// two-pass K-selection of Sec. 4).
+__global__ __launch_bounds__(256) void k_merge(const uint64_t *__restrict__ partial, int nsplit, int K, int sz,
+                                               float *__restrict__ out_dist, int32_t *__restrict__ out_ids)
+{
+    extern __shared__ unsigned char smem[];
+    uint64_t *keys = (uint64_t *)smem;
+    const int tid = threadIdx.x, q = blockIdx.x;
+    const int total = nsplit * K;
+    for (int i = tid; i < sz; i += 256) keys[i] = i < total ? partial[(int64_t)q * total + i] : KEY_MAX;
+    __syncthreads();
+    block_bitonic_sort<256>(keys, sz, tid);
+    for (int i = tid; i < K; i += 256) {
+        const uint64_t key = keys[i];
+        const bool ok = key != KEY_MAX;
+        out_dist[(int64_t)q * K + i] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+        out_ids[(int64_t)q * K + i] = ok ? (int32_t)(uint32_t)key : -1;
+    }
+}
+
+void launch_merge(const uint64_t *partial, int nq, int nsplit, int K, float *out_dist, int32_t *out_ids,
+                  hipStream_t st)
+{
+    if (nq <= 0) return;
+    const int sz = next_pow2(nsplit * K);
+    size_t smem = (size_t)sz * 8;
+    (void)hipFuncSetAttribute((const void *)k_merge, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(k_merge, dim3((unsigned)nq), dim3(256), smem, st, partial, nsplit, K, sz, out_dist, out_ids);
+}
