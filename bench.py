@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the VLQ-ADC query path on one MI355X.
+
+A step is one vlq_search call (all of Alg. 3: coarse distances, cell and
+sub-region selection, lookup tables, list scan, K-selection) over the whole
+query batch of the configuration, with queries and index resident in HBM.
+Prints one JSON line: queries/s at the stated recall, the roofline figures of
+the dominant kernel (the list scan) from HIP events on the search stream, and
+the CPU oracle's timing on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def scan_bytes(vlq, wl, w1, w2, torch):
+    """Algorithmic bytes of the list scan for one batch: every point of every
+    visited list once (m code bytes + 1 lambda byte + 4 id bytes) plus the two
+    list offsets per visited list."""
+    cfg = wl.cfg
+    nq = wl.Y.shape[0]
+    dev = wl.Y.device
+    od = torch.empty(nq, cfg.K, device=dev)
+    oi = torch.empty(nq, cfg.K, dtype=torch.int32, device=dev)
+    sub = torch.empty(nq, w2, dtype=torch.int32, device=dev)
+    vlq.vlq_search_debug(wl.idx, wl.Y, nq, w1, w2, cfg.K, od, oi, None, None, sub, None)
+    off = torch.empty(cfg.k * cfg.n + 1, dtype=torch.int64, device=dev)
+    vlq.vlq_index_get_lists(wl.idx, off, None, None, None)
+    torch.cuda.synchronize()
+    s = sub.long().clamp_min(0)
+    lens = (off[s + 1] - off[s]) * (sub >= 0)
+    points = int(lens.sum())
+    visited = int((sub >= 0).sum())
+    return points * (cfg.m + 5) + visited * 8, points, oi
+
+
+def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
+    """The oracle's search (as it stands) on the host cores, on a sample of the
+    batch's queries, against the same index (copied out of the library for this
+    timing leg only; nothing is compared against it for parity)."""
+    import numpy as np
+
+    import oracle
+
+    cfg = wl.cfg
+    dev = wl.Y.device
+    N = vlq.vlq_index_ntotal(wl.idx)
+    off = torch.empty(cfg.k * cfg.n + 1, dtype=torch.int64, device=dev)
+    ids = torch.empty(N, dtype=torch.int32, device=dev)
+    codes = torch.empty(N, cfg.m, dtype=torch.uint8, device=dev)
+    lam = torch.empty(N, dtype=torch.uint8, device=dev)
+    vlq.vlq_index_get_lists(wl.idx, off, ids, codes, lam)
+    torch.cuda.synchronize()
+    lists = oracle.Lists(off.cpu().numpy(), ids.cpu().numpy(), codes.cpu().numpy(), lam.cpu().numpy())
+    del ids, codes, lam
+    Cb, P, Y = wl.C.cpu().numpy(), wl.P.cpu().numpy(), wl.Y.cpu().numpy()
+
+    def run(Yq):
+        t0 = time.time()
+        dist = oracle.coarse(Cb, Yq)
+        cells = oracle.select_smallest(dist, w1)
+        t1 = time.time()
+        S, E = oracle.sparse_graph(Cb, cfg.n, cells.ravel())  # index data, not query work: untimed
+        t2 = time.time()
+        score, label = oracle.subregion_scores(dist, S, E, cells)
+        sub = oracle.select_smallest(score, w2, key=label)
+        out_d, out_i, _ = oracle.scan(Cb, S, P, lists, Yq, sub, cfg.K)
+        t3 = time.time()
+        return (t1 - t0) + (t3 - t2), out_i
+
+    nprobe = min(32, len(Y))
+    t, _ = run(Y[:nprobe])
+    ns = int(min(len(Y), max(nprobe, target_s / max(t / nprobe, 1e-9))))
+    if cfg.k > 20000:  # the oracle's graph rows for the probed cells cost k*D each: keep that bounded
+        ns = min(ns, 256)
+    t, out_i = run(Y[:ns])
+    return {"value": ns / t, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {ns} of the {len(Y)} queries, full index, same w1/w2/K; {t:.1f} s of oracle search"}, out_i, ns
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="mid_sift")
+    ap.add_argument("--w1", type=int, default=0, help="probed cells (default: the configuration's operating point)")
+    ap.add_argument("--points", type=int, default=0, help="build only the first POINTS vectors (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also time the other w1 values of the configuration")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1")
+        sys.exit(2)
+
+    import torch
+
+    import datagen
+    import paper_1901_00275_amd as vlq
+    from datagen import workloads
+
+    vlq.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = workloads.CONFIGS[args.config]
+    wl = workloads.materialise(vlq, cfg, "cuda:0", n_points=args.points or None, log=log)
+    nq, K = cfg.nq, cfg.K
+    dev = wl.Y.device
+    od = torch.empty(nq, K, device=dev)
+    oi = torch.empty(nq, K, dtype=torch.int32, device=dev)
+
+    def timed(w1, steps, warmup):
+        w2 = cfg.w2(w1)
+        for _ in range(warmup):
+            vlq.vlq_search(wl.idx, wl.Y, nq, w1, w2, K, od, oi)
+        torch.cuda.synchronize()
+        vlq.vlq_profile_read(wl.idx)
+        vlq.vlq_profile_enable(wl.idx, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            vlq.vlq_search(wl.idx, wl.Y, nq, w1, w2, K, od, oi)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        vlq.vlq_profile_enable(wl.idx, False)
+        prof = vlq.vlq_profile_read(wl.idx)
+        rec = {f"R@{r}": datagen.recall_at(oi, wl.gt, r) for r in (1, 10, 100)}
+        return dt, prof, rec, w2
+
+    w1 = args.w1 or cfg.w1[-1]
+    dt, prof, rec, w2 = timed(w1, args.steps, args.warmup)
+    nbytes, points, oi_dbg = scan_bytes(vlq, wl, w1, w2, torch)
+    scan_ms, scan_launches = prof["scan"]
+    scan_avg_s = scan_ms / 1e3 / max(scan_launches, 1)
+    achieved = nbytes / scan_avg_s / 1e9
+    stage_ms = {s: round(v[0] / args.steps, 4) for s, v in prof.items()}
+    result = {
+        "metric": "queries/sec at Recall@10 (VLQ-ADC search, 1 GPU); ADC-scan HBM GB/s vs peak",
+        "value": nq * args.steps / dt,
+        "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "N": vlq.vlq_index_ntotal(wl.idx), "D": cfg.D, "centroids": cfg.k,
+                   "edges": cfg.n, "code_bytes": cfg.m, "queries": nq, "w1": w1, "w2": w2, "K": K,
+                   "recall": rec, "points_scanned_per_query": points / nq,
+                   "stage_ms_per_step": stage_ms, "build_s": wl.timings},
+        "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": scan_avg_s * 1e3},
+    }
+    if args.sweep:
+        sweep = []
+        for w in cfg.w1:
+            d2, p2, r2, w22 = timed(w, max(2, args.steps // 2), 1)
+            sweep.append({"w1": w, "w2": w22, "queries_per_s": nq * max(2, args.steps // 2) / d2, **r2})
+        result["config"]["sweep"] = sweep
+    if not args.no_cpu_baseline:
+        base, o_ids, ns = cpu_baseline(vlq, wl, w1, w2, torch)
+        result["cpu_baseline"] = base
+        agree = float((oi_dbg[:ns].cpu().numpy() == o_ids).mean())
+        result["config"]["oracle_id_agreement_on_sample"] = agree
+    print(json.dumps(result), flush=True)
+    vlq.vlq_index_free(wl.idx)
+
+
+if __name__ == "__main__":
+    main()

@@ -12,7 +12,9 @@ import torch
 from . import MASTER_SEED, STREAM_KMEANS, _gen
 
 
-def _assign(X, Cb, chunk=1 << 16):
+def _assign(X, Cb, chunk=None):
+    if chunk is None:
+        chunk = max(1024, (1 << 28) // Cb.shape[0])
     cn = (Cb * Cb).sum(1)
     out = torch.empty(X.shape[0], dtype=torch.int64, device=X.device)
     for s in range(0, X.shape[0], chunk):

@@ -173,6 +173,8 @@ struct ScanArgs {
     int32_t *out_ids;
 };
 void launch_scan(const ScanArgs &a, hipStream_t st);
+bool scan_mfma_supported(const ScanArgs &a);
+void launch_scan_mfma(const ScanArgs &a, hipStream_t st);
 void launch_merge(const uint64_t *partial, int nq, int nsplit, int K, float *out_dist, int32_t *out_ids,
                   hipStream_t st);
 int scan_pick_nsplit(int nq, int w2, int K);

@@ -1,4 +1,6 @@
 // Second-level traversal, lookup tables, list scan and K-selection (Alg. 3).
+#include <stdlib.h>
+
 #include "common.h"
 
 // ---------------------------------------------------------------------------
@@ -303,6 +305,12 @@ int scan_pick_nsplit(int nq, int w2, int K)
 void launch_scan(const ScanArgs &a, hipStream_t st)
 {
     if (a.nq <= 0) return;
+    // VLQ_SCAN_GENERIC=1 forces the generic kernel (used by the tests to cover both paths)
+    static const bool force_generic = getenv("VLQ_SCAN_GENERIC") && atoi(getenv("VLQ_SCAN_GENERIC")) != 0;
+    if (!force_generic && scan_mfma_supported(a)) {
+        launch_scan_mfma(a, st);
+        return;
+    }
     int KP, SZ;
     scan_sizes(a.K, &KP, &SZ);
     size_t smem = (size_t)SZ * 8 + (size_t)a.m * 256 * 8 + (size_t)a.D * 4 * 3;
