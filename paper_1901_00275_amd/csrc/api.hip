@@ -60,6 +60,7 @@ struct vlq_index {
     int64_t *off = nullptr;
     int32_t *ids = nullptr;
     uint8_t *codes = nullptr, *lam = nullptr;
+    float *sx = nullptr; // query-independent part of the distance, per stored point
     // scratch
     void *ws = nullptr;
     size_t ws_bytes = 0;
@@ -124,7 +125,7 @@ extern "C" void vlq_index_free(vlq_index_t *idx)
     if (!idx) return;
     (void)hipDeviceSynchronize();
     void *ptrs[] = {idx->C, idx->cn, idx->P, idx->E, idx->S, idx->st_label, idx->st_ids, idx->st_lam,
-                    idx->st_codes, idx->off, idx->ids, idx->codes, idx->lam, idx->ws};
+                    idx->st_codes, idx->off, idx->ids, idx->codes, idx->lam, idx->sx, idx->ws};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (auto &r : idx->recs) {
@@ -440,16 +441,18 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
     const int64_t N = idx->ntotal;
     if (N > idx->lists_cap) {
         HIPCHK(hipDeviceSynchronize());
-        void *old[] = {idx->ids, idx->codes, idx->lam};
+        void *old[] = {idx->ids, idx->codes, idx->lam, idx->sx};
         for (void *p : old)
             if (p) HIPCHK(hipFree(p));
         idx->ids = nullptr;
         idx->codes = nullptr;
         idx->lam = nullptr;
+        idx->sx = nullptr;
         idx->lists_cap = 0;
         HIPCHK(hipMalloc(&idx->ids, (size_t)N * 4));
         HIPCHK(hipMalloc(&idx->codes, (size_t)N * m + 16));
         HIPCHK(hipMalloc(&idx->lam, (size_t)N + 16));
+        HIPCHK(hipMalloc(&idx->sx, (size_t)N * 4 + 16));
         idx->lists_cap = N;
     }
     Bump plan(nullptr);
@@ -501,6 +504,11 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
         }
         if (hn <= MAX_LONG) break;
     }
+    if (N > 0) {
+        launch_list_static(idx->off, nl, idx->p.n_edges, idx->p.d, m, idx->C, idx->S, idx->E, idx->P, idx->codes,
+                           idx->lam, idx->lam_step, idx->lam_zero, idx->sx, st);
+        LAUNCHCHK();
+    }
     HIPCHK(hipStreamSynchronize(st));
     idx->finalized = true;
     return VLQ_OK;
@@ -532,8 +540,10 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     if (TQ > nq) TQ = nq;
     const int nsplit = scan_pick_nsplit(nq, w2, K);
 
+    uint4 *desc;
     auto carve = [&](Bump &b, float **qn, float **dist, int32_t **cells, float **cell_dist, int32_t **slab,
                      float **sg, uint64_t **partial) {
+        desc = b.take<uint4>((size_t)nq * w2);
         *qn = b.take<float>((size_t)nq);
         *dist = b.take<float>((size_t)TQ * k);
         *cells = b.take<int32_t>((size_t)nq * w1);
@@ -571,7 +581,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     {
         StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS);
         launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, cells, cell_dist, w1, w2, d_sub, d_sub_score, slab,
-                          sg, st);
+                          sg, idx->off, desc, st);
     }
     LAUNCHCHK();
     ScanArgs a;
@@ -591,6 +601,8 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     a.ids = idx->ids;
     a.codes = idx->codes;
     a.lam = idx->lam;
+    a.sx = idx->sx;
+    a.desc = desc;
     a.lam_step = idx->lam_step;
     a.lam_zero = idx->lam_zero;
     a.scan_label = slab;

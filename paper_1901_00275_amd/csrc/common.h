@@ -149,10 +149,11 @@ void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const f
                          int32_t *cells, float *cell_dist, hipStream_t st);
 
 // Line scores of the w1*n sub-regions of the probed cells and the w2 best of them.
+// desc (optional): per visited sub-region {list begin, list length, a, b - a} for the streaming scan.
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
                        int n, const int32_t *cells, const float *cell_dist, int w1, int w2,
                        int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       hipStream_t st);
+                       const int64_t *off, uint4 *desc, hipStream_t st);
 
 struct ScanArgs {
     const float *Q;
@@ -165,7 +166,9 @@ struct ScanArgs {
     const int32_t *ids;
     const uint8_t *codes;
     const uint8_t *lam;
+    const float *sx;   // per point: query-independent part of the distance (streaming scan)
     float lam_step, lam_zero;
+    const uint4 *desc; // [nq x w2] {begin, length, a, b - a} per visited sub-region (streaming scan)
     const int32_t *scan_label;
     const float *scan_g;
     uint64_t *partial; // [nq x nsplit x K] when nsplit > 1
@@ -173,8 +176,8 @@ struct ScanArgs {
     int32_t *out_ids;
 };
 void launch_scan(const ScanArgs &a, hipStream_t st);
-bool scan_mfma_supported(const ScanArgs &a);
-void launch_scan_mfma(const ScanArgs &a, hipStream_t st);
+bool scan_stream_supported(const ScanArgs &a);
+void launch_scan_stream(const ScanArgs &a, hipStream_t st);
 void launch_merge(const uint64_t *partial, int nq, int nsplit, int K, float *out_dist, int32_t *out_ids,
                   hipStream_t st);
 int scan_pick_nsplit(int nq, int w2, int K);
@@ -204,6 +207,10 @@ void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStre
 void launch_list_scatter(const int32_t *label, const int32_t *st_ids, const uint8_t *st_codes,
                          const uint8_t *st_lam, int64_t N, int m, const int64_t *off, int32_t *cursor,
                          int32_t *ids, uint8_t *codes, uint8_t *lam, hipStream_t st);
+// s_x of every stored point (see scan_stream.hip)
+void launch_list_static(const int64_t *off, int64_t nl, int n, int D, int m, const float *C, const int32_t *S,
+                        const float *E, const float *P, const uint8_t *codes, const uint8_t *lam, float lam_step,
+                        float lam_zero, float *sx, hipStream_t st);
 void launch_list_sort(const int64_t *off, int64_t nl, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
                       int32_t *long_lists, int32_t *n_long, int max_long, hipStream_t st);
 void launch_long_list_sort_at(int64_t beg, int64_t len, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,

@@ -1,0 +1,244 @@
+// Streaming list scan with fused K-selection (Sec. 3.3.2 - 3.3.3): the fast path.
+//
+// Eq. 15 splits the ADC distance ||y - q1 - q2||^2 (Eq. 14) into
+//     ||y - q1||^2  +  ||q2||^2 + 2 <q1, q2>  -  2 <y, q2>
+// and Eq. 17 writes the first part with the coarse distances a = ||y - c_i||^2,
+// b = ||y - s_ij||^2 and the edge length c:  (1-l) a + l b + (l^2 - l) c.
+// Everything that does not depend on the query,
+//     s_x = ||q2||^2 + 2 <q1, q2> + (l^2 - l) c          (term2 + term3/4 + the term7 part),
+// is summed once per point when the lists are built and streamed with the code,
+// so that a query needs ONE lookup table for the whole scan,
+//     T[p][t] = 2 <y^p, P[p][t]>                           (term5, 256 D multiply-adds),
+// and per point m table reads:
+//     dist = s_x + a + l (b - a) - sum_p T[p][t_p].
+// a and b come from the traversal kernels (term6 / term8 are by-products of the
+// region traversal), so the scan itself touches no centroid.
+//
+// Streams per point: m code bytes, 1 lambda byte, 4 bytes s_x.  Vector ids are
+// not streamed: candidates are tracked by their position in the list arrays and
+// ids are looked up for the K survivors only (the paper keeps ids off the scan
+// path in the same way, Sec. 4).
+//
+// Work layout: one workgroup of 512 threads (8 waves) per (query, split).  The
+// table lives in LDS.  Waves take whole lists from a shared counter; a wave
+// issues all loads of up to 8 chunks of 64 points before it consumes the first,
+// and enough waves are resident per compute unit to cover the memory latency.
+// K-selection: every wave keeps its own sorted K-best list and a candidate
+// buffer in LDS and merges them alone; the waves share one monotonically
+// decreasing upper bound of the K-th best key; the eight lists are merged once
+// at the end, ids are resolved and the result is ordered by (distance, id).
+#include "common.h"
+
+#define SS_NT 512
+#define SS_NW 8
+#define SS_CH 8      // chunks of 64 points loaded ahead per wave
+#define SS_KP 128    // per-wave sorted list (K <= 128)
+#define SS_WSZ 256   // per-wave keys: list + candidate buffer
+
+typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+
+// wave-private bitonic sort of SS_WSZ keys in LDS (LDS operations of one wave
+// complete in issue order, so no workgroup barrier is needed)
+__device__ __forceinline__ void wave_sort256(volatile lds_u64 *wk, int lane)
+{
+    for (int k = 2; k <= SS_WSZ; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int h = 0; h < SS_WSZ / 128; ++h) {
+                const int i = lane + 64 * h;
+                const int l = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                const int r = l | j;
+                const uint64_t x = wk[l], y = wk[r];
+                if ((x > y) == ((l & k) == 0)) {
+                    wk[l] = y;
+                    wk[r] = x;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+}
+
+template <int M>
+__global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint4 *__restrict__ desc)
+{
+    extern __shared__ unsigned char smem[];
+    uint64_t *keys = (uint64_t *)smem;                 // [NW][WSZ]
+    float *T = (float *)(keys + SS_NW * SS_WSZ);       // [M][256]
+    float *yv = T + M * 256;                           // [D]
+    __shared__ unsigned long long sh_thr;              // upper bound of the K-th smallest key of the workgroup
+    __shared__ unsigned long long sh_q[SS_NW];         // every wave's ceil(K/8)-th key
+    __shared__ int sh_next;                            // next list to hand out
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = blockIdx.x / a.nsplit, split = blockIdx.x - q * a.nsplit;
+    const int r0 = (int)((int64_t)a.w2 * split / a.nsplit), r1 = (int)((int64_t)a.w2 * (split + 1) / a.nsplit);
+    const int K = a.K, D = a.D, ds = D / M;
+    const int KQ = (K + SS_NW - 1) / SS_NW;
+    volatile lds_u64 *wk = (volatile lds_u64 *)(keys + wave * SS_WSZ);
+    int wcnt = 0;
+
+    for (int d = tid; d < D; d += SS_NT) yv[d] = a.Q[(int64_t)q * D + d];
+    for (int i = lane; i < SS_WSZ; i += 64) wk[i] = KEY_MAX;
+    if (tid == 0) {
+        sh_thr = KEY_MAX;
+        sh_next = r0;
+    }
+    if (tid < SS_NW) sh_q[tid] = KEY_MAX;
+    __syncthreads();
+    // the query's table: T[p][t] = 2 <y^p, P[p][t]>
+    for (int idx = tid; idx < M * 256; idx += SS_NT) {
+        const float *w = a.P + (int64_t)idx * ds;
+        const float *yp = yv + (idx >> 8) * ds;
+        float s = 0.f;
+        for (int d = 0; d < ds; ++d) s = fmaf(yp[d], w[d], s);
+        T[idx] = 2.f * s;
+    }
+    __syncthreads();
+
+    // Merge of this wave's candidates into its sorted list.  Publishes two upper bounds of
+    // the K-th smallest key of the whole workgroup: the wave's own K-th key, and the largest
+    // of all waves' ceil(K/8)-th keys (8 * ceil(K/8) >= K keys lie at or below it).
+    auto merge_wave = [&]() {
+        for (int i = SS_KP + wcnt + lane; i < SS_WSZ; i += 64) wk[i] = KEY_MAX;
+        __builtin_amdgcn_wave_barrier();
+        wave_sort256(wk, lane);
+        for (int i = K + lane; i < SS_KP; i += 64) wk[i] = KEY_MAX;
+        __builtin_amdgcn_wave_barrier();
+        wcnt = 0;
+        if (lane == 0) sh_q[wave] = wk[KQ - 1];
+        __builtin_amdgcn_wave_barrier();
+        uint64_t bound = 0;
+#pragma unroll
+        for (int w = 0; w < SS_NW; ++w) {
+            const uint64_t t = ((volatile lds_u64 *)sh_q)[w];
+            bound = t > bound ? t : bound;
+        }
+        const uint64_t own = wk[K - 1];
+        bound = own < bound ? own : bound;
+        if (lane == 0 && bound != KEY_MAX) atomicMin(&sh_thr, (unsigned long long)bound);
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    uint64_t thr = KEY_MAX;
+    for (;;) {
+        int s = 0;
+        if (lane == 0) s = atomicAdd(&sh_next, 1);
+        s = __builtin_amdgcn_readfirstlane(s);
+        if (s >= r1) break;
+        const uint4 dsc = desc[(int64_t)q * a.w2 + s]; // uniform address: scalar load
+        const uint32_t beg = dsc.x;
+        const int len = (int)dsc.y;
+        const float av = __uint_as_float(dsc.z), bav = __uint_as_float(dsc.w);
+        if (len <= 0) continue;
+        const uint32_t *codes = (const uint32_t *)(a.codes + (int64_t)beg * M);
+        const uint8_t *lam = a.lam + beg;
+        const float *sx = a.sx + beg;
+        thr = sh_thr;
+        for (int base = 0; base < len; base += 64 * SS_CH) {
+            // ---- all loads of up to SS_CH chunks ----
+            uint32_t cw[SS_CH][M / 4];
+            uint32_t lb[SS_CH];
+            float sv[SS_CH];
+#pragma unroll
+            for (int u = 0; u < SS_CH; ++u) {
+                if (base + 64 * u < len) { // uniform over the wave
+                    int within = base + 64 * u + lane;
+                    within = within < len ? within : len - 1; // stay inside the list
+                    const uint32_t *cp = codes + (int64_t)within * (M / 4);
+#pragma unroll
+                    for (int x = 0; x < M / 4; ++x) cw[u][x] = cp[x];
+                    lb[u] = lam[within];
+                    sv[u] = sx[within];
+                }
+            }
+            // ---- score ----
+#pragma unroll
+            for (int u = 0; u < SS_CH; ++u) {
+                if (base + 64 * u < len) {
+                    const int within = base + 64 * u + lane;
+                    const bool live = within < len;
+                    float t[M];
+#pragma unroll
+                    for (int x = 0; x < M / 4; ++x)
+#pragma unroll
+                        for (int bb = 0; bb < 4; ++bb)
+                            t[x * 4 + bb] = T[(x * 4 + bb) * 256 + ((cw[u][x] >> (8 * bb)) & 255u)];
+                    float ts = 0.f;
+#pragma unroll
+                    for (int x = 0; x < M; ++x) ts += t[x];
+                    const float l = ((float)lb[u] - a.lam_zero) * a.lam_step;
+                    const float dist = (sv[u] - ts) + fmaf(l, bav, av);
+                    const uint64_t key = make_key(dist, beg + (uint32_t)within);
+                    bool pass = live && key < thr;
+                    uint64_t mask = __ballot(pass);
+                    if (mask) {
+                        int np = __popcll(mask);
+                        if (wcnt + np > SS_WSZ - SS_KP) {
+                            merge_wave();
+                            thr = sh_thr;
+                            pass = pass && key < thr;
+                            mask = __ballot(pass);
+                            np = __popcll(mask);
+                        }
+                        if (pass) wk[SS_KP + wcnt + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+                        wcnt += np;
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- merge the eight wave lists; resolve ids; order by (distance, id) ----
+    merge_wave();
+    for (int i = SS_KP + lane; i < SS_WSZ; i += 64) wk[i] = KEY_MAX;
+    __syncthreads();
+    block_bitonic_sort<SS_NT>(keys, SS_NW * SS_WSZ, tid);
+    const int KP = next_pow2_dev(K);
+    uint64_t mine = KEY_MAX;
+    if (tid < K) {
+        const uint64_t key = keys[tid];
+        if (key != KEY_MAX) mine = (key & 0xFFFFFFFF00000000ull) | (uint32_t)a.ids[(uint32_t)key];
+    }
+    __syncthreads();
+    if (tid < KP) keys[tid] = mine;
+    __syncthreads();
+    block_bitonic_sort<SS_NT>(keys, KP, tid);
+    if (a.nsplit > 1) {
+        uint64_t *dst = a.partial + ((int64_t)q * a.nsplit + split) * K;
+        for (int i = tid; i < K; i += SS_NT) dst[i] = keys[i];
+    } else {
+        for (int i = tid; i < K; i += SS_NT) {
+            const uint64_t key = keys[i];
+            const bool ok = key != KEY_MAX;
+            a.out_dist[(int64_t)q * K + i] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+            a.out_ids[(int64_t)q * K + i] = ok ? (int32_t)(uint32_t)key : -1;
+        }
+    }
+}
+
+static size_t scan_stream_smem(int M, int D)
+{
+    return (size_t)SS_NW * SS_WSZ * 8 + (size_t)M * 256 * 4 + (size_t)D * 4;
+}
+
+// Shapes served by this kernel; everything else takes the generic kernel.
+bool scan_stream_supported(const ScanArgs &a)
+{
+    return (a.m == 8 || a.m == 16) && a.K <= SS_KP && a.sx != nullptr && a.desc != nullptr &&
+           (((uintptr_t)a.codes) % 16 == 0);
+}
+
+void launch_scan_stream(const ScanArgs &a, hipStream_t st)
+{
+    if (a.nq <= 0) return;
+    const size_t smem = scan_stream_smem(a.m, a.D);
+    const dim3 grid((unsigned)(a.nq * a.nsplit));
+    if (a.m == 8) {
+        (void)hipFuncSetAttribute((const void *)k_scan_stream<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipLaunchKernelGGL((k_scan_stream<8>), grid, dim3(SS_NT), smem, st, a, (const uint4 *)a.desc);
+    } else {
+        (void)hipFuncSetAttribute((const void *)k_scan_stream<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipLaunchKernelGGL((k_scan_stream<16>), grid, dim3(SS_NT), smem, st, a, (const uint4 *)a.desc);
+    }
+}

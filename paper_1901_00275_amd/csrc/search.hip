@@ -24,7 +24,9 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                                                     int sz, int32_t *__restrict__ sub,
                                                     float *__restrict__ sub_score,
                                                     int32_t *__restrict__ scan_label,
-                                                    float *__restrict__ scan_g)
+                                                    float *__restrict__ scan_g,
+                                                    const int64_t *__restrict__ off,
+                                                    uint4 *__restrict__ desc)
 {
     extern __shared__ unsigned char smem[];
     uint64_t *keys = (uint64_t *)smem;          // [sz]
@@ -75,6 +77,7 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
         if (sub) sub[(int64_t)q * w2 + r] = label;
         if (sub_score) sub_score[(int64_t)q * w2 + r] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
         uint64_t k2 = KEY_MAX;
+        uint4 dsc = make_uint4(0u, 0u, 0u, 0u);
         if (ok) {
             const int p = pos[r];
             const int e = p / n;
@@ -82,7 +85,12 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
             const float c = E[label];
             const float g = 0.5f * (a + c - bval[p]);
             k2 = ((uint64_t)(uint32_t)label << 32) | __float_as_uint(g);
+            if (desc) {
+                const int64_t b0 = off[label], b1 = off[label + 1];
+                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(bval[p] - a));
+            }
         }
+        if (desc) desc[(int64_t)q * w2 + r] = dsc;
         mine[cnt] = k2;
     }
     __syncthreads();
@@ -103,7 +111,7 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
                        int n, const int32_t *cells, const float *cell_dist, int w1, int w2,
                        int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       hipStream_t st)
+                       const int64_t *off, uint4 *desc, hipStream_t st)
 {
     if (nq <= 0) return;
     int sz = next_pow2(w1 * n);
@@ -112,7 +120,7 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
     size_t smem = (size_t)sz * (8 + 4 + 2) + (size_t)D * 4;
     (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
-                       cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g);
+                       cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g, off, desc);
 }
 
 // ---------------------------------------------------------------------------
@@ -307,8 +315,8 @@ void launch_scan(const ScanArgs &a, hipStream_t st)
     if (a.nq <= 0) return;
     // VLQ_SCAN_GENERIC=1 forces the generic kernel (used by the tests to cover both paths)
     static const bool force_generic = getenv("VLQ_SCAN_GENERIC") && atoi(getenv("VLQ_SCAN_GENERIC")) != 0;
-    if (!force_generic && scan_mfma_supported(a)) {
-        launch_scan_mfma(a, st);
+    if (!force_generic && scan_stream_supported(a)) {
+        launch_scan_stream(a, st);
         return;
     }
     int KP, SZ;
