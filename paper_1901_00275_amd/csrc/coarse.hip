@@ -416,11 +416,284 @@ __global__ __launch_bounds__(256) void k_select_cells(const float *__restrict__ 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Register-resident variant for k <= 65536: one workgroup of 1024 threads holds
+// the whole row in registers (one pass over memory) and narrows a value range
+// [lo, hi] around the w-th smallest entry with 1024-bin linear histograms until
+// at most SEL_CAP entries are selected.  Entries are tracked by two bit masks per
+// thread (selected / undecided).  Exact ties at the cut go to the smaller index.
+// The selected entries are then ordered by (GEMM-form distance, index); those
+// within the rounding band of the w-th get direct distances and the final order.
+// ---------------------------------------------------------------------------
+#define SEL2_NT 1024
+#define SEL2_NB 1024
+
+__device__ __forceinline__ int wave_incl_scan_int(int v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// inclusive scan over the 1024 threads of the block; *total receives the block sum
+__device__ __forceinline__ int block_incl_scan_int(int v, int tid, int *sh16, int *total)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int inc = wave_incl_scan_int(v, lane);
+    __syncthreads();
+    if (lane == 63) sh16[wave] = inc;
+    __syncthreads();
+    int before = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < SEL2_NT / 64; ++w) {
+        const int t = sh16[w];
+        before += w < wave ? t : 0;
+        tot += t;
+    }
+    *total = tot;
+    return inc + before;
+}
+
+__device__ __forceinline__ void block_minmax(float mn, float mx, int tid, float *shf, float *omn, float *omx)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    }
+    __syncthreads();
+    if (lane == 0) {
+        shf[wave] = mn;
+        shf[16 + wave] = mx;
+    }
+    __syncthreads();
+    float a = shf[0], b = shf[16];
+#pragma unroll
+    for (int w = 1; w < SEL2_NT / 64; ++w) {
+        a = fminf(a, shf[w]);
+        b = fmaxf(b, shf[16 + w]);
+    }
+    *omn = a;
+    *omx = b;
+}
+
+template <int VPT>
+__global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__restrict__ dist, int64_t ld, int k,
+                                                              const float *__restrict__ Q, int D,
+                                                              const float *__restrict__ qn,
+                                                              const float *__restrict__ C,
+                                                              const float *__restrict__ cn, int w, int self0,
+                                                              int32_t *__restrict__ cells,
+                                                              float *__restrict__ cell_dist)
+{
+    extern __shared__ float yv[]; // [D]
+    __shared__ int hist[SEL2_NB];
+    __shared__ uint64_t keys[SEL_CAP];
+    __shared__ int sh16[16];
+    __shared__ float shf[32];
+    __shared__ int sh_bin, sh_before, sh_inbin, sh_cnt, sh_taken;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = blockIdx.x;
+    const float *drow = dist + (int64_t)row * ld;
+    const int self = self0 >= 0 ? self0 + row : -1;
+    const int want = w + (self >= 0 ? 1 : 0);
+
+    for (int d = tid; d < D; d += SEL2_NT) yv[d] = Q[(int64_t)row * D + d];
+    // raw buffer over the row: base, stride 0, size in bytes, dword data format
+    const __amdgpu_buffer_rsrc_t rowbuf = __builtin_amdgcn_make_buffer_rsrc((void *)drow, 0, k * 4, 0x00020000);
+    float v[VPT];
+#pragma unroll
+    for (int e = 0; e < VPT; ++e) // one lane offset for all loads; the row end is range-checked by the buffer
+        v[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rowbuf, tid * 4, e * SEL2_NT * 4, 0));
+#pragma unroll
+    for (int e = 0; e < VPT; ++e)
+        if (e * SEL2_NT + tid >= k) v[e] = INFINITY;
+    uint64_t selm = 0, undm = 0; // bit e: entry e*1024 + tid is selected / still undecided
+    float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < VPT; ++e)
+        if (v[e] < INFINITY) {
+            undm |= 1ull << e;
+            mn = fminf(mn, v[e]);
+            mx = fmaxf(mx, v[e]);
+        }
+    float lo, hi;
+    block_minmax(mn, mx, tid, shf, &lo, &hi);
+    int nsel = 0;      // entries selected so far (all below lo)
+    bool ties = false; // the undecided entries are all equal to lo == hi
+    for (int level = 0; level < 8; ++level) {
+        if (!(hi > lo)) {
+            ties = true;
+            break;
+        }
+        const float scale = (float)SEL2_NB / (hi - lo);
+        hist[tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < VPT; ++e)
+            if (undm >> e & 1) {
+                int b = (int)((v[e] - lo) * scale);
+                b = b > SEL2_NB - 1 ? SEL2_NB - 1 : b;
+                atomicAdd(&hist[b], 1);
+            }
+        __syncthreads();
+        const int need = want - nsel; // rank of the cut among the undecided entries (1-based)
+        const int mine = hist[tid];
+        int total;
+        const int cum = block_incl_scan_int(mine, tid, sh16, &total);
+        if (cum - mine < need && need <= cum) {
+            sh_bin = tid;
+            sh_before = cum - mine;
+            sh_inbin = mine;
+        }
+        __syncthreads();
+        const int B = sh_bin, before = sh_before, inbin = sh_inbin;
+        // bins below B are in, bins above B are out
+        float bmn = INFINITY, bmx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < VPT; ++e)
+            if (undm >> e & 1) {
+                int b = (int)((v[e] - lo) * scale);
+                b = b > SEL2_NB - 1 ? SEL2_NB - 1 : b;
+                if (b < B) {
+                    selm |= 1ull << e;
+                    undm &= ~(1ull << e);
+                } else if (b > B) {
+                    undm &= ~(1ull << e);
+                } else {
+                    bmn = fminf(bmn, v[e]);
+                    bmx = fmaxf(bmx, v[e]);
+                }
+            }
+        nsel += before;
+        if (nsel + inbin <= SEL_CAP) { // take the whole bin
+            selm |= undm;
+            undm = 0;
+            nsel += inbin;
+            break;
+        }
+        block_minmax(bmn, bmx, tid, shf, &lo, &hi);
+    }
+    if (tid == 0) {
+        sh_cnt = 0;
+        sh_taken = 0;
+    }
+    __syncthreads();
+    if (ties || undm != 0 || nsel < want) {
+        // the undecided entries share one value (or the range could not be narrowed further):
+        // the missing ones are taken in index order
+        const int need = want - nsel;
+        for (int e = 0; e < VPT; ++e) {
+            const int flag = (int)(undm >> e & 1);
+            int total;
+            const int inc = block_incl_scan_int(flag, tid, sh16, &total);
+            const int taken = sh_taken;
+            if (flag && taken + inc <= need) selm |= 1ull << e;
+            __syncthreads();
+            if (tid == 0) sh_taken = taken + total;
+            __syncthreads();
+            if (sh_taken >= need) break;
+        }
+        undm = 0;
+    }
+    // ---- gather the selected entries: (GEMM-form distance, index) ----
+#pragma unroll
+    for (int e = 0; e < VPT; ++e)
+        if (selm >> e & 1) {
+            const int pos = atomicAdd(&sh_cnt, 1);
+            if (pos < SEL_CAP) keys[pos] = ((uint64_t)__float_as_uint(v[e]) << 32) | (uint32_t)(e * SEL2_NT + tid);
+        }
+    __syncthreads();
+    int cnt = min(sh_cnt, SEL_CAP);
+    int sz = next_pow2_dev(cnt);
+    for (int c = cnt + tid; c < sz; c += SEL2_NT) keys[c] = KEY_MAX;
+    __syncthreads();
+    block_bitonic_sort<SEL2_NT>(keys, sz, tid);
+    // ---- rounding band above the w-th smallest: entries not selected that may still belong ----
+    const float vw = __uint_as_float((uint32_t)(keys[want - 1] >> 32));
+    const float rq = qn[row];
+    __syncthreads();
+    // ||c|| <= ||y|| + sqrt(d) bounds the centroid norm without touching memory; the exact
+    // band (with the centroid's own norm) is applied to the few survivors below
+    const float sq = sqrtf(rq) + sqrtf(vw);
+    const float wide = vw * (1.f + 1e-5f) + 4e-6f * (rq + sq * sq) * 1.5f;
+#pragma unroll
+    for (int e = 0; e < VPT; ++e) {
+        if (!(selm >> e & 1) && v[e] <= wide) {
+            const int i = e * SEL2_NT + tid;
+            if (v[e] <= vw + 4e-6f * (rq + cn[i])) {
+                const int pos = atomicAdd(&sh_cnt, 1);
+                if (pos < SEL_CAP) keys[pos] = ((uint64_t)__float_as_uint(v[e]) << 32) | (uint32_t)i;
+            }
+        }
+    }
+    __syncthreads();
+    cnt = min(sh_cnt, SEL_CAP);
+    // ---- direct distances for everything inside the band; the rest cannot make the cut ----
+    const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
+    const int sub16 = lane >> 4, l16 = lane & 15;
+    for (int c0 = wave * 4; c0 < cnt; c0 += (SEL2_NT / 64) * 4) {
+        const int c = c0 + sub16;
+        uint64_t key = c < cnt ? keys[c] : KEY_MAX;
+        const int i = (int)(uint32_t)key;
+        bool inband = false;
+        if (c < cnt) inband = __uint_as_float((uint32_t)(key >> 32)) <= vw + 4e-6f * (rq + cn[i]);
+        float acc = 0.f;
+        if (inband) {
+            const float *rowp = C + (int64_t)i * D;
+            if (vec) {
+                for (int d = l16 * 4; d < D; d += 64) {
+                    const f32x4 cv = *(const f32x4 *)(rowp + d);
+                    const float t0 = yv[d] - cv.x, t1 = yv[d + 1] - cv.y, t2 = yv[d + 2] - cv.z, t3 = yv[d + 3] - cv.w;
+                    acc = fmaf(t0, t0, acc);
+                    acc = fmaf(t1, t1, acc);
+                    acc = fmaf(t2, t2, acc);
+                    acc = fmaf(t3, t3, acc);
+                }
+            } else {
+                for (int d = l16; d < D; d += 16) {
+                    const float t = yv[d] - rowp[d];
+                    acc = fmaf(t, t, acc);
+                }
+            }
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if (l16 == 0 && c < cnt) keys[c] = (inband && i != self) ? make_key(acc, (uint32_t)i) : KEY_MAX;
+    }
+    sz = next_pow2_dev(cnt);
+    for (int c = cnt + tid; c < sz; c += SEL2_NT) keys[c] = KEY_MAX;
+    __syncthreads();
+    block_bitonic_sort<SEL2_NT>(keys, sz, tid);
+    for (int e = tid; e < w; e += SEL2_NT) {
+        const uint64_t key = keys[e];
+        const bool ok = e < cnt && key != KEY_MAX;
+        cells[(int64_t)row * w + e] = ok ? (int32_t)(uint32_t)key : -1;
+        if (cell_dist) cell_dist[(int64_t)row * w + e] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+    }
+}
+
 void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const float *Q, int D,
                          const float *qn, const float *C, const float *cn, int w, int self0,
                          int32_t *cells, float *cell_dist, hipStream_t st)
 {
     if (rows <= 0) return;
-    hipLaunchKernelGGL(k_select_cells, dim3((unsigned)rows), dim3(256), (size_t)D * sizeof(float), st, dist, ld,
-                       k, Q, D, qn, C, cn, w, self0, cells, cell_dist);
+    const size_t smem = (size_t)D * sizeof(float);
+    if (k <= 4 * SEL2_NT) {
+        hipLaunchKernelGGL(k_select_cells_reg<4>, dim3((unsigned)rows), dim3(SEL2_NT), smem, st, dist, ld, k, Q, D, qn,
+                           C, cn, w, self0, cells, cell_dist);
+    } else if (k <= 16 * SEL2_NT) {
+        hipLaunchKernelGGL(k_select_cells_reg<16>, dim3((unsigned)rows), dim3(SEL2_NT), smem, st, dist, ld, k, Q, D, qn,
+                           C, cn, w, self0, cells, cell_dist);
+    } else if (k <= 64 * SEL2_NT) {
+        hipLaunchKernelGGL(k_select_cells_reg<64>, dim3((unsigned)rows), dim3(SEL2_NT), smem, st, dist, ld, k, Q, D, qn,
+                           C, cn, w, self0, cells, cell_dist);
+    } else {
+        hipLaunchKernelGGL(k_select_cells, dim3((unsigned)rows), dim3(256), smem, st, dist, ld, k, Q, D, qn, C, cn, w,
+                           self0, cells, cell_dist);
+    }
 }

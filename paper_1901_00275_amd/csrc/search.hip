@@ -37,27 +37,73 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
     const int q = blockIdx.x;
     const int total = w1 * n;
 
-    for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)q * D + d];
-    __syncthreads();
+    int *nbr = (int *)(pos + sz);                // [sz] neighbour centroid of every sub-region
 
-    for (int t = wave; t < total; t += 4) {
+    for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)q * D + d];
+    for (int t = tid; t < total; t += 256) {
         const int e = t / n, j = t - e * n;
         const int i = cells[(int64_t)q * w1 + e];
-        uint64_t key = KEY_MAX;
-        float b = 0.f;
-        if (i >= 0) {
-            const int s = S[(int64_t)i * n + j];
-            b = wave_sqdist(yv, C + (int64_t)s * D, D, lane);
-            const float a = cell_dist[(int64_t)q * w1 + e];
-            const float c = E[(int64_t)i * n + j];
-            const float lam = c > 0.f ? 0.5f * (a + c - b) / c : 0.f;
-            const float score = a - c * lam * lam;
-            key = make_key(score, (uint32_t)(i * n + j));
+        nbr[t] = i >= 0 ? S[(int64_t)i * n + j] : -1;
+    }
+    __syncthreads();
+
+    // b = ||y - s_ij||^2 for all w1*n sub-regions: 16 lanes per centroid row, 4 rows per wave
+    // instruction, 16 rows in flight per wave (the rows are scattered over the codebook, so
+    // the loop lives on memory-level parallelism).  The order of the additions is fixed.
+    const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
+    const int sub16 = lane >> 4, l16 = lane & 15;
+    for (int t0 = wave * 16; t0 < total; t0 += 64) {
+        float part[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int t = t0 + g * 4 + sub16;
+            const int s = t < total ? nbr[t] : -1;
+            float acc = 0.f;
+            if (s >= 0) {
+                const float *row = C + (int64_t)s * D;
+                if (vec) {
+                    for (int d = l16 * 4; d < D; d += 64) {
+                        const f32x4 cv = *(const f32x4 *)(row + d);
+                        const float t0v = yv[d] - cv.x, t1v = yv[d + 1] - cv.y, t2v = yv[d + 2] - cv.z,
+                                    t3v = yv[d + 3] - cv.w;
+                        acc = fmaf(t0v, t0v, acc);
+                        acc = fmaf(t1v, t1v, acc);
+                        acc = fmaf(t2v, t2v, acc);
+                        acc = fmaf(t3v, t3v, acc);
+                    }
+                } else {
+                    for (int d = l16; d < D; d += 16) {
+                        const float tv = yv[d] - row[d];
+                        acc = fmaf(tv, tv, acc);
+                    }
+                }
+            }
+            part[g] = acc;
         }
-        if (lane == 0) {
-            keys[t] = key;
-            bval[t] = b;
-            pos[t] = (uint16_t)t;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) part[g] += __shfl_xor(part[g], o, 64);
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int t = t0 + g * 4 + sub16;
+            if (l16 == 0 && t < total) {
+                const int e = t / n, j = t - e * n;
+                const int i = cells[(int64_t)q * w1 + e];
+                uint64_t key = KEY_MAX;
+                const float b = part[g];
+                if (i >= 0) {
+                    const float a = cell_dist[(int64_t)q * w1 + e];
+                    const float c = E[(int64_t)i * n + j];
+                    const float lam = c > 0.f ? 0.5f * (a + c - b) / c : 0.f;
+                    const float score = a - c * lam * lam;
+                    key = make_key(score, (uint32_t)(i * n + j));
+                }
+                keys[t] = key;
+                bval[t] = b;
+                pos[t] = (uint16_t)t;
+            }
         }
     }
     for (int t = total + tid; t < sz; t += 256) {
@@ -117,7 +163,7 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
     int sz = next_pow2(w1 * n);
     if (sz < next_pow2(w2)) sz = next_pow2(w2);
     if (sz < 2) sz = 2;
-    size_t smem = (size_t)sz * (8 + 4 + 2) + (size_t)D * 4;
+    size_t smem = (size_t)sz * (8 + 4 + 2 + 4) + (size_t)D * 4;
     (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
                        cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g, off, desc);
