@@ -29,8 +29,9 @@ def log(*a):
 
 def scan_bytes(vlq, wl, w1, w2, torch):
     """Algorithmic bytes of the list scan for one batch: every point of every
-    visited list once (m code bytes + 1 lambda byte + 4 id bytes) plus the two
-    list offsets per visited list."""
+    visited list once (m code bytes + 1 lambda byte + 4 bytes of the stored
+    query-independent term) plus one 16-byte descriptor per visited list and
+    the K ids looked up for the survivors."""
     cfg = wl.cfg
     nq = wl.Y.shape[0]
     dev = wl.Y.device
@@ -45,7 +46,7 @@ def scan_bytes(vlq, wl, w1, w2, torch):
     lens = (off[s + 1] - off[s]) * (sub >= 0)
     points = int(lens.sum())
     visited = int((sub >= 0).sum())
-    return points * (cfg.m + 5) + visited * 8, points, oi
+    return points * (cfg.m + 5) + visited * 16 + nq * cfg.K * 4, points, oi
 
 
 def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
@@ -69,27 +70,29 @@ def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
     del ids, codes, lam
     Cb, P, Y = wl.C.cpu().numpy(), wl.P.cpu().numpy(), wl.Y.cpu().numpy()
 
+    # graph rows are index data, not query work: for this timing leg they are copied out of the
+    # library as well (the oracle's own graph construction is O(k^2 D) and would take minutes here)
+    Sd = torch.empty(cfg.k, cfg.n, dtype=torch.int32, device=dev)
+    Ed = torch.empty(cfg.k, cfg.n, dtype=torch.float32, device=dev)
+    vlq.vlq_index_get_graph(wl.idx, Sd, Ed)
+    torch.cuda.synchronize()
+    S, E = Sd.cpu().numpy(), Ed.cpu().numpy().astype(np.float64)
+
     def run(Yq):
         t0 = time.time()
         dist = oracle.coarse(Cb, Yq)
         cells = oracle.select_smallest(dist, w1)
-        t1 = time.time()
-        S, E = oracle.sparse_graph(Cb, cfg.n, cells.ravel())  # index data, not query work: untimed
-        t2 = time.time()
         score, label = oracle.subregion_scores(dist, S, E, cells)
         sub = oracle.select_smallest(score, w2, key=label)
         out_d, out_i, _ = oracle.scan(Cb, S, P, lists, Yq, sub, cfg.K)
-        t3 = time.time()
-        return (t1 - t0) + (t3 - t2), out_i
+        return time.time() - t0, out_i
 
     nprobe = min(32, len(Y))
     t, _ = run(Y[:nprobe])
     ns = int(min(len(Y), max(nprobe, target_s / max(t / nprobe, 1e-9))))
-    if cfg.k > 20000:  # the oracle's graph rows for the probed cells cost k*D each: keep that bounded
-        ns = min(ns, 256)
     t, out_i = run(Y[:ns])
     return {"value": ns / t, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"first {ns} of the {len(Y)} queries, full index, same w1/w2/K; {t:.1f} s of oracle search"}, out_i, ns
+            "sample": f"first {ns} of the {len(Y)} queries, index and graph copied from the library, same w1/w2/K; {t:.1f} s of oracle search"}, out_i, ns
 
 
 def main():
@@ -97,7 +100,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="mid_sift")
+    ap.add_argument("--config", default="billion_sift")
     ap.add_argument("--w1", type=int, default=0, help="probed cells (default: the configuration's operating point)")
     ap.add_argument("--points", type=int, default=0, help="build only the first POINTS vectors (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -159,7 +162,7 @@ def main():
                    "edges": cfg.n, "code_bytes": cfg.m, "queries": nq, "w1": w1, "w2": w2, "K": K,
                    "recall": rec, "points_scanned_per_query": points / nq,
                    "stage_ms_per_step": stage_ms, "build_s": wl.timings},
-        "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "roofline": {"bound": "hbm", "kernel": "k_scan_stream", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": scan_avg_s * 1e3},
     }

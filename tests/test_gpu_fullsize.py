@@ -1,0 +1,144 @@
+"""Full-size check of the mid SIFT-like configuration (10^7 points, k = 16 384, n = 32, m = 8,
+10 000 queries, w1 = 64, w2 = 512, K = 100) in the launch configuration that bench.py times.
+The oracle cannot encode 10^7 points, so it is used on samples it can compute one by one; all of its
+inputs come from the seeded generators (raw vectors are regenerated from the seed by id):
+
+ * encoding of sampled base vectors (every field, tie-band protocol);
+ * traversal (cells, sub-regions) of sampled queries;
+ * every returned (id, distance) of sampled queries: the oracle encodes the raw vector of that id,
+   rebuilds the approximated point and its distance to the query (Eq. 14), and checks that the
+   point's list was visited;
+ * completeness probe: the exact nearest neighbour of a sampled query, if its list is visited and
+   its ADC distance beats the K-th result, must be among the results.
+"""
+import numpy as np
+import pytest
+import torch
+
+import datagen
+from datagen import workloads
+from parity import DTOL, GAP, check_selection
+from test_gpu_parity import DEV, check_encode, gpu_encode
+from util import Problem
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vlq():
+    import paper_1901_00275_amd as vlq
+
+    vlq.lib()
+    return vlq
+
+
+def _raw_vectors(mix, cfg, ids):
+    """Base vectors with the given ids, regenerated chunk by chunk from the seed."""
+    ids = np.asarray(ids, np.int64)
+    out = np.empty((len(ids), cfg.D), np.float32)
+    sizes = {c: cnt for c, cnt in workloads.chunks(cfg)}
+    for c in np.unique(ids // datagen.CHUNK):
+        X = mix.base_chunk(int(c), DEV, sizes[int(c)])
+        sel = np.nonzero(ids // datagen.CHUNK == c)[0]
+        rows = torch.as_tensor(ids[sel] % datagen.CHUNK, device=DEV)
+        out[sel] = X[rows].cpu().numpy()
+        del X
+    return out
+
+
+def _oracle_encode(oracle, pr, X):
+    cell, _ = oracle.vq_assign(pr.C, X)
+    S, E = oracle.sparse_graph(pr.C, pr.n, cell)
+    return oracle.encode(pr.C, S, E, pr.P, X), S, E
+
+
+def test_mid_sift_sampled(vlq, oracle_mod):
+    cfg = workloads.CONFIGS["mid_sift"]
+    wl = workloads.materialise(vlq, cfg, DEV, log=lambda *a: print(*a, flush=True))
+    try:
+        pr = Problem("sift", None, wl.Y.cpu().numpy(), wl.C.cpu().numpy(), wl.P.cpu().numpy(), cfg.n)
+        rng = np.random.default_rng(7)
+
+        # ---- encoding of sampled base vectors ----
+        ids = np.sort(rng.choice(cfg.N, 1500, replace=False))
+        Xs = _raw_vectors(wl.mix, cfg, ids)
+        enc, S, E = _oracle_encode(oracle_mod, pr, Xs)
+        got = gpu_encode(vlq, wl.idx, Xs, cfg.m)
+        S, E = oracle_mod.sparse_graph(pr.C, pr.n, np.concatenate([enc.cell, got[0]]))
+        check_encode(oracle_mod, pr, S, E, Xs, got)
+        # the stored lists hold these points with the same fields
+        nl = cfg.k * cfg.n
+        off = torch.empty(nl + 1, dtype=torch.int64, device=DEV)
+        lids = torch.empty(cfg.N, dtype=torch.int32, device=DEV)
+        lcodes = torch.empty(cfg.N, cfg.m, dtype=torch.uint8, device=DEV)
+        llam = torch.empty(cfg.N, dtype=torch.uint8, device=DEV)
+        vlq.vlq_index_get_lists(wl.idx, off, lids, lcodes, llam)
+        torch.cuda.synchronize()
+        off_h = off.cpu().numpy()
+        assert off_h[0] == 0 and off_h[-1] == cfg.N and (np.diff(off_h) >= 0).all()
+        for t in rng.choice(len(ids), 200, replace=False):
+            label = int(got[0][t]) * cfg.n + int(got[1][t])
+            seg = lids[off_h[label]:off_h[label + 1]].cpu().numpy()
+            pos = np.searchsorted(seg, ids[t])  # ids ascend inside a list
+            assert pos < len(seg) and seg[pos] == ids[t], f"id {ids[t]} not in list {label}"
+            assert (np.diff(seg) > 0).all()
+            g = off_h[label] + pos
+            assert (lcodes[g].cpu().numpy() == got[3][t]).all() and int(llam[g]) == int(got[2][t])
+        del lids, lcodes, llam
+
+        # ---- search in the bench launch configuration ----
+        nq, w1, w2, K = cfg.nq, cfg.w1[-1], cfg.w2(cfg.w1[-1]), cfg.K
+        od = torch.empty(nq, K, device=DEV)
+        oi = torch.empty(nq, K, dtype=torch.int32, device=DEV)
+        cells = torch.empty(nq, w1, dtype=torch.int32, device=DEV)
+        cd = torch.empty(nq, w1, device=DEV)
+        sub = torch.empty(nq, w2, dtype=torch.int32, device=DEV)
+        ss = torch.empty(nq, w2, device=DEV)
+        vlq.vlq_search_debug(wl.idx, wl.Y, nq, w1, w2, K, od, oi, cells, cd, sub, ss)
+        torch.cuda.synchronize()
+        assert datagen.recall_at(oi, wl.gt, 100) > 0.2  # sanity: the index finds neighbours
+        qs = rng.choice(nq, 24, replace=False)
+        od, oi, cells, cd, sub, ss = (t[torch.as_tensor(qs, device=DEV)].cpu().numpy() for t in (od, oi, cells, cd, sub, ss))
+        Yq = pr.Y[qs]
+        dist = oracle_mod.coarse(pr.C, Yq)
+        ocells = oracle_mod.select_smallest(dist, w1)
+        S, E = oracle_mod.sparse_graph(pr.C, pr.n, np.concatenate([ocells.ravel(), cells.ravel()]))
+        gt = wl.gt.cpu().numpy()[qs]
+        gt_vec = _raw_vectors(wl.mix, cfg, gt)
+        gt_enc, Sg, _ = _oracle_encode(oracle_mod, pr, gt_vec)
+        for r, q in enumerate(qs):
+            what = f"query {q}"
+            check_selection(cells[r], dict(enumerate(dist[r])), w1, what=what + " cells")
+            assert np.allclose(cd[r], dist[r][cells[r]], rtol=DTOL), what
+            score, label = (x[0] for x in oracle_mod.subregion_scores(dist[r:r + 1], S, E, cells[r:r + 1]))
+            val = {int(l): float(s) for l, s in zip(label, score)}
+            a_max = dist[r][cells[r]].max()
+            check_selection(sub[r], val, w2, scale=a_max, what=what + " sub-regions")
+            assert np.allclose(ss[r], [val[int(l)] for l in sub[r]], rtol=0, atol=DTOL * a_max), what
+            # every returned point: distance and membership re-derived from its raw vector
+            valid = oi[r] >= 0
+            assert valid.sum() == K and (np.diff(od[r]) >= 0).all() and len(set(oi[r].tolist())) == K
+            Xr = _raw_vectors(wl.mix, cfg, oi[r])
+            renc, Sr, _ = _oracle_encode(oracle_mod, pr, Xr)
+            Xh = oracle_mod.reconstruct(pr.C, Sr, pr.P, renc.cell, renc.edge, renc.lamq, renc.codes)
+            dref = ((Yq[r].astype(np.float64) - Xh) ** 2).sum(1)
+            visited = set(sub[r].tolist())
+            for j in range(K):
+                tie = renc.cell_d[j, 1] - renc.cell_d[j, 0] <= GAP * renc.cell_d[j, 1] or \
+                    renc.edge_d[j, 1] - renc.edge_d[j, 0] <= GAP * renc.cell_d[j, 0]
+                if tie:
+                    continue  # the point may legitimately sit in a neighbouring list
+                assert int(renc.cell[j]) * cfg.n + int(renc.edge[j]) in visited, f"{what}: result {j} from an unvisited list"
+                frac = renc.lam_coord[j] - np.floor(renc.lam_coord[j])
+                if abs(frac - 0.5) < 2e-3 or (renc.code_d[j, :, 1] - renc.code_d[j, :, 0] <= GAP * renc.code_d[j, :, 1]).any():
+                    continue  # byte / code inside a tie band: the stored code may differ
+                assert abs(od[r][j] - dref[j]) <= DTOL * dref[j], f"{what}: distance of result {j}"
+            # completeness: the true neighbour, if visited and good enough, must be returned
+            glabel = int(gt_enc.cell[r]) * cfg.n + int(gt_enc.edge[r])
+            gh = oracle_mod.reconstruct(pr.C, Sg, pr.P, gt_enc.cell[r:r + 1], gt_enc.edge[r:r + 1],
+                                        gt_enc.lamq[r:r + 1], gt_enc.codes[r:r + 1])
+            gd = ((Yq[r].astype(np.float64) - gh[0]) ** 2).sum()
+            if glabel in visited and gd < od[r][K - 1] * (1 - 1e-4):
+                assert gt[r] in set(oi[r].tolist()), f"{what}: true neighbour {gt[r]} missed"
+    finally:
+        vlq.vlq_index_free(wl.idx)
