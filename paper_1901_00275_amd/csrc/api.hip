@@ -2,6 +2,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -50,6 +51,9 @@ struct vlq_index {
     // codebooks and graph
     float *C = nullptr, *cn = nullptr, *P = nullptr, *E = nullptr;
     int32_t *S = nullptr;
+    // centroids split into bf16 (hi, lo) for the matrix-core shortlist; null when D does not allow it
+    uint16_t *Ch = nullptr, *Cl = nullptr;
+    int32_t *flags = nullptr;
     // staged points, in insertion order
     int64_t ntotal = 0, cap = 0;
     int32_t *st_label = nullptr, *st_ids = nullptr;
@@ -125,7 +129,8 @@ extern "C" void vlq_index_free(vlq_index_t *idx)
     if (!idx) return;
     (void)hipDeviceSynchronize();
     void *ptrs[] = {idx->C, idx->cn, idx->P, idx->E, idx->S, idx->st_label, idx->st_ids, idx->st_lam,
-                    idx->st_codes, idx->off, idx->ids, idx->codes, idx->lam, idx->sx, idx->ws};
+                    idx->st_codes, idx->off, idx->ids, idx->codes, idx->lam, idx->sx, idx->ws,
+                    idx->Ch, idx->Cl, idx->flags};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (auto &r : idx->recs) {
@@ -217,6 +222,13 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
         HIPCHK(hipMemsetAsync(idx->off, 0, ((size_t)k * n + 1) * 8, st));
         launch_row_norms(idx->C, k, D, idx->cn, st);
         LAUNCHCHK();
+        if (coarse_bf16_supported(D)) {
+            HIPCHK(hipMalloc(&idx->Ch, (size_t)k * D * 2));
+            HIPCHK(hipMalloc(&idx->Cl, (size_t)k * D * 2));
+            HIPCHK(hipMalloc(&idx->flags, 256));
+            launch_split_bf16(idx->C, k, D, idx->Ch, idx->Cl, idx->flags, st);
+            LAUNCHCHK();
+        }
         int r = build_graph(idx, st);
         if (r) return r;
         idx->finalized = true; // an empty index is searchable
@@ -262,11 +274,20 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
     const int k = idx->p.nlist, D = idx->p.d, n = idx->p.n_edges, m = idx->p.m;
     const int64_t chunk = nb < ENC_CHUNK ? nb : ENC_CHUNK;
     const int nsplit = coarse_gemm_nn_splits((int)chunk, k);
+    // shortlist on the bf16 matrix cores unless the dimension rules it out (or the environment asks
+    // for the fp32 product, which the tests use to cover both)
+    const char *env = getenv("VLQ_COARSE_FP32");
+    const bool bf16 = idx->Ch && !(env && env[0] == '1');
     float *xn;
     uint64_t *cand;
+    uint16_t *xh = nullptr, *xl = nullptr;
     int32_t *tcell, *tedge, *flag;
     auto carve = [&](Bump &b) {
         xn = b.take<float>((size_t)chunk);
+        if (bf16) {
+            xh = b.take<uint16_t>((size_t)chunk * D);
+            xl = b.take<uint16_t>((size_t)chunk * D);
+        }
         cand = b.take<uint64_t>((size_t)chunk * nsplit * VLQ_NN_CANDS);
         tcell = b.take<int32_t>((size_t)chunk);
         tedge = b.take<int32_t>((size_t)chunk);
@@ -284,9 +305,18 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
         // the split count is fixed by the buffer; a short tail only leaves less work per split
         launch_row_norms(x, cnt, D, xn, st);
         LAUNCHCHK();
-        launch_coarse_gemm_nn(x, (int)cnt, idx->C, k, D, xn, idx->cn, cand, nsplit, st);
-        LAUNCHCHK();
         EncodeArgs a;
+        if (bf16) {
+            launch_split_bf16(x, cnt, D, xh, xl, flag + 1, st);
+            LAUNCHCHK();
+            launch_coarse_gemm_nn_bf16(xh, xl, flag + 1, (int)cnt, idx->Ch, idx->Cl, k, D, xn, idx->cn, cand, nsplit,
+                                       &a.band_norm, &a.band_dist, st);
+        } else {
+            launch_coarse_gemm_nn(x, (int)cnt, idx->C, k, D, xn, idx->cn, cand, nsplit, st);
+            a.band_norm = VLQ_FP32_BAND_NORM;
+            a.band_dist = 0.f;
+        }
+        LAUNCHCHK();
         a.X = x;
         a.nb = cnt;
         a.D = D;

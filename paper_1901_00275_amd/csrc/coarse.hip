@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
             if (mn == KEY_MAX) continue;
             const float dmin = __uint_as_float((uint32_t)(mn >> 32));
             // rounding band of the GEMM form: a few ulp of ||a||^2 + ||b||^2 <= 3||a||^2 + 2 d
-            const float band = dmin + 4e-6f * (3.f * ra[i][r] + 2.f * dmin);
+            const float band = dmin + VLQ_FP32_BAND_NORM * (3.f * ra[i][r] + 2.f * dmin);
             uint64_t ks[2] = {b1[i][r], b2[i][r]};
 #pragma unroll
             for (int s = 0; s < 2; ++s) {

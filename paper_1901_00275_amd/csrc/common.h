@@ -136,10 +136,23 @@ void launch_coarse_gemm_full(const float *A, int M, const float *B, int N, int D
 // Same product, but only nearest-row candidates are kept: for every row of A
 // up to VLQ_NN_CANDS keys (distance bits << 32 | column) per column split that lie
 // within the rounding band of the row minimum.  cand [M x nsplit x VLQ_NN_CANDS].
-#define VLQ_NN_CANDS 4
+#define VLQ_NN_CANDS 8
+// Width of the band as used by the fp32 product: band_norm * (3 ||a||^2 + 2 d) + band_dist * d.
+#define VLQ_FP32_BAND_NORM 4e-6f
 int coarse_gemm_nn_splits(int M, int N);
 void launch_coarse_gemm_nn(const float *A, int M, const float *B, int N, int D, const float *an,
                            const float *bn, uint64_t *cand, int nsplit, hipStream_t st);
+
+// The same shortlist from operands split into bf16 (hi, lo) pairs, on the bf16 matrix
+// cores (coarse_bf16.hip).  Requires coarse_bf16_supported(D).  The band the
+// consumer has to apply is returned in *band_norm / *band_dist.
+bool coarse_bf16_supported(int D);
+void launch_split_bf16(const float *X, int64_t rows, int D, uint16_t *hi, uint16_t *lo, int *any_lo,
+                       hipStream_t st);
+void launch_coarse_gemm_nn_bf16(const uint16_t *Ah, const uint16_t *Al, const int *a_any_lo, int M,
+                                const uint16_t *Bh, const uint16_t *Bl, int N, int D, const float *an,
+                                const float *bn, uint64_t *cand, int nsplit, float *band_norm,
+                                float *band_dist, hipStream_t st);
 
 // w smallest entries of each row of dist [rows x k] (GEMM-form values), re-evaluated
 // as direct sums of squared differences and ordered by (distance, index).
@@ -193,6 +206,7 @@ struct EncodeArgs {
     float lam_step, lam_zero;
     const uint64_t *cand;
     int nsplit;
+    float band_norm, band_dist; // error band of the shortlist's distances
     int32_t *cell, *edge;
     uint8_t *lamq, *codes;
 };

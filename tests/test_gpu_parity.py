@@ -196,6 +196,21 @@ def test_build_encode_search_against_oracle(vlq, oracle_mod, name):
         vlq.vlq_index_free(idx)
 
 
+@pytest.mark.parametrize("kind,fp32", [("sift", False), ("deep", False), ("sift", True)])
+def test_encode_with_both_coarse_products(vlq, oracle_mod, monkeypatch, kind, fp32):
+    """Alg. 1 + 2 with the nearest-centroid shortlist from the split-bf16 product (integer-valued and
+    real-valued data: without and with low halves) and from the fp32 product; several ragged tiles."""
+    if fp32:
+        monkeypatch.setenv("VLQ_COARSE_FP32", "1")
+    pr = problem(kind=kind, N=6000, k=300, n=6, m=8, G=16, nq=8)
+    idx = make_index(vlq, pr)
+    try:
+        S, E = oracle_mod.graph(pr.C, pr.n)
+        check_encode(oracle_mod, pr, S, E, pr.X, gpu_encode(vlq, idx, pr.X, pr.m))
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_lists_layout_matches_oracle(vlq, oracle_mod):
     """vlq_index_add + finalize: the four list arrays of Sec. 4, ids ascending inside a list."""
     pr = problem(N=20011, k=100, n=7, m=8, G=16, nq=77)
