@@ -52,7 +52,7 @@ struct vlq_index {
     float *C = nullptr, *cn = nullptr, *P = nullptr, *E = nullptr;
     int32_t *S = nullptr;
     // centroids split into bf16 (hi, lo) for the matrix-core shortlist; null when D does not allow it
-    uint16_t *Ch = nullptr, *Cl = nullptr;
+    void *Cimg = nullptr;
     int32_t *flags = nullptr;
     // staged points, in insertion order
     int64_t ntotal = 0, cap = 0;
@@ -130,7 +130,7 @@ extern "C" void vlq_index_free(vlq_index_t *idx)
     (void)hipDeviceSynchronize();
     void *ptrs[] = {idx->C, idx->cn, idx->P, idx->E, idx->S, idx->st_label, idx->st_ids, idx->st_lam,
                     idx->st_codes, idx->off, idx->ids, idx->codes, idx->lam, idx->sx, idx->ws,
-                    idx->Ch, idx->Cl, idx->flags};
+                    idx->Cimg, idx->flags};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (auto &r : idx->recs) {
@@ -223,10 +223,9 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
         launch_row_norms(idx->C, k, D, idx->cn, st);
         LAUNCHCHK();
         if (coarse_bf16_supported(D)) {
-            HIPCHK(hipMalloc(&idx->Ch, (size_t)k * D * 2));
-            HIPCHK(hipMalloc(&idx->Cl, (size_t)k * D * 2));
+            HIPCHK(hipMalloc(&idx->Cimg, coarse_bf16_image_bytes(k, D)));
             HIPCHK(hipMalloc(&idx->flags, 256));
-            launch_split_bf16(idx->C, k, D, idx->Ch, idx->Cl, idx->flags, st);
+            launch_split_bf16(idx->C, k, D, idx->Cimg, idx->flags, st);
             LAUNCHCHK();
         }
         int r = build_graph(idx, st);
@@ -277,17 +276,14 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
     // shortlist on the bf16 matrix cores unless the dimension rules it out (or the environment asks
     // for the fp32 product, which the tests use to cover both)
     const char *env = getenv("VLQ_COARSE_FP32");
-    const bool bf16 = idx->Ch && !(env && env[0] == '1');
+    const bool bf16 = idx->Cimg && !(env && env[0] == '1');
     float *xn;
     uint64_t *cand;
-    uint16_t *xh = nullptr, *xl = nullptr;
+    uint8_t *ximg = nullptr;
     int32_t *tcell, *tedge, *flag;
     auto carve = [&](Bump &b) {
         xn = b.take<float>((size_t)chunk);
-        if (bf16) {
-            xh = b.take<uint16_t>((size_t)chunk * D);
-            xl = b.take<uint16_t>((size_t)chunk * D);
-        }
+        if (bf16) ximg = b.take<uint8_t>(coarse_bf16_image_bytes(chunk, D));
         cand = b.take<uint64_t>((size_t)chunk * nsplit * VLQ_NN_CANDS);
         tcell = b.take<int32_t>((size_t)chunk);
         tedge = b.take<int32_t>((size_t)chunk);
@@ -307,10 +303,10 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
         LAUNCHCHK();
         EncodeArgs a;
         if (bf16) {
-            launch_split_bf16(x, cnt, D, xh, xl, flag + 1, st);
+            launch_split_bf16(x, cnt, D, ximg, flag + 1, st);
             LAUNCHCHK();
-            launch_coarse_gemm_nn_bf16(xh, xl, flag + 1, (int)cnt, idx->Ch, idx->Cl, k, D, xn, idx->cn, cand, nsplit,
-                                       &a.band_norm, &a.band_dist, st);
+            HIPCHK((hipError_t)launch_coarse_gemm_nn_bf16(ximg, flag + 1, (int)cnt, idx->Cimg, k, D, xn, idx->cn, cand,
+                                                          nsplit, &a.band_norm, &a.band_dist, st));
         } else {
             launch_coarse_gemm_nn(x, (int)cnt, idx->C, k, D, xn, idx->cn, cand, nsplit, st);
             a.band_norm = VLQ_FP32_BAND_NORM;

@@ -9,21 +9,29 @@
 // is handed on and re-evaluated there as a direct fp32 sum of squared differences,
 // so the decision itself is taken in fp32 exactly as by the fp32 path.
 //
-// Workgroup = 256 threads = 4 waves, tile 128 x 128, each wave a 64 x 64 quadrant
-// (2 x 2 MFMA blocks).  Operands are streamed in slabs of 32 contraction indices:
-// global -> registers -> LDS, double buffered, one barrier per slab; two workgroups
-// share a CU so one's epilogue overlaps the other's MFMAs.  An LDS slab row is
-// 64 bytes = four 16-byte chunks; chunk c of row r is stored at position
-// c ^ ((r >> 1) & 3), which makes both the row-contiguous writes and the
-// 32-rows-by-one-chunk fragment reads free of bank conflicts.
+// Operand images.  Both operands are first rewritten (k_split_bf16) into the exact
+// byte image the product kernel wants in LDS: rows in blocks of 128, the contraction
+// index in steps of 16, and per (block, step) a 4 KB "hi" page followed by a 4 KB "lo"
+// page.  A page holds 128 rows x 2 chunks of 16 bytes (8 bf16); chunk c of row r sits
+// at position 2 r + (c ^ ((r >> 2) & 1)), which keeps the 32-rows-by-one-chunk
+// fragment reads of the MFMA operands free of bank conflicts.  Pages of one block are
+// contiguous, so every global access of the product kernel is a fully used 4 KB run.
+//
+// Product kernel.  Workgroup = 256 threads = 4 waves, 128 rows of A against all
+// columns of its split; each wave owns a 64 x 64 quadrant (2 x 2 MFMA blocks).  The
+// 128 rows of A stay in LDS for the whole sweep (D <= 128: 64 KB); the pages of B
+// stream global -> registers (four steps ahead) -> a two-page-pair ring in LDS, one
+// barrier per step.  Two workgroups share a CU (2 x 80 KB of LDS), so one's
+// selection epilogue overlaps the other's MFMAs.
 #include "common.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
-#define BT 128
-#define BK 32
+#define BT 128          // rows per block
+#define BSTEP 16        // contraction indices per step
+#define PAGE 256        // 16-byte chunks per page
+#define BF16_MAX_D 128  // A block resident in LDS: D / 16 steps x 2 pages x 4 KB
 
 __device__ __forceinline__ uint32_t bf16_rne(float f)
 {
@@ -31,59 +39,79 @@ __device__ __forceinline__ uint32_t bf16_rne(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-// X [count] fp32 -> hi, lo [count] bf16; *any_lo is raised when some lo is non-zero.
-__global__ __launch_bounds__(256) void k_split_bf16(const float *__restrict__ X, int64_t count4,
-                                                    uint16_t *__restrict__ hi, uint16_t *__restrict__ lo,
+// X [rows x D] fp32 -> image [ceil(rows / 128)][D / 16][hi page, lo page]; rows past
+// the end are written as zeros.  *any_lo is raised when some lo is non-zero.
+// One thread per (row, chunk of 8 values).
+__global__ __launch_bounds__(256) void k_split_bf16(const float *__restrict__ X, int64_t rows, int D,
+                                                    int64_t padded_rows, u32x4 *__restrict__ img,
                                                     int *__restrict__ any_lo)
 {
+    const int cpr = D / 8; // chunks per row
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     bool nz = false;
-    if (i < count4) {
-        const f32x4 v = ((const f32x4 *)X)[i];
-        uint32_t h[4], l[4];
+    if (i < padded_rows * cpr) {
+        const int64_t row = i / cpr;
+        const int ch = (int)(i - row * cpr);
+        u32x4 ph = {0, 0, 0, 0}, pl = {0, 0, 0, 0};
+        if (row < rows) {
+            const f32x4 v0 = *(const f32x4 *)(X + row * D + ch * 8);
+            const f32x4 v1 = *(const f32x4 *)(X + row * D + ch * 8 + 4);
+            uint32_t h[8], l[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            h[e] = bf16_rne(v[e]);
-            const float r = v[e] - __uint_as_float(h[e] << 16);
-            l[e] = bf16_rne(r);
-            nz |= (l[e] & 0x7FFFu) != 0;
+            for (int e = 0; e < 8; ++e) {
+                const float v = e < 4 ? v0[e] : v1[e - 4];
+                h[e] = bf16_rne(v);
+                l[e] = bf16_rne(v - __uint_as_float(h[e] << 16));
+                nz |= (l[e] & 0x7FFFu) != 0;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ph[e] = h[2 * e] | (h[2 * e + 1] << 16);
+                pl[e] = l[2 * e] | (l[2 * e + 1] << 16);
+            }
         }
-        u32x2 ph, pl;
-        ph.x = h[0] | (h[1] << 16);
-        ph.y = h[2] | (h[3] << 16);
-        pl.x = l[0] | (l[1] << 16);
-        pl.y = l[2] | (l[3] << 16);
-        ((u32x2 *)hi)[i] = ph;
-        ((u32x2 *)lo)[i] = pl;
+        const int64_t blk = row / BT;
+        const int r = (int)(row - blk * BT);
+        const int step = ch >> 1, c = ch & 1;
+        const int64_t page = (blk * (D / BSTEP) + step) * 2;
+        const int pos = 2 * r + (c ^ ((r >> 2) & 1));
+        img[page * PAGE + pos] = ph;
+        img[(page + 1) * PAGE + pos] = pl;
     }
     if (__ballot(nz) != 0 && (threadIdx.x & 63) == 0) atomicOr(any_lo, 1);
 }
 
 __global__ void k_zero_flag(int *p) { *p = 0; }
 
-void launch_split_bf16(const float *X, int64_t rows, int D, uint16_t *hi, uint16_t *lo, int *any_lo,
-                       hipStream_t st)
+bool coarse_bf16_supported(int D) { return D == 32 || D == 64 || D == 96 || D == 128; }
+
+size_t coarse_bf16_image_bytes(int64_t rows, int D)
 {
-    hipLaunchKernelGGL(k_zero_flag, dim3(1), dim3(1), 0, st, any_lo);
-    const int64_t count4 = rows * D / 4;
-    if (count4 <= 0) return;
-    hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, st, X, count4, hi, lo,
-                       any_lo);
+    const int64_t blocks = (rows + BT - 1) / BT;
+    return (size_t)blocks * BT * D * 4;
 }
 
-bool coarse_bf16_supported(int D) { return D % BK == 0; }
+void launch_split_bf16(const float *X, int64_t rows, int D, void *img, int *any_lo, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_zero_flag, dim3(1), dim3(1), 0, st, any_lo);
+    const int64_t padded = (rows + BT - 1) / BT * BT;
+    const int64_t n = padded * (D / 8);
+    if (n <= 0) return;
+    hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, X, rows, D, padded,
+                       (u32x4 *)img, any_lo);
+}
 
-// Rounding band of the split product relative to ||a||^2 + ||b||^2 (both rows of a
-// comparison carry the error, hence twice 2 * 3 * 2^-18 / 2, rounded up).
+// Error of the split product relative to ||a||^2 + ||b||^2 <= 3 ||a||^2 + 2 d: minimum and
+// candidate each carry 2 * 3 * 2^-18 |a| |b| <= 3 * 2^-18 (||a||^2 + ||b||^2), rounded up.
 #define BF16_BAND_NORM 3e-5f
-// Columns past the end of B get this "norm": finite, so that the index bits can be
-// planted in it, and above BF16_INVALID_BITS, from where on a key counts as absent.
+// Columns past the end of B get this "norm": finite, so that index bits can be planted
+// in the key, and beyond BF16_NO_KEY, from where on a key counts as absent.
 #define BF16_NO_COLUMN 3e38f
-#define BF16_INVALID_BITS 0x7E000000u
+#define BF16_NO_KEY 1e38f
 
 struct Bf16NNArgs {
-    const u32x4 *Ah, *Al; // [M x D/8]
-    const u32x4 *Bh, *Bl; // [N x D/8]
+    const u32x4 *A; // image of the rows
+    const u32x4 *B; // image of the columns
     const int *a_any_lo;
     int M, N, D;
     const float *an, *bn;
@@ -93,14 +121,15 @@ struct Bf16NNArgs {
     float band_dist;
 };
 
+// SPT = D / 16 steps per tile; PDEPTH page pairs of B in flight in registers (divides SPT, so
+// that every register set and ring half has a fixed role in the unrolled tile body).
+template <int SPT>
 __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
 {
-    __shared__ u32x4 slab[2][4][BT * 4]; // [buffer][Ah, Al, Bh, Bl][row * 4 + swizzled chunk]
-    __shared__ float ran[BT];
-    __shared__ unsigned rowmin[BT];
-    __shared__ int rowcnt[BT];
-    __shared__ unsigned long long rowcand[BT][VLQ_NN_CANDS];
-
+    constexpr int PDEPTH = SPT % 4 == 0 ? 4 : (SPT % 3 == 0 ? 3 : 2);
+    static_assert(SPT % 2 == 0 && SPT % PDEPTH == 0, "steps per tile");
+    // [A pages: SPT x 2][B ring: 2 x 2 pages]; the tail of the kernel reuses the front
+    extern __shared__ u32x4 lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int64_t m0 = (int64_t)blockIdx.x * BT;
@@ -108,60 +137,41 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
     const int ntiles = (a.N + BT - 1) / BT;
     const int t0 = split * a.tiles_per_split;
     const int t1 = min(ntiles, t0 + a.tiles_per_split);
-    const int DC = a.D / 8;   // 16-byte chunks per row
-    const int SL = a.D / BK;  // slabs per tile
-    const int total = (t1 - t0) * SL;
+    const int ntl = t1 > t0 ? t1 - t0 : 0;
+    const int last = ntl * SPT - 1; // last step of the split
     const bool use_lo = *a.a_any_lo != 0;
+    u32x4 *Apages = lds;
+    u32x4 *ring = lds + SPT * 2 * PAGE;
 
-    if (tid < BT) {
-        ran[tid] = m0 + tid < a.M ? a.an[m0 + tid] : 0.f;
-        rowmin[tid] = 0xFFFFFFFFu;
-        rowcnt[tid] = 0;
+    // the block of A
+    {
+        const u32x4 *src = a.A + (int64_t)blockIdx.x * SPT * 2 * PAGE;
 #pragma unroll
-        for (int s = 0; s < VLQ_NN_CANDS; ++s) rowcand[tid][s] = KEY_MAX;
+        for (int p = 0; p < SPT * 2; ++p) Apages[p * PAGE + tid] = src[p * PAGE + tid];
     }
 
-    // staging: thread moves chunks q = tid and tid + 256 of every operand slab
-    int lrow[2], lpos[2];
-    int64_t offA[2];
+    // B pages: step j of this split is the page pair at (t0 * SPT + j) * 2.  Loads past the
+    // last step re-read the last pair, so that the number of loads in flight never varies.
+    const u32x4 *bsrc = a.B + (int64_t)t0 * SPT * 2 * PAGE + tid;
+    auto fetch = [&](u32x4 (&r)[2], int j) {
+        j = min(j, last);
+        r[0] = bsrc[(int64_t)(2 * j) * PAGE];
+        r[1] = bsrc[(int64_t)(2 * j + 1) * PAGE];
+    };
+    u32x4 rb[PDEPTH][2];
+    if (ntl > 0) {
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const int q = tid + 256 * p;
-        lrow[p] = q >> 2;
-        const int c = q & 3;
-        lpos[p] = lrow[p] * 4 + (c ^ ((lrow[p] >> 1) & 3));
-        int64_t r = m0 + lrow[p];
-        if (r > a.M - 1) r = a.M - 1; // rows past the end repeat the last one and are never emitted
-        offA[p] = r * DC + c;
+        for (int j = 0; j < PDEPTH; ++j) fetch(rb[j], j);
+        ring[tid] = rb[0][0];
+        ring[PAGE + tid] = rb[0][1];
+        fetch(rb[0], PDEPTH);
     }
-    // fragment reads: lane reads row (lane & 31) of a 32-row block, chunk 2 s + (lane >> 5)
+
+    // fragment of a 32-row block: lane reads row (lane & 31), chunk (lane >> 5)
     const int frow = lane & 31;
-    const int fsw = (frow >> 1) & 3;
-    const int fch = lane >> 5;
-
-    u32x4 ra_h[2], ra_l[2], rb_h[2], rb_l[2];
-    auto issue = [&](int g) {
-        const int t = t0 + g / SL, kc = (g % SL) * (BK / 8);
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            int64_t r = (int64_t)t * BT + lrow[p];
-            if (r > a.N - 1) r = a.N - 1;
-            const int64_t ob = r * DC + (tid & 3) + kc;
-            ra_h[p] = a.Ah[offA[p] + kc];
-            ra_l[p] = a.Al[offA[p] + kc];
-            rb_h[p] = a.Bh[ob];
-            rb_l[p] = a.Bl[ob];
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            slab[buf][0][lpos[p]] = ra_h[p];
-            slab[buf][1][lpos[p]] = ra_l[p];
-            slab[buf][2][lpos[p]] = rb_h[p];
-            slab[buf][3][lpos[p]] = rb_l[p];
-        }
-    };
+    const int fpos = 2 * frow + ((lane >> 5) ^ ((frow >> 2) & 1));
+    const int fa0 = 2 * wm + fpos, fa1 = fa0 + 64; // + 32 rows
+    const int fb0 = 2 * wn + fpos, fb1 = fb0 + 64;
 
     float b1[2][16], b2[2][16];
 #pragma unroll
@@ -171,42 +181,43 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
     const uint32_t keep = ~((1u << a.idx_bits) - 1u);
 
     f32x16 acc[2][2];
-    __syncthreads();
-    auto reset_acc = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                // the row norm enters through the accumulator: -2 acc = ||a||^2 - 2 <a, b>
-                const float v = -0.5f * ran[wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)];
-                acc[i][0][r] = v;
-                acc[i][1][r] = v;
-            }
-    };
-    reset_acc();
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    if (total > 0) {
-        issue(0);
-        stash(0);
-    }
     __syncthreads();
-    for (int g = 0; g < total; ++g) {
-        const int cur = g & 1;
-        const bool more = g + 1 < total;
-        if (more) issue(g + 1);
+    for (int tl = 0; tl < ntl; ++tl) {
+        // column norms of this tile, asked for now and used after its last step
+        const int64_t n0 = (int64_t)(t0 + tl) * BT;
+        float cb[2];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            bf16x8 ah[2], al[2], bh[2], bl[2];
-            const int ch = ((2 * s + fch) ^ fsw);
+        for (int j = 0; j < 2; ++j) {
+            const int64_t col = n0 + wn + 32 * j + (lane & 31);
+            cb[j] = a.bn[min(col, (int64_t)a.N - 1)];
+            cb[j] = col < a.N ? cb[j] : BF16_NO_COLUMN;
+        }
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int ia = (wm + 32 * i + frow) * 4 + ch;
-                const int ib = (wn + 32 * i + frow) * 4 + ch;
-                ah[i] = __builtin_bit_cast(bf16x8, slab[cur][0][ia]);
-                al[i] = __builtin_bit_cast(bf16x8, slab[cur][1][ia]);
-                bh[i] = __builtin_bit_cast(bf16x8, slab[cur][2][ib]);
-                bl[i] = __builtin_bit_cast(bf16x8, slab[cur][3][ib]);
+        for (int u = 0; u < SPT; ++u) {
+            const int s = tl * SPT + u;
+            // page pair of step s + 1 into the other half of the ring, its registers refilled
+            {
+                u32x4 *dst = ring + ((u + 1) & 1) * 2 * PAGE;
+                dst[tid] = rb[(u + 1) % PDEPTH][0];
+                dst[PAGE + tid] = rb[(u + 1) % PDEPTH][1];
+                fetch(rb[(u + 1) % PDEPTH], s + 1 + PDEPTH);
             }
+            const u32x4 *ap = Apages + u * 2 * PAGE;
+            const u32x4 *bp = ring + (u & 1) * 2 * PAGE;
+            bf16x8 ah[2], bh[2], bl[2];
+            ah[0] = __builtin_bit_cast(bf16x8, ap[fa0]);
+            ah[1] = __builtin_bit_cast(bf16x8, ap[fa1]);
+            bh[0] = __builtin_bit_cast(bf16x8, bp[fb0]);
+            bh[1] = __builtin_bit_cast(bf16x8, bp[fb1]);
+            bl[0] = __builtin_bit_cast(bf16x8, bp[PAGE + fb0]);
+            bl[1] = __builtin_bit_cast(bf16x8, bp[PAGE + fb1]);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -218,50 +229,53 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
             if (use_lo) {
+                bf16x8 al[2];
+                al[0] = __builtin_bit_cast(bf16x8, ap[PAGE + fa0]);
+                al[1] = __builtin_bit_cast(bf16x8, ap[PAGE + fa1]);
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
             }
+            __syncthreads();
         }
-        if (more) stash(cur ^ 1);
-        __syncthreads();
-        if (g % SL == SL - 1) {
-            // tile finished: fold its 64 values per lane into the running two smallest per row slot
-            const int tl = g / SL; // tile index inside this split
-            const int64_t n0 = (int64_t)(t0 + tl) * BT;
+        // tile finished: fold e = ||b||^2 - 2 <a, b> (the row norm is common to a row and joins
+        // at the end) into the running two smallest of every row slot of the lane
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int64_t col = n0 + wn + 32 * j + (lane & 31);
-                const float cb = col < a.N ? a.bn[col] : BF16_NO_COLUMN;
-                const uint32_t tj = (uint32_t)(tl * 2 + j);
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t tj = (uint32_t)(tl * 2 + j);
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float e = fmaf(-2.f, acc[i][j][r], cb);
-                        const float key = __uint_as_float((__float_as_uint(e) & keep) | tj);
-                        b2[i][r] = __builtin_amdgcn_fmed3f(b1[i][r], b2[i][r], key);
-                        b1[i][r] = fminf(b1[i][r], key);
-                    }
-            }
-            reset_acc();
+                for (int r = 0; r < 16; ++r) {
+                    const float e = fmaf(-2.f, acc[i][j][r], cb[j]);
+                    const float key = __uint_as_float((__float_as_uint(e) & keep) | tj);
+                    b2[i][r] = __builtin_amdgcn_fmed3f(b1[i][r], b2[i][r], key);
+                    b1[i][r] = fminf(b1[i][r], key);
+                    acc[i][j][r] = 0.f;
+                }
         }
     }
 
     // ---- row minimum over the workgroup, then every kept key inside the band of it ----
-    auto clamp_bits = [&](float v) -> uint32_t {
-        const uint32_t u = __float_as_uint(v);
-        return (u & 0x80000000u) ? (u & ~keep) : u; // negative approximations count as zero
-    };
+    __syncthreads(); // the operand pages are dead from here on
+    unsigned *rowmin = (unsigned *)lds;                                         // [BT]
+    int *rowcnt = (int *)(rowmin + BT);                                         // [BT]
+    unsigned long long *rowcand = (unsigned long long *)(rowcnt + BT);          // [BT][VLQ_NN_CANDS]
+    if (tid < BT) {
+        rowmin[tid] = 0xFFFFFFFFu;
+        rowcnt[tid] = 0;
+#pragma unroll
+        for (int s = 0; s < VLQ_NN_CANDS; ++s) rowcand[tid * VLQ_NN_CANDS + s] = KEY_MAX;
+    }
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int rl = wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            const uint32_t u = clamp_bits(b1[i][r]);
-            if (u < BF16_INVALID_BITS) atomicMin(&rowmin[rl], u);
+            if (b1[i][r] < BF16_NO_KEY) atomicMin(&rowmin[rl], f2ord(b1[i][r]));
         }
     __syncthreads();
 #pragma unroll
@@ -269,22 +283,26 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int rl = wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            const uint32_t mn = rowmin[rl];
-            if (mn >= BF16_INVALID_BITS) continue;
-            const float dmin = __uint_as_float(mn & keep);
-            const float band = dmin + a.band_dist * dmin + BF16_BAND_NORM * (3.f * ran[rl] + 2.f * dmin);
+            const uint32_t mo = rowmin[rl];
+            if (mo == 0xFFFFFFFFu || m0 + rl >= a.M) continue;
+            const float ra = a.an[m0 + rl];
+            const float emin = __uint_as_float(__float_as_uint(ord2f(mo)) & keep);
+            const float dmin = fmaxf(emin + ra, 0.f);
+            const float band = emin + a.band_dist * (ra + dmin) + BF16_BAND_NORM * (3.f * ra + 2.f * dmin);
             const float ks[2] = {b1[i][r], b2[i][r]};
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const uint32_t u = clamp_bits(ks[s]);
-                if (u >= BF16_INVALID_BITS) continue;
-                const float d = __uint_as_float(u & keep);
-                if (d <= band) {
+                if (!(ks[s] < BF16_NO_KEY)) continue;
+                const uint32_t u = __float_as_uint(ks[s]);
+                const float e = __uint_as_float(u & keep);
+                if (e <= band) {
                     const uint32_t tj = u & ~keep;
                     const uint32_t col = (uint32_t)(t0 + (int)(tj >> 1)) * BT + wn + 32 * (tj & 1) + (lane & 31);
                     if (col >= (uint32_t)a.N) continue;
                     const int pos = atomicAdd(&rowcnt[rl], 1);
-                    if (pos < VLQ_NN_CANDS) rowcand[rl][pos] = ((uint64_t)(u & keep) << 32) | col;
+                    const float d = fmaxf(e + ra, 0.f) + 0.f;
+                    if (pos < VLQ_NN_CANDS)
+                        rowcand[rl * VLQ_NN_CANDS + pos] = ((uint64_t)__float_as_uint(d) << 32) | col;
                 }
             }
         }
@@ -292,20 +310,17 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
     if (tid < BT && m0 + tid < a.M) {
         uint64_t *dst = a.cand + ((m0 + tid) * a.nsplit + split) * VLQ_NN_CANDS;
 #pragma unroll
-        for (int s = 0; s < VLQ_NN_CANDS; ++s) dst[s] = rowcand[tid][s];
+        for (int s = 0; s < VLQ_NN_CANDS; ++s) dst[s] = rowcand[tid * VLQ_NN_CANDS + s];
     }
 }
 
-void launch_coarse_gemm_nn_bf16(const uint16_t *Ah, const uint16_t *Al, const int *a_any_lo, int M,
-                                const uint16_t *Bh, const uint16_t *Bl, int N, int D, const float *an,
-                                const float *bn, uint64_t *cand, int nsplit, float *band_norm,
-                                float *band_dist, hipStream_t st)
+int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, const void *Bimg, int N, int D,
+                               const float *an, const float *bn, uint64_t *cand, int nsplit, float *band_norm,
+                               float *band_dist, hipStream_t st)
 {
     Bf16NNArgs a;
-    a.Ah = (const u32x4 *)Ah;
-    a.Al = (const u32x4 *)Al;
-    a.Bh = (const u32x4 *)Bh;
-    a.Bl = (const u32x4 *)Bl;
+    a.A = (const u32x4 *)Aimg;
+    a.B = (const u32x4 *)Bimg;
     a.a_any_lo = a_any_lo;
     a.M = M;
     a.N = N;
@@ -319,12 +334,28 @@ void launch_coarse_gemm_nn_bf16(const uint16_t *Ah, const uint16_t *Al, const in
     int bits = 1;
     while ((1 << bits) < 2 * a.tiles_per_split) ++bits;
     a.idx_bits = bits;
-    // truncating the low mantissa bits moves a value by less than 2^(bits - 23) of itself;
-    // minimum and candidate both carry it
-    a.band_dist = 2.2f * ldexpf(1.f, bits - 23);
+    // planting the index moves a key by less than 2^(bits - 23) of its own size, and a key
+    // e = d - ||a||^2 is at most ||a||^2 + d in size; minimum and candidate both carry it
+    a.band_dist = 2.5f * ldexpf(1.f, bits - 23);
     *band_norm = BF16_BAND_NORM;
     *band_dist = a.band_dist;
-    if (M <= 0 || N <= 0) return;
+    if (M <= 0 || N <= 0) return 0;
+    const int spt = D / BSTEP;
+    const size_t lds_bytes = (size_t)(spt * 2 + 4) * PAGE * 16;
     dim3 grid((unsigned)((M + BT - 1) / BT), (unsigned)nsplit);
-    hipLaunchKernelGGL(k_coarse_nn_bf16, grid, dim3(256), 0, st, a);
+    auto go = [&](auto kern) -> int {
+        // more than 64 KB of dynamic LDS has to be asked for once per kernel
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_bytes);
+        if (e != hipSuccess) return (int)e;
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, st, a);
+        return 0;
+    };
+    switch (spt) {
+    case 2: return go(k_coarse_nn_bf16<2>);
+    case 4: return go(k_coarse_nn_bf16<4>);
+    case 6: return go(k_coarse_nn_bf16<6>);
+    case 8: return go(k_coarse_nn_bf16<8>);
+    }
+    return (int)hipErrorInvalidValue;
 }

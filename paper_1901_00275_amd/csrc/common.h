@@ -137,22 +137,24 @@ void launch_coarse_gemm_full(const float *A, int M, const float *B, int N, int D
 // up to VLQ_NN_CANDS keys (distance bits << 32 | column) per column split that lie
 // within the rounding band of the row minimum.  cand [M x nsplit x VLQ_NN_CANDS].
 #define VLQ_NN_CANDS 8
-// Width of the band as used by the fp32 product: band_norm * (3 ||a||^2 + 2 d) + band_dist * d.
+// Width of the band around the smallest distance d of a row a:
+// band_norm * (3 ||a||^2 + 2 d) + band_dist * (||a||^2 + d); the fp32 product has band_dist = 0.
 #define VLQ_FP32_BAND_NORM 4e-6f
 int coarse_gemm_nn_splits(int M, int N);
 void launch_coarse_gemm_nn(const float *A, int M, const float *B, int N, int D, const float *an,
                            const float *bn, uint64_t *cand, int nsplit, hipStream_t st);
 
-// The same shortlist from operands split into bf16 (hi, lo) pairs, on the bf16 matrix
-// cores (coarse_bf16.hip).  Requires coarse_bf16_supported(D).  The band the
-// consumer has to apply is returned in *band_norm / *band_dist.
+// The same shortlist on the bf16 matrix cores (coarse_bf16.hip).  Both operands are first
+// rewritten by launch_split_bf16 into an image of coarse_bf16_image_bytes(rows, D) bytes
+// (bf16 hi/lo pairs in the order the product kernel reads them).  Requires
+// coarse_bf16_supported(D).  The band the consumer has to apply is returned in
+// *band_norm / *band_dist; the return value is 0 or a hipError_t.
 bool coarse_bf16_supported(int D);
-void launch_split_bf16(const float *X, int64_t rows, int D, uint16_t *hi, uint16_t *lo, int *any_lo,
-                       hipStream_t st);
-void launch_coarse_gemm_nn_bf16(const uint16_t *Ah, const uint16_t *Al, const int *a_any_lo, int M,
-                                const uint16_t *Bh, const uint16_t *Bl, int N, int D, const float *an,
-                                const float *bn, uint64_t *cand, int nsplit, float *band_norm,
-                                float *band_dist, hipStream_t st);
+size_t coarse_bf16_image_bytes(int64_t rows, int D);
+void launch_split_bf16(const float *X, int64_t rows, int D, void *img, int *any_lo, hipStream_t st);
+int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, const void *Bimg, int N, int D,
+                               const float *an, const float *bn, uint64_t *cand, int nsplit, float *band_norm,
+                               float *band_dist, hipStream_t st);
 
 // w smallest entries of each row of dist [rows x k] (GEMM-form values), re-evaluated
 // as direct sums of squared differences and ordered by (distance, index).

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
         }
         mn = wave_min_u64(mn);
         const float dmin = __uint_as_float((uint32_t)(mn >> 32));
-        const float band = dmin + a.band_dist * dmin + a.band_norm * (3.f * xn + 2.f * dmin);
+        const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
         uint64_t bk = KEY_MAX;
         for (int c = 0; c < nc; ++c) {
             const uint64_t key = cd[c]; // same address in all lanes
