@@ -561,17 +561,32 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     if (nq == 0) return VLQ_OK;
     if (!d_q || !d_out_dist || !d_out_ids) return fail(VLQ_EINVAL, "d_q, d_out_dist and d_out_ids must not be NULL");
 
+    // cells from two sweeps of the bf16 product where the shape allows it (the environment can ask for
+    // the fp32 distance matrix instead, which the tests use to cover both)
+    const char *env = getenv("VLQ_COARSE_FP32");
+    int csplit = 0, ccap = 0;
+    const bool bf16 = idx->Cimg && !(env && env[0] == '1') && cells_bf16_plan(nq, k, D, w1, &csplit, &ccap);
     int64_t TQ = ((int64_t)512 << 20) / ((int64_t)4 * k);
     if (TQ < 128) TQ = 128;
     if (TQ > nq) TQ = nq;
     const int nsplit = scan_pick_nsplit(nq, w2, K);
 
     uint4 *desc;
+    uint8_t *qimg = nullptr, *cws = nullptr;
+    int32_t *qflag = nullptr;
+    size_t o0, o1, o2, o3;
     auto carve = [&](Bump &b, float **qn, float **dist, int32_t **cells, float **cell_dist, int32_t **slab,
                      float **sg, uint64_t **partial) {
         desc = b.take<uint4>((size_t)nq * w2);
         *qn = b.take<float>((size_t)nq);
-        *dist = b.take<float>((size_t)TQ * k);
+        if (bf16) {
+            *dist = nullptr;
+            qimg = b.take<uint8_t>(coarse_bf16_image_bytes(nq, D));
+            qflag = b.take<int32_t>(64);
+            cws = b.take<uint8_t>(cells_bf16_workspace(nq, csplit, ccap, &o0, &o1, &o2, &o3));
+        } else {
+            *dist = b.take<float>((size_t)TQ * k);
+        }
         *cells = b.take<int32_t>((size_t)nq * w1);
         *cell_dist = b.take<float>((size_t)nq * w1);
         *slab = b.take<int32_t>((size_t)nq * w2);
@@ -590,19 +605,35 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
 
     launch_row_norms(d_q, nq, D, qn, st);
     LAUNCHCHK();
-    for (int64_t q0 = 0; q0 < nq; q0 += TQ) {
-        const int rows = (int)(nq - q0 < TQ ? nq - q0 : TQ);
+    if (bf16) {
         {
             StageTimer t(idx, st, VLQ_STAGE_COARSE);
-            launch_coarse_gemm_full(d_q + q0 * D, rows, idx->C, k, D, qn + q0, idx->cn, dist, k, st);
+            launch_split_bf16(d_q, nq, D, qimg, qflag, st);
+            LAUNCHCHK();
+            HIPCHK((hipError_t)launch_cells_bf16_coarse(qimg, qflag, nq, idx->Cimg, k, D, qn, idx->cn, w1, csplit, ccap,
+                                                        cws, st));
         }
         LAUNCHCHK();
         {
             StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS);
-            launch_select_cells(dist, k, rows, k, d_q + q0 * D, D, qn + q0, idx->C, idx->cn, w1, -1,
-                                cells + q0 * w1, cell_dist + q0 * w1, st);
+            launch_cells_bf16_exact(d_q, nq, D, idx->C, k, w1, ccap, cws, csplit, cells, cell_dist, st);
         }
         LAUNCHCHK();
+    } else {
+        for (int64_t q0 = 0; q0 < nq; q0 += TQ) {
+            const int rows = (int)(nq - q0 < TQ ? nq - q0 : TQ);
+            {
+                StageTimer t(idx, st, VLQ_STAGE_COARSE);
+                launch_coarse_gemm_full(d_q + q0 * D, rows, idx->C, k, D, qn + q0, idx->cn, dist, k, st);
+            }
+            LAUNCHCHK();
+            {
+                StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS);
+                launch_select_cells(dist, k, rows, k, d_q + q0 * D, D, qn + q0, idx->C, idx->cn, w1, -1,
+                                    cells + q0 * w1, cell_dist + q0 * w1, st);
+            }
+            LAUNCHCHK();
+        }
     }
     {
         StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS);

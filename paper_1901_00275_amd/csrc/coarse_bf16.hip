@@ -109,22 +109,40 @@ void launch_split_bf16(const float *X, int64_t rows, int D, void *img, int *any_
 #define BF16_NO_COLUMN 3e38f
 #define BF16_NO_KEY 1e38f
 
-struct Bf16NNArgs {
+// What the product kernel does with a finished 128 x 128 tile of e = ||b||^2 - 2 <a, b>
+// (the row norm is common to a row and joins at the end):
+//  MODE_NN    running two smallest per row slot of every lane; at the end every kept key inside
+//             the band of the row minimum is emitted (encoding: nearest centroid);
+//  MODE_MIN   running minimum per row slot of every lane, written out as 64 group minima per
+//             (row, split) (search, first sweep);
+//  MODE_EMIT  every column with e <= thr[row] is appended to the row's candidate list
+//             (search, second sweep).
+enum { MODE_NN = 0, MODE_MIN = 1, MODE_EMIT = 2 };
+
+struct Bf16Args {
     const u32x4 *A; // image of the rows
     const u32x4 *B; // image of the columns
     const int *a_any_lo;
     int M, N, D;
     const float *an, *bn;
-    uint64_t *cand;
     int nsplit, tiles_per_split;
+    // MODE_NN
+    uint64_t *cand;
     int idx_bits; // low mantissa bits of a running key that hold (tile, column block)
     float band_dist;
+    // MODE_MIN
+    float *gmin; // [M x nsplit x 64]
+    // MODE_EMIT
+    const float *thr; // [M]
+    int32_t *ccnt;    // [M]
+    int32_t *cidx;    // [M x cap]
+    int cap;
 };
 
 // SPT = D / 16 steps per tile; PDEPTH page pairs of B in flight in registers (divides SPT, so
 // that every register set and ring half has a fixed role in the unrolled tile body).
-template <int SPT>
-__global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
+template <int SPT, int MODE>
+__global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
 {
     constexpr int PDEPTH = SPT % 4 == 0 ? 4 : (SPT % 3 == 0 ? 3 : 2);
     static_assert(SPT % 2 == 0 && SPT % PDEPTH == 0, "steps per tile");
@@ -172,13 +190,24 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
     const int fpos = 2 * frow + ((lane >> 5) ^ ((frow >> 2) & 1));
     const int fa0 = 2 * wm + fpos, fa1 = fa0 + 64; // + 32 rows
     const int fb0 = 2 * wn + fpos, fb1 = fb0 + 64;
+    // accumulator register r of block i holds row wm + 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4
+    auto slot_row = [&](int i, int r) { return wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); };
 
-    float b1[2][16], b2[2][16];
+    // per row slot: MODE_NN smallest / second smallest key, MODE_MIN minimum, MODE_EMIT threshold
+    float b1[2][16], b2[MODE == MODE_NN ? 2 : 1][16];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) b1[i][r] = b2[i][r] = INFINITY;
-    const uint32_t keep = ~((1u << a.idx_bits) - 1u);
+        for (int r = 0; r < 16; ++r) {
+            if (MODE == MODE_EMIT) {
+                const int64_t row = m0 + slot_row(i, r);
+                b1[i][r] = row < a.M ? a.thr[row] : -INFINITY;
+            } else {
+                b1[i][r] = INFINITY;
+                if (MODE == MODE_NN) b2[i][r] = INFINITY;
+            }
+        }
+    const uint32_t keep = MODE == MODE_NN ? ~((1u << a.idx_bits) - 1u) : 0xFFFFFFFFu;
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -240,8 +269,8 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
             }
             __syncthreads();
         }
-        // tile finished: fold e = ||b||^2 - 2 <a, b> (the row norm is common to a row and joins
-        // at the end) into the running two smallest of every row slot of the lane
+        // ---- tile finished ----
+        uint64_t hits = 0; // MODE_EMIT: bit (2 j + i) * 16 + r
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t tj = (uint32_t)(tl * 2 + j);
@@ -250,15 +279,45 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float e = fmaf(-2.f, acc[i][j][r], cb[j]);
-                    const float key = __uint_as_float((__float_as_uint(e) & keep) | tj);
-                    b2[i][r] = __builtin_amdgcn_fmed3f(b1[i][r], b2[i][r], key);
-                    b1[i][r] = fminf(b1[i][r], key);
+                    if (MODE == MODE_NN) {
+                        const float key = __uint_as_float((__float_as_uint(e) & keep) | tj);
+                        b2[i][r] = __builtin_amdgcn_fmed3f(b1[i][r], b2[i][r], key);
+                        b1[i][r] = fminf(b1[i][r], key);
+                    } else if (MODE == MODE_MIN) {
+                        b1[i][r] = fminf(b1[i][r], e);
+                    } else {
+                        hits |= e <= b1[i][r] ? 1ull << ((2 * j + i) * 16 + r) : 0ull;
+                    }
                     acc[i][j][r] = 0.f;
                 }
         }
+        if (MODE == MODE_EMIT) {
+            while (hits) {
+                const int bit = __ffsll((unsigned long long)hits) - 1;
+                hits &= hits - 1;
+                const int j = bit >> 5, i = (bit >> 4) & 1, r = bit & 15;
+                const int64_t row = m0 + slot_row(i, r);
+                const int col = (int)n0 + wn + 32 * j + (lane & 31);
+                const int pos = atomicAdd(&a.ccnt[row], 1);
+                if (pos < a.cap) a.cidx[row * a.cap + pos] = col;
+            }
+        }
     }
 
-    // ---- row minimum over the workgroup, then every kept key inside the band of it ----
+    if (MODE == MODE_EMIT) return;
+    if (MODE == MODE_MIN) {
+        // 64 group minima per (row, split): column class (lane & 31) of each column half
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = m0 + slot_row(i, r);
+                if (row < a.M) a.gmin[(row * a.nsplit + split) * 64 + (wn >> 6) * 32 + (lane & 31)] = b1[i][r];
+            }
+        return;
+    }
+
+    // ---- MODE_NN: row minimum over the workgroup, then every kept key inside the band of it ----
     __syncthreads(); // the operand pages are dead from here on
     unsigned *rowmin = (unsigned *)lds;                                         // [BT]
     int *rowcnt = (int *)(rowmin + BT);                                         // [BT]
@@ -273,23 +332,21 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int rl = wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (b1[i][r] < BF16_NO_KEY) atomicMin(&rowmin[rl], f2ord(b1[i][r]));
-        }
+        for (int r = 0; r < 16; ++r)
+            if (b1[i][r] < BF16_NO_KEY) atomicMin(&rowmin[slot_row(i, r)], f2ord(b1[i][r]));
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int rl = wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            const int rl = slot_row(i, r);
             const uint32_t mo = rowmin[rl];
             if (mo == 0xFFFFFFFFu || m0 + rl >= a.M) continue;
             const float ra = a.an[m0 + rl];
             const float emin = __uint_as_float(__float_as_uint(ord2f(mo)) & keep);
             const float dmin = fmaxf(emin + ra, 0.f);
             const float band = emin + a.band_dist * (ra + dmin) + BF16_BAND_NORM * (3.f * ra + 2.f * dmin);
-            const float ks[2] = {b1[i][r], b2[i][r]};
+            const float ks[2] = {b1[i][r], b2[MODE == MODE_NN ? i : 0][r]};
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 if (!(ks[s] < BF16_NO_KEY)) continue;
@@ -314,11 +371,36 @@ __global__ __launch_bounds__(256, 2) void k_coarse_nn_bf16(Bf16NNArgs a)
     }
 }
 
+template <int MODE>
+static int launch_mode(Bf16Args &a, hipStream_t st)
+{
+    const int ntiles = (a.N + BT - 1) / BT;
+    a.tiles_per_split = (ntiles + a.nsplit - 1) / a.nsplit;
+    const int spt = a.D / BSTEP;
+    const size_t lds_bytes = (size_t)(spt * 2 + 4) * PAGE * 16;
+    dim3 grid((unsigned)((a.M + BT - 1) / BT), (unsigned)a.nsplit);
+    auto go = [&](auto kern) -> int {
+        // more than 64 KB of dynamic LDS has to be asked for
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_bytes);
+        if (e != hipSuccess) return (int)e;
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, st, a);
+        return 0;
+    };
+    switch (spt) {
+    case 2: return go(k_coarse_bf16<2, MODE>);
+    case 4: return go(k_coarse_bf16<4, MODE>);
+    case 6: return go(k_coarse_bf16<6, MODE>);
+    case 8: return go(k_coarse_bf16<8, MODE>);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
 int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, const void *Bimg, int N, int D,
                                const float *an, const float *bn, uint64_t *cand, int nsplit, float *band_norm,
                                float *band_dist, hipStream_t st)
 {
-    Bf16NNArgs a;
+    Bf16Args a = {};
     a.A = (const u32x4 *)Aimg;
     a.B = (const u32x4 *)Bimg;
     a.a_any_lo = a_any_lo;
@@ -330,9 +412,9 @@ int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, con
     a.cand = cand;
     a.nsplit = nsplit;
     const int ntiles = (N + BT - 1) / BT;
-    a.tiles_per_split = (ntiles + nsplit - 1) / nsplit;
+    const int per = (ntiles + nsplit - 1) / nsplit;
     int bits = 1;
-    while ((1 << bits) < 2 * a.tiles_per_split) ++bits;
+    while ((1 << bits) < 2 * per) ++bits;
     a.idx_bits = bits;
     // planting the index moves a key by less than 2^(bits - 23) of its own size, and a key
     // e = d - ||a||^2 is at most ||a||^2 + d in size; minimum and candidate both carry it
@@ -340,22 +422,205 @@ int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, con
     *band_norm = BF16_BAND_NORM;
     *band_dist = a.band_dist;
     if (M <= 0 || N <= 0) return 0;
-    const int spt = D / BSTEP;
-    const size_t lds_bytes = (size_t)(spt * 2 + 4) * PAGE * 16;
-    dim3 grid((unsigned)((M + BT - 1) / BT), (unsigned)nsplit);
-    auto go = [&](auto kern) -> int {
-        // more than 64 KB of dynamic LDS has to be asked for once per kernel
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds_bytes);
-        if (e != hipSuccess) return (int)e;
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, st, a);
-        return 0;
-    };
-    switch (spt) {
-    case 2: return go(k_coarse_nn_bf16<2>);
-    case 4: return go(k_coarse_nn_bf16<4>);
-    case 6: return go(k_coarse_nn_bf16<6>);
-    case 8: return go(k_coarse_nn_bf16<8>);
+    return launch_mode<MODE_NN>(a, st);
+}
+
+// ---------------------------------------------------------------------------
+// w1 nearest centroids of every query (Alg. 3, first loop) without the nq x k matrix.
+//
+// Sweep 1 leaves 64 * nsplit group minima per query; the want-th smallest of them, tau, has at
+// least want columns at or below it, so it bounds the want-th smallest approximate value from
+// above, and it is tight: the want smallest columns rarely share a group.  Sweep 2 recomputes
+// the product and lists every column with e <= tau + band, where the band covers the error of
+// both sweeps' values against the exact distances.  The listed columns (about want of them)
+// get their distance again as direct fp32 sums of squared differences and are sorted by
+// (distance, index): the first w1 are the cells, exactly as a full exact ranking would give.
+// A query whose list overflows (masses of coinciding distances) is ranked exactly over all
+// columns instead.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict__ gmin, int G, int want,
+                                                        const float *__restrict__ qn, float *__restrict__ thr,
+                                                        int32_t *__restrict__ ccnt)
+{
+    extern __shared__ uint64_t tkeys[]; // [next_pow2(G)]
+    const int tid = threadIdx.x, row = blockIdx.x;
+    const int sz = next_pow2_dev(G);
+    for (int i = tid; i < sz; i += 256) tkeys[i] = i < G ? (uint64_t)f2ord(gmin[(int64_t)row * G + i]) : KEY_MAX;
+    __syncthreads();
+    block_bitonic_sort<256>(tkeys, sz, tid);
+    if (tid == 0) {
+        const float tau = ord2f((uint32_t)tkeys[want - 1]);
+        const float ra = qn[row];
+        const float dt = fmaxf(tau + ra, 0.f);
+        // below BF16_NO_KEY, so that columns past the end never qualify
+        thr[row] = fminf(tau + BF16_BAND_NORM * (3.f * ra + 2.f * dt), BF16_NO_KEY);
+        ccnt[row] = 0;
     }
-    return (int)hipErrorInvalidValue;
+}
+
+// direct ||y - c||^2 by 16 lanes (l16 = lane % 16), butterfly over the 16: same value in all of them
+__device__ __forceinline__ float sqdist16(const float *yv, const float *__restrict__ rowp, int D, int l16, bool vec)
+{
+    float acc = 0.f;
+    if (vec) {
+        for (int d = l16 * 4; d < D; d += 64) {
+            const f32x4 cv = *(const f32x4 *)(rowp + d);
+            const float t0 = yv[d] - cv.x, t1 = yv[d + 1] - cv.y, t2 = yv[d + 2] - cv.z, t3 = yv[d + 3] - cv.w;
+            acc = fmaf(t0, t0, acc);
+            acc = fmaf(t1, t1, acc);
+            acc = fmaf(t2, t2, acc);
+            acc = fmaf(t3, t3, acc);
+        }
+    } else {
+        for (int d = l16; d < D; d += 16) {
+            const float t = yv[d] - rowp[d];
+            acc = fmaf(t, t, acc);
+        }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    return acc;
+}
+
+#define CELLS_FB 2048 // buffer of the exact ranking over all columns
+
+__global__ __launch_bounds__(256) void k_cells_exact(const float *__restrict__ Q, int D,
+                                                     const float *__restrict__ C, int k,
+                                                     const int32_t *__restrict__ ccnt,
+                                                     const int32_t *__restrict__ cidx, int cap, int w,
+                                                     int32_t *__restrict__ cells, float *__restrict__ cell_dist)
+{
+    extern __shared__ uint64_t ckeys[]; // [max(cap, CELLS_FB)] then yv [D]
+    __shared__ int sh_n;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub16 = lane >> 4, l16 = lane & 15;
+    const int row = blockIdx.x;
+    const int nkeys = cap > CELLS_FB ? cap : CELLS_FB;
+    float *yv = (float *)(ckeys + nkeys);
+    for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)row * D + d];
+    const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
+    const int listed = ccnt[row];
+    int cnt;
+    __syncthreads();
+    if (listed <= cap) {
+        cnt = listed;
+        for (int c0 = wave * 4; c0 < cnt; c0 += 16) {
+            const int c = c0 + sub16;
+            const int i = c < cnt ? cidx[(int64_t)row * cap + c] : 0;
+            const float d = sqdist16(yv, C + (int64_t)i * D, D, l16, vec);
+            if (l16 == 0 && c < cnt) ckeys[c] = make_key(d, (uint32_t)i);
+        }
+        const int sz = next_pow2_dev(cnt);
+        for (int c = cnt + tid; c < sz; c += 256) ckeys[c] = KEY_MAX;
+        __syncthreads();
+        block_bitonic_sort<256>(ckeys, sz, tid);
+    } else {
+        // exact ranking over all columns: keys below the current w-th smallest are collected;
+        // a full buffer is sorted and cut back to w
+        uint64_t cut = KEY_MAX;
+        if (tid == 0) sh_n = 0;
+        __syncthreads();
+        for (int i0 = 0; i0 < k; i0 += 16) {
+            const int i = i0 + wave * 4 + sub16;
+            const float d = sqdist16(yv, C + (int64_t)min(i, k - 1) * D, D, l16, vec);
+            const uint64_t key = make_key(d, (uint32_t)i);
+            if (l16 == 0 && i < k && key < cut) ckeys[atomicAdd(&sh_n, 1)] = key;
+            __syncthreads();
+            const int n = sh_n;
+            __syncthreads(); // everyone has read the fill level before the next round appends
+            if (n > CELLS_FB - 16 || i0 + 16 >= k) {
+                const int sz = next_pow2_dev(n);
+                for (int c = n + tid; c < sz; c += 256) ckeys[c] = KEY_MAX;
+                __syncthreads();
+                block_bitonic_sort<256>(ckeys, sz, tid);
+                if (n >= w) cut = ckeys[w - 1];
+                __syncthreads();
+                if (tid == 0) sh_n = min(n, w);
+                __syncthreads();
+            }
+        }
+        cnt = sh_n;
+    }
+    for (int e = tid; e < w; e += 256) {
+        const uint64_t key = ckeys[e];
+        const bool ok = e < cnt && key != KEY_MAX;
+        cells[(int64_t)row * w + e] = ok ? (int32_t)(uint32_t)key : -1;
+        if (cell_dist) cell_dist[(int64_t)row * w + e] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+    }
+}
+
+bool cells_bf16_plan(int nq, int k, int D, int w1, int *nsplit, int *cap)
+{
+    if (!coarse_bf16_supported(D)) return false;
+    const int ntiles = (k + BT - 1) / BT;
+    const int strips = (nq + BT - 1) / BT;
+    int ns = 512 / strips; // one round of two workgroups per CU
+    const int need = (2 * w1 + 63) / 64; // at least twice as many groups as cells wanted
+    if (ns < need) ns = need;
+    if (ns > 64) ns = 64;
+    if (ns > ntiles / 2) ns = ntiles / 2; // every group sees at least two tiles
+    if (ns < 1 || ns < need) return false;
+    const int per = (ntiles + ns - 1) / ns;
+    ns = (ntiles + per - 1) / per; // no empty split
+    if (ns < need) return false;
+    *nsplit = ns;
+    *cap = next_pow2(4 * w1 > 256 ? 4 * w1 : 256);
+    return true;
+}
+
+size_t cells_bf16_workspace(int nq, int nsplit, int cap, size_t *gmin_off, size_t *thr_off, size_t *ccnt_off,
+                            size_t *cidx_off)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        off = (off + 255) & ~(size_t)255;
+        const size_t at = off;
+        off += bytes;
+        return at;
+    };
+    *gmin_off = take((size_t)nq * nsplit * 64 * 4);
+    *thr_off = take((size_t)nq * 4);
+    *ccnt_off = take((size_t)nq * 4);
+    *cidx_off = take((size_t)nq * cap * 4);
+    return off;
+}
+
+int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, const void *Cimg, int k, int D,
+                             const float *qn, const float *cn, int w1, int nsplit, int cap, void *ws, hipStream_t st)
+{
+    size_t og, ot, oc, oi;
+    cells_bf16_workspace(nq, nsplit, cap, &og, &ot, &oc, &oi);
+    char *base = (char *)ws;
+    Bf16Args a = {};
+    a.A = (const u32x4 *)Qimg;
+    a.B = (const u32x4 *)Cimg;
+    a.a_any_lo = q_any_lo;
+    a.M = nq;
+    a.N = k;
+    a.D = D;
+    a.an = qn;
+    a.bn = cn;
+    a.nsplit = nsplit;
+    a.gmin = (float *)(base + og);
+    a.thr = (float *)(base + ot);
+    a.ccnt = (int32_t *)(base + oc);
+    a.cidx = (int32_t *)(base + oi);
+    a.cap = cap;
+    int rc = launch_mode<MODE_MIN>(a, st);
+    if (rc) return rc;
+    const int G = nsplit * 64;
+    hipLaunchKernelGGL(k_cell_threshold, dim3((unsigned)nq), dim3(256), (size_t)next_pow2(G) * 8, st, a.gmin, G, w1,
+                       qn, (float *)(base + ot), a.ccnt);
+    return launch_mode<MODE_EMIT>(a, st);
+}
+
+void launch_cells_bf16_exact(const float *Q, int nq, int D, const float *C, int k, int w1, int cap, const void *ws,
+                             int nsplit, int32_t *cells, float *cell_dist, hipStream_t st)
+{
+    size_t og, ot, oc, oi;
+    cells_bf16_workspace(nq, nsplit, cap, &og, &ot, &oc, &oi);
+    const char *base = (const char *)ws;
+    const int nkeys = cap > CELLS_FB ? cap : CELLS_FB;
+    hipLaunchKernelGGL(k_cells_exact, dim3((unsigned)nq), dim3(256), (size_t)nkeys * 8 + (size_t)D * 4, st, Q, D, C, k,
+                       (const int32_t *)(base + oc), (const int32_t *)(base + oi), cap, w1, cells, cell_dist);
 }

@@ -156,6 +156,19 @@ int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, con
                                const float *an, const float *bn, uint64_t *cand, int nsplit, float *band_norm,
                                float *band_dist, hipStream_t st);
 
+// w1 nearest centroids of every query from two sweeps of the bf16 product, without the nq x k
+// matrix (coarse_bf16.hip).  cells_bf16_plan says whether the shape allows it and fixes the
+// split count and the candidate capacity per query; the workspace holds group minima,
+// thresholds, candidate counts and candidate lists.  launch_cells_bf16_coarse runs both sweeps
+// (return value 0 or a hipError_t), launch_cells_bf16_exact ranks the candidates exactly.
+bool cells_bf16_plan(int nq, int k, int D, int w1, int *nsplit, int *cap);
+size_t cells_bf16_workspace(int nq, int nsplit, int cap, size_t *gmin_off, size_t *thr_off, size_t *ccnt_off,
+                            size_t *cidx_off);
+int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, const void *Cimg, int k, int D,
+                             const float *qn, const float *cn, int w1, int nsplit, int cap, void *ws, hipStream_t st);
+void launch_cells_bf16_exact(const float *Q, int nq, int D, const float *C, int k, int w1, int cap, const void *ws,
+                             int nsplit, int32_t *cells, float *cell_dist, hipStream_t st);
+
 // w smallest entries of each row of dist [rows x k] (GEMM-form values), re-evaluated
 // as direct sums of squared differences and ordered by (distance, index).
 // self0 >= 0: row r must not select column self0 + r (graph construction).

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from parity import DTOL, GAP, check_selection, check_topk
-from util import problem
+from util import Problem, problem
 
 pytestmark = pytest.mark.gpu
 
@@ -207,6 +207,37 @@ def test_encode_with_both_coarse_products(vlq, oracle_mod, monkeypatch, kind, fp
     try:
         S, E = oracle_mod.graph(pr.C, pr.n)
         check_encode(oracle_mod, pr, S, E, pr.X, gpu_encode(vlq, idx, pr.X, pr.m))
+    finally:
+        vlq.vlq_index_free(idx)
+
+
+@pytest.mark.parametrize("dup,fp32", [(0, False), (600, False), (0, True)])
+def test_cell_selection_with_many_centroids(vlq, oracle_mod, monkeypatch, dup, fp32):
+    """Alg. 3, first loop, at a codebook size where the cells come from the two sweeps of the bf16
+    product (and, for comparison, from the fp32 distance matrix).  With `dup` coinciding centroids
+    the candidate lists of the queries near them overflow and the exact ranking over all centroids
+    takes over; ties go to the smaller index."""
+    if fp32:
+        monkeypatch.setenv("VLQ_COARSE_FP32", "1")
+    pr = problem(N=4000, k=1024, n=4, m=8, G=64, nq=300, D=32, iters=2)
+    C = pr.C.copy()
+    if dup:
+        C[100:100 + dup] = C[100]
+    pr2 = Problem(pr.kind, pr.X, pr.Y, C, pr.P, pr.n)
+    Y = pr.Y.copy()
+    if dup:
+        Y[:20] = C[100] + np.arange(20, dtype=np.float32)[:, None]  # queries that see the whole tie
+    idx = make_index(vlq, pr2, base=pr.X[:500])
+    try:
+        for w1 in (1, 7, 32):
+            od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y, w1, min(w1 * pr.n, 16), 10)
+            dist = oracle_mod.coarse(C, Y)
+            for q in range(len(Y)):
+                check_selection(cells[q], dict(enumerate(dist[q])), w1, what=f"w1 {w1} query {q} cells")
+                assert np.allclose(cd[q], dist[q][cells[q]], rtol=DTOL, atol=1e-3)
+            if dup:
+                ref = oracle_mod.select_smallest(dist[:20], w1)
+                assert (cells[:20] == ref).all()  # exact ties are ordered by index
     finally:
         vlq.vlq_index_free(idx)
 
