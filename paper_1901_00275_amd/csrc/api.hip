@@ -572,8 +572,10 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     const int nsplit = scan_pick_nsplit(nq, w2, K);
 
     uint4 *desc;
-    uint8_t *qimg = nullptr, *cws = nullptr;
+    uint8_t *qimg = nullptr, *cws = nullptr, *nws = nullptr;
     int32_t *qflag = nullptr;
+    const char *env2 = getenv("VLQ_NEIGHBOURS_PER_QUERY");
+    const bool by_cell = neighbour_dists_by_cell(nq, k, n, D, w1) && !(env2 && env2[0] == '1');
     size_t o0, o1, o2, o3;
     auto carve = [&](Bump &b, float **qn, float **dist, int32_t **cells, float **cell_dist, int32_t **slab,
                      float **sg, uint64_t **partial) {
@@ -587,6 +589,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
         } else {
             *dist = b.take<float>((size_t)TQ * k);
         }
+        if (by_cell) nws = b.take<uint8_t>(neighbour_dists_workspace(nq, k, n, w1));
         *cells = b.take<int32_t>((size_t)nq * w1);
         *cell_dist = b.take<float>((size_t)nq * w1);
         *slab = b.take<int32_t>((size_t)nq * w2);
@@ -635,12 +638,6 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
             LAUNCHCHK();
         }
     }
-    {
-        StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS);
-        launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, cells, cell_dist, w1, w2, d_sub, d_sub_score, slab,
-                          sg, idx->off, desc, st);
-    }
-    LAUNCHCHK();
     ScanArgs a;
     a.Q = d_q;
     a.nq = nq;
@@ -667,6 +664,14 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     a.partial = partial;
     a.out_dist = d_out_dist;
     a.out_ids = d_out_ids;
+    {
+        StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS);
+        // the streaming scan takes the visited sub-regions from desc alone, in any order
+        const bool stream = scan_will_stream(a);
+        launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, k, cells, cell_dist, w1, w2, d_sub, d_sub_score,
+                          stream ? nullptr : slab, stream ? nullptr : sg, idx->off, desc, nws, st);
+    }
+    LAUNCHCHK();
     {
         StageTimer t(idx, st, VLQ_STAGE_SCAN);
         launch_scan(a, st);

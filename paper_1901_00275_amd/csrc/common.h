@@ -178,10 +178,15 @@ void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const f
 
 // Line scores of the w1*n sub-regions of the probed cells and the w2 best of them.
 // desc (optional): per visited sub-region {list begin, list length, a, b - a} for the streaming scan.
+// ws (optional, neighbour_dists_workspace() bytes): the distances to the neighbour centroids are
+// then computed cell by cell over the whole batch first; neighbour_dists_by_cell() says when
+// that pays.
+bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1);
+size_t neighbour_dists_workspace(int nq, int k, int n, int w1);
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
-                       int n, const int32_t *cells, const float *cell_dist, int w1, int w2,
+                       int n, int k, const int32_t *cells, const float *cell_dist, int w1, int w2,
                        int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       const int64_t *off, uint4 *desc, hipStream_t st);
+                       const int64_t *off, uint4 *desc, void *ws, hipStream_t st);
 
 struct ScanArgs {
     const float *Q;
@@ -205,6 +210,7 @@ struct ScanArgs {
 };
 void launch_scan(const ScanArgs &a, hipStream_t st);
 bool scan_stream_supported(const ScanArgs &a);
+bool scan_will_stream(const ScanArgs &a); // the choice launch_scan is going to make
 void launch_scan_stream(const ScanArgs &a, hipStream_t st);
 void launch_merge(const uint64_t *partial, int nq, int nsplit, int K, float *out_dist, int32_t *out_ids,
                   hipStream_t st);

@@ -15,6 +15,16 @@
 // sub-regions of one cell are adjacent, with g = <y-c_i, s_ij-c_i> = (a+c-b)/2
 // for the scan.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ int wave_incl_scan(int v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
 __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q, int D,
                                                     const float *__restrict__ C,
                                                     const int32_t *__restrict__ S,
@@ -26,7 +36,8 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                                                     int32_t *__restrict__ scan_label,
                                                     float *__restrict__ scan_g,
                                                     const int64_t *__restrict__ off,
-                                                    uint4 *__restrict__ desc)
+                                                    uint4 *__restrict__ desc,
+                                                    const float *__restrict__ bpre)
 {
     extern __shared__ unsigned char smem[];
     uint64_t *keys = (uint64_t *)smem;          // [sz]
@@ -38,80 +49,193 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
     const int total = w1 * n;
 
     int *nbr = (int *)(pos + sz);                // [sz] neighbour centroid of every sub-region
+    __shared__ int hist[256];
+    __shared__ int sh4[4];
+    __shared__ int sh_bin, sh_before, sh_inbin;
 
     for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)q * D + d];
-    for (int t = tid; t < total; t += 256) {
+    if (!bpre)
+        for (int t = tid; t < total; t += 256) {
+            const int e = t / n, j = t - e * n;
+            const int i = cells[(int64_t)q * w1 + e];
+            nbr[t] = i >= 0 ? S[(int64_t)i * n + j] : -1;
+        }
+    __syncthreads();
+
+    // Line score of sub-region t = (probed cell e, edge j) from b = ||y - s_ij||^2: lambda by
+    // Eq. 13, squared distance to the line a - c lambda^2 (Eq. 7 at that lambda)
+    auto put_score = [&](int t, float b) {
         const int e = t / n, j = t - e * n;
         const int i = cells[(int64_t)q * w1 + e];
-        nbr[t] = i >= 0 ? S[(int64_t)i * n + j] : -1;
+        uint64_t key = KEY_MAX;
+        if (i >= 0) {
+            const float a = cell_dist[(int64_t)q * w1 + e];
+            const float c = E[(int64_t)i * n + j];
+            const float lam = c > 0.f ? 0.5f * (a + c - b) / c : 0.f;
+            const float score = a - c * lam * lam;
+            key = make_key(score, (uint32_t)(i * n + j));
+        }
+        keys[t] = key;
+        bval[t] = b;
+        pos[t] = (uint16_t)t;
+    };
+    if (bpre) {
+        // the distances were computed cell by cell beforehand (k_neighbour_dists)
+        for (int t = tid; t < total; t += 256) put_score(t, bpre[(int64_t)q * total + t]);
+    } else {
+        // b = ||y - s_ij||^2 for all w1*n sub-regions: 16 lanes per centroid row, 4 rows per wave
+        // instruction, 16 rows in flight per wave (the rows are scattered over the codebook, so
+        // the loop lives on memory-level parallelism).  The order of the additions is fixed.
+        const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
+        const int sub16 = lane >> 4, l16 = lane & 15;
+        for (int t0 = wave * 16; t0 < total; t0 += 64) {
+            float part[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int t = t0 + g * 4 + sub16;
+                const int s = t < total ? nbr[t] : -1;
+                float acc = 0.f;
+                if (s >= 0) {
+                    const float *row = C + (int64_t)s * D;
+                    if (vec) {
+                        for (int d = l16 * 4; d < D; d += 64) {
+                            const f32x4 cv = *(const f32x4 *)(row + d);
+                            const float t0v = yv[d] - cv.x, t1v = yv[d + 1] - cv.y, t2v = yv[d + 2] - cv.z,
+                                        t3v = yv[d + 3] - cv.w;
+                            acc = fmaf(t0v, t0v, acc);
+                            acc = fmaf(t1v, t1v, acc);
+                            acc = fmaf(t2v, t2v, acc);
+                            acc = fmaf(t3v, t3v, acc);
+                        }
+                    } else {
+                        for (int d = l16; d < D; d += 16) {
+                            const float tv = yv[d] - row[d];
+                            acc = fmaf(tv, tv, acc);
+                        }
+                    }
+                }
+                part[g] = acc;
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) part[g] += __shfl_xor(part[g], o, 64);
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int t = t0 + g * 4 + sub16;
+                if (l16 == 0 && t < total) put_score(t, part[g]);
+            }
+        }
     }
     __syncthreads();
 
-    // b = ||y - s_ij||^2 for all w1*n sub-regions: 16 lanes per centroid row, 4 rows per wave
-    // instruction, 16 rows in flight per wave (the rows are scattered over the codebook, so
-    // the loop lives on memory-level parallelism).  The order of the additions is fixed.
-    const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
-    const int sub16 = lane >> 4, l16 = lane & 15;
-    for (int t0 = wave * 16; t0 < total; t0 += 64) {
-        float part[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int t = t0 + g * 4 + sub16;
-            const int s = t < total ? nbr[t] : -1;
-            float acc = 0.f;
-            if (s >= 0) {
-                const float *row = C + (int64_t)s * D;
-                if (vec) {
-                    for (int d = l16 * 4; d < D; d += 64) {
-                        const f32x4 cv = *(const f32x4 *)(row + d);
-                        const float t0v = yv[d] - cv.x, t1v = yv[d + 1] - cv.y, t2v = yv[d + 2] - cv.z,
-                                    t3v = yv[d + 3] - cv.w;
-                        acc = fmaf(t0v, t0v, acc);
-                        acc = fmaf(t1v, t1v, acc);
-                        acc = fmaf(t2v, t2v, acc);
-                        acc = fmaf(t3v, t3v, acc);
-                    }
-                } else {
-                    for (int d = l16; d < D; d += 16) {
-                        const float tv = yv[d] - row[d];
-                        acc = fmaf(tv, tv, acc);
-                    }
-                }
-            }
-            part[g] = acc;
-        }
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) part[g] += __shfl_xor(part[g], o, 64);
-        }
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int t = t0 + g * 4 + sub16;
-            if (l16 == 0 && t < total) {
-                const int e = t / n, j = t - e * n;
-                const int i = cells[(int64_t)q * w1 + e];
-                uint64_t key = KEY_MAX;
-                const float b = part[g];
-                if (i >= 0) {
-                    const float a = cell_dist[(int64_t)q * w1 + e];
-                    const float c = E[(int64_t)i * n + j];
-                    const float lam = c > 0.f ? 0.5f * (a + c - b) / c : 0.f;
-                    const float score = a - c * lam * lam;
-                    key = make_key(score, (uint32_t)(i * n + j));
-                }
-                keys[t] = key;
-                bval[t] = b;
-                pos[t] = (uint16_t)t;
-            }
-        }
-    }
-    for (int t = total + tid; t < sz; t += 256) {
-        keys[t] = KEY_MAX;
-        pos[t] = 0;
-    }
+    // ---- the w2 smallest (score, label) keys: radix select of the cut key, then compaction ----
+    int *selpos = nbr; // [w2] positions of the selected sub-regions (the neighbour ids are dead by now)
+    int nvalid = 0;
+    for (int t = tid; t < total; t += 256) nvalid += keys[t] != KEY_MAX;
+    nvalid = wave_incl_scan(nvalid, lane);
+    if (lane == 63) sh4[wave] = nvalid;
     __syncthreads();
-    block_bitonic_sort_kv<256>(keys, pos, sz, tid);
+    nvalid = sh4[0] + sh4[1] + sh4[2] + sh4[3];
+    __syncthreads();
+    const int w2eff = min(w2, nvalid);
+    // rank-th smallest (0-based) value of one 32-bit half of the keys: the high half over all keys,
+    // or the low half over the keys whose high half is `fixed`; 4 passes of 8 bits.  Leaves the
+    // rank inside the final bin and the size of that bin.
+    int res_rank = 0, res_inbin = 0;
+    auto select32 = [&](bool low, uint32_t fixed, int rank) -> uint32_t {
+        uint32_t prefix = 0;
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            hist[tid] = 0;
+            __syncthreads();
+            for (int t = tid; t < total; t += 256) {
+                const uint64_t key = keys[t];
+                if (key == KEY_MAX || (low && (uint32_t)(key >> 32) != fixed)) continue;
+                const uint32_t u = low ? (uint32_t)key : (uint32_t)(key >> 32);
+                if (pass == 0 || (u >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(u >> shift) & 255], 1);
+            }
+            __syncthreads();
+            const int c = hist[tid];
+            int inc = wave_incl_scan(c, lane);
+            if (lane == 63) sh4[wave] = inc;
+            __syncthreads();
+            for (int w = 0; w < wave; ++w) inc += sh4[w];
+            if (inc - c <= rank && rank < inc) {
+                sh_bin = tid;
+                sh_before = inc - c;
+                sh_inbin = c;
+            }
+            __syncthreads();
+            prefix |= (uint32_t)sh_bin << shift;
+            rank -= sh_before;
+            res_inbin = sh_inbin;
+            __syncthreads();
+        }
+        res_rank = rank;
+        return prefix;
+    };
+    uint64_t cut = 0;
+    if (w2eff > 0) {
+        const uint32_t v = select32(false, 0u, w2eff - 1);
+        // res_inbin keys share the score v and res_rank + 1 of them are wanted: the smaller labels
+        uint32_t lcut = 0xFFFFFFFFu;
+        if (res_inbin != res_rank + 1) lcut = select32(true, v, res_rank);
+        cut = ((uint64_t)v << 32) | lcut;
+    }
+    int mysel = 0;
+    if (w2eff > 0)
+        for (int t = tid; t < total; t += 256) mysel += keys[t] <= cut;
+    int base = wave_incl_scan(mysel, lane);
+    if (lane == 63) sh4[wave] = base;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) base += sh4[w];
+    base -= mysel;
+    if (w2eff > 0)
+        for (int t = tid; t < total; t += 256)
+            if (keys[t] <= cut) selpos[base++] = t;
+    __syncthreads();
+
+    if (!sub && !sub_score && !scan_label) {
+        // only the streaming scan follows: it takes the visited sub-regions in any order
+        for (int r = tid; r < w2; r += 256) {
+            uint4 dsc = make_uint4(0u, 0u, 0u, 0u);
+            if (r < w2eff) {
+                const int t = selpos[r];
+                const int label = (int)(uint32_t)keys[t];
+                const float a = cell_dist[(int64_t)q * w1 + t / n];
+                const int64_t b0 = off[label], b1 = off[label + 1];
+                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(bval[t] - a));
+            }
+            desc[(int64_t)q * w2 + r] = dsc;
+        }
+        return;
+    }
+
+    // the selected keys to the front, sorted by (score, label), original positions alongside
+    const int sz2 = next_pow2_dev(w2);
+    {
+        uint64_t mk[8]; // w2 <= 2048 = 8 * 256
+        int mp[8];
+        int c = 0;
+        for (int r = tid; r < w2; r += 256, ++c) {
+            mk[c] = r < w2eff ? keys[selpos[r]] : KEY_MAX;
+            mp[c] = r < w2eff ? selpos[r] : 0;
+        }
+        __syncthreads();
+        c = 0;
+        for (int r = tid; r < w2; r += 256, ++c) {
+            keys[r] = mk[c];
+            pos[r] = (uint16_t)mp[c];
+        }
+        for (int r = w2 + tid; r < sz2; r += 256) {
+            keys[r] = KEY_MAX;
+            pos[r] = 0;
+        }
+        __syncthreads();
+        block_bitonic_sort_kv<256>(keys, pos, sz2, tid);
+    }
 
     // (score, label) order for the caller; then re-key the visited ones by label
     uint64_t mine[8]; // w2 <= 2048 = 8 * 256
@@ -139,8 +263,8 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
         if (desc) desc[(int64_t)q * w2 + r] = dsc;
         mine[cnt] = k2;
     }
+    if (!scan_label) return;
     __syncthreads();
-    const int sz2 = next_pow2_dev(w2);
     cnt = 0;
     for (int r = tid; r < w2; r += 256, ++cnt) keys[r] = mine[cnt];
     for (int r = w2 + tid; r < sz2; r += 256) keys[r] = KEY_MAX;
@@ -154,19 +278,210 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
     }
 }
 
+// ---------------------------------------------------------------------------
+// b = ||y - s_ij||^2 cell by cell (Alg. 3, second loop).  A batch of queries probes most cells
+// several times; the (query, probed cell) pairs are grouped by cell, a workgroup brings the n
+// neighbour centroids of its cell into LDS once and serves every pair of the cell from there.
+// The sums are formed exactly as in k_subregions (16 lanes per row, fixed order).
+// ---------------------------------------------------------------------------
+__global__ void k_zero_i32(int32_t *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+__global__ void k_pair_count(const int32_t *__restrict__ cells, int64_t np, int32_t *__restrict__ cnt)
+{
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p < np) {
+        const int c = cells[p];
+        if (c >= 0) atomicAdd(&cnt[c], 1);
+    }
+}
+
+__global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, const int64_t *__restrict__ poff,
+                               int32_t *__restrict__ cursor, int32_t *__restrict__ pairs)
+{
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p < np) {
+        const int c = cells[p];
+        if (c >= 0) pairs[poff[c] + atomicAdd(&cursor[c], 1)] = (int32_t)p;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict__ Q, int D,
+                                                         const float *__restrict__ C,
+                                                         const int32_t *__restrict__ S, int n, int w1,
+                                                         const int64_t *__restrict__ poff,
+                                                         const int32_t *__restrict__ pairs,
+                                                         float *__restrict__ bq)
+{
+    extern __shared__ float nrows[]; // [n][D]
+    const int cell = blockIdx.x, tid = threadIdx.x;
+    const int64_t p0 = poff[cell], p1 = poff[cell + 1];
+    if (p0 == p1) return;
+    const bool vec = (D % 4 == 0) && ((((uintptr_t)C) | ((uintptr_t)Q)) % 16 == 0);
+    if (vec) {
+        const int d4 = D / 4;
+        for (int t = tid; t < n * d4; t += 256) {
+            const int j = t / d4, c = t - j * d4;
+            const int s = S[(int64_t)cell * n + j];
+            ((f32x4 *)nrows)[t] = ((const f32x4 *)(C + (int64_t)s * D))[c];
+        }
+    } else {
+        for (int t = tid; t < n * D; t += 256) {
+            const int j = t / D, d = t - j * D;
+            nrows[t] = C[(int64_t)S[(int64_t)cell * n + j] * D + d];
+        }
+    }
+    __syncthreads();
+    const int lane = tid & 63, wave = tid >> 6;
+    const int sub = lane >> 4, l16 = lane & 15;
+    if (vec && D <= 128) {
+        // a wave per pair, four rows per pass; the lane's two chunks of the query stay in
+        // registers, the next pair's are asked for before this pair's rows are worked on
+        const int d0 = l16 * 4, d1 = 64 + l16 * 4;
+        const bool has0 = d0 < D, has1 = d1 < D;
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        int64_t pi = p0 + wave;
+        int p = pi < p1 ? pairs[pi] : -1;
+        f32x4 y0 = zero, y1 = zero;
+        if (p >= 0) {
+            const float *y = Q + (int64_t)(p / w1) * D;
+            if (has0) y0 = *(const f32x4 *)(y + d0);
+            if (has1) y1 = *(const f32x4 *)(y + d1);
+        }
+        while (p >= 0) {
+            const int64_t pin = pi + 4;
+            const int pn = pin < p1 ? pairs[pin] : -1;
+            f32x4 n0 = zero, n1 = zero;
+            if (pn >= 0) {
+                const float *y = Q + (int64_t)(pn / w1) * D;
+                if (has0) n0 = *(const f32x4 *)(y + d0);
+                if (has1) n1 = *(const f32x4 *)(y + d1);
+            }
+            for (int j0 = 0; j0 < n; j0 += 4) {
+                const int j = j0 + sub;
+                float acc = 0.f;
+                if (j < n) {
+                    const float *row = nrows + j * D;
+                    if (has0) {
+                        const f32x4 cv = *(const f32x4 *)(row + d0);
+                        const float t0v = y0.x - cv.x, t1v = y0.y - cv.y, t2v = y0.z - cv.z, t3v = y0.w - cv.w;
+                        acc = fmaf(t0v, t0v, acc);
+                        acc = fmaf(t1v, t1v, acc);
+                        acc = fmaf(t2v, t2v, acc);
+                        acc = fmaf(t3v, t3v, acc);
+                    }
+                    if (has1) {
+                        const f32x4 cv = *(const f32x4 *)(row + d1);
+                        const float t0v = y1.x - cv.x, t1v = y1.y - cv.y, t2v = y1.z - cv.z, t3v = y1.w - cv.w;
+                        acc = fmaf(t0v, t0v, acc);
+                        acc = fmaf(t1v, t1v, acc);
+                        acc = fmaf(t2v, t2v, acc);
+                        acc = fmaf(t3v, t3v, acc);
+                    }
+                }
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+                if (l16 == 0 && j < n) bq[(int64_t)p * n + j] = acc;
+            }
+            p = pn;
+            pi = pin;
+            y0 = n0;
+            y1 = n1;
+        }
+        return;
+    }
+    for (int64_t pi = p0 + wave; pi < p1; pi += 4) {
+        const int p = pairs[pi];
+        const float *y = Q + (int64_t)(p / w1) * D;
+        for (int j0 = 0; j0 < n; j0 += 4) {
+            const int j = j0 + sub;
+            float acc = 0.f;
+            if (j < n) {
+                const float *row = nrows + j * D;
+                if (vec) {
+                    for (int d = l16 * 4; d < D; d += 64) {
+                        const f32x4 cv = *(const f32x4 *)(row + d);
+                        const f32x4 yv = *(const f32x4 *)(y + d);
+                        const float t0v = yv.x - cv.x, t1v = yv.y - cv.y, t2v = yv.z - cv.z, t3v = yv.w - cv.w;
+                        acc = fmaf(t0v, t0v, acc);
+                        acc = fmaf(t1v, t1v, acc);
+                        acc = fmaf(t2v, t2v, acc);
+                        acc = fmaf(t3v, t3v, acc);
+                    }
+                } else {
+                    for (int d = l16; d < D; d += 16) {
+                        const float tv = y[d] - row[d];
+                        acc = fmaf(tv, tv, acc);
+                    }
+                }
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+            if (l16 == 0 && j < n) bq[(int64_t)p * n + j] = acc;
+        }
+    }
+}
+
+bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1)
+{
+    // worth it once a cell is probed about twice per batch; the neighbour rows must fit in LDS
+    return (int64_t)nq * w1 >= 2 * (int64_t)k && (size_t)n * D * 4 <= 65536;
+}
+
+size_t neighbour_dists_workspace(int nq, int k, int n, int w1)
+{
+    size_t b = 0;
+    b += (((size_t)2 * k * 4) + 255) & ~(size_t)255;               // counts, cursors
+    b += (((size_t)(k + 1) * 8) + 255) & ~(size_t)255;             // offsets
+    b += (((size_t)nq * w1 * 4) + 255) & ~(size_t)255;             // pairs
+    b += (((size_t)nq * w1 * n * 4) + 255) & ~(size_t)255;         // distances
+    return b;
+}
+
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
-                       int n, const int32_t *cells, const float *cell_dist, int w1, int w2,
+                       int n, int k, const int32_t *cells, const float *cell_dist, int w1, int w2,
                        int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       const int64_t *off, uint4 *desc, hipStream_t st)
+                       const int64_t *off, uint4 *desc, void *ws, hipStream_t st)
 {
     if (nq <= 0) return;
+    const float *bpre = nullptr;
+    if (ws) {
+        // neighbour distances cell by cell; ws has neighbour_dists_workspace() bytes
+        char *base = (char *)ws;
+        auto take = [&](size_t bytes) {
+            char *at = base;
+            base += (bytes + 255) & ~(size_t)255;
+            return at;
+        };
+        int32_t *cnt = (int32_t *)take((size_t)2 * k * 4);
+        int32_t *cursor = cnt + k;
+        int64_t *poff = (int64_t *)take((size_t)(k + 1) * 8);
+        int32_t *pairs = (int32_t *)take((size_t)nq * w1 * 4);
+        float *bq = (float *)take((size_t)nq * w1 * n * 4);
+        const int64_t np = (int64_t)nq * w1;
+        hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((2 * (int64_t)k + 255) / 256)), dim3(256), 0, st, cnt,
+                           (int64_t)2 * k);
+        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt);
+        launch_exclusive_scan(cnt, k, poff, st);
+        hipLaunchKernelGGL(k_pair_scatter, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, poff,
+                           cursor, pairs);
+        const size_t rows_bytes = (size_t)n * D * 4;
+        (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)rows_bytes);
+        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)k), dim3(256), rows_bytes, st, Q, D, C, S, n, w1, poff,
+                           pairs, bq);
+        bpre = bq;
+    }
     int sz = next_pow2(w1 * n);
     if (sz < next_pow2(w2)) sz = next_pow2(w2);
     if (sz < 2) sz = 2;
     size_t smem = (size_t)sz * (8 + 4 + 2 + 4) + (size_t)D * 4;
     (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
-                       cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g, off, desc);
+                       cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g, off, desc, bpre);
 }
 
 // ---------------------------------------------------------------------------
@@ -356,12 +671,17 @@ int scan_pick_nsplit(int nq, int w2, int K)
     return ns;
 }
 
+bool scan_will_stream(const ScanArgs &a)
+{
+    // VLQ_SCAN_GENERIC=1 forces the generic kernel (used by the tests to cover both paths)
+    static const bool force_generic = getenv("VLQ_SCAN_GENERIC") && atoi(getenv("VLQ_SCAN_GENERIC")) != 0;
+    return !force_generic && scan_stream_supported(a);
+}
+
 void launch_scan(const ScanArgs &a, hipStream_t st)
 {
     if (a.nq <= 0) return;
-    // VLQ_SCAN_GENERIC=1 forces the generic kernel (used by the tests to cover both paths)
-    static const bool force_generic = getenv("VLQ_SCAN_GENERIC") && atoi(getenv("VLQ_SCAN_GENERIC")) != 0;
-    if (!force_generic && scan_stream_supported(a)) {
+    if (scan_will_stream(a)) {
         launch_scan_stream(a, st);
         return;
     }

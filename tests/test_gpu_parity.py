@@ -242,6 +242,23 @@ def test_cell_selection_with_many_centroids(vlq, oracle_mod, monkeypatch, dup, f
         vlq.vlq_index_free(idx)
 
 
+def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
+    """The distances to the neighbour centroids (Alg. 3, second loop) computed cell by cell over the
+    batch and computed inside the per-query kernel are the same sums: every output is identical.
+    (The parity cases above run the cell-by-cell form; this pins the other one to it.)"""
+    kw, w1, w2, K = CASES["sift_ragged"]
+    pr = problem(**kw)
+    idx = make_index(vlq, pr, base=pr.X)
+    try:
+        a = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        monkeypatch.setenv("VLQ_NEIGHBOURS_PER_QUERY", "1")
+        b = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_lists_layout_matches_oracle(vlq, oracle_mod):
     """vlq_index_add + finalize: the four list arrays of Sec. 4, ids ascending inside a list."""
     pr = problem(N=20011, k=100, n=7, m=8, G=16, nq=77)
