@@ -52,6 +52,9 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
     __shared__ int hist[256];
     __shared__ int sh4[4];
     __shared__ int sh_bin, sh_before, sh_inbin;
+    __shared__ unsigned sh_lo, sh_hi;
+    __shared__ unsigned long long sh_cut;
+    __shared__ uint64_t ckeys[256];
 
     for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)q * D + d];
     if (!bpre)
@@ -176,24 +179,148 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
         res_rank = rank;
         return prefix;
     };
+    // The cut key = the w2eff-th smallest key.  The scores between the smallest and the largest
+    // are binned linearly (monotone in the score, so the bins partition the order); the bin that
+    // holds the cut is binned again over its own range until it is small, then its keys are ranked
+    // by counting.  Scores are handled as their ordered bit patterns.
     uint64_t cut = 0;
     if (w2eff > 0) {
-        const uint32_t v = select32(false, 0u, w2eff - 1);
-        // res_inbin keys share the score v and res_rank + 1 of them are wanted: the smaller labels
-        uint32_t lcut = 0xFFFFFFFFu;
-        if (res_inbin != res_rank + 1) lcut = select32(true, v, res_rank);
-        cut = ((uint64_t)v << 32) | lcut;
+        uint32_t olo = 0xFFFFFFFFu, ohi = 0u;
+        for (int t = tid; t < total; t += 256) {
+            const uint64_t key = keys[t];
+            if (key == KEY_MAX) continue;
+            const uint32_t o = (uint32_t)(key >> 32);
+            olo = min(olo, o);
+            ohi = max(ohi, o);
+        }
+        int need = w2eff; // rank (1-based) of the cut among the keys with olo <= score <= ohi
+        int inbin = nvalid;
+        for (int level = 0; level < 8; ++level) {
+            // range of the undecided scores over the workgroup
+            if (tid == 0) {
+                sh_lo = 0xFFFFFFFFu;
+                sh_hi = 0u;
+            }
+            hist[tid] = 0;
+            __syncthreads();
+            if (olo <= ohi) {
+                atomicMin(&sh_lo, olo);
+                atomicMax(&sh_hi, ohi);
+            }
+            __syncthreads();
+            const uint32_t glo = sh_lo, ghi = sh_hi;
+            if (inbin <= 256 || glo == ghi) {
+                olo = glo;
+                ohi = ghi;
+                break;
+            }
+            const float flo = ord2f(glo), fhi = ord2f(ghi);
+            if (!(fhi > flo)) { // one score (or not comparable): resolved below
+                olo = glo;
+                ohi = ghi;
+                break;
+            }
+            const float scale = 256.f / (fhi - flo);
+            for (int t = tid; t < total; t += 256) {
+                const uint64_t key = keys[t];
+                const uint32_t o = (uint32_t)(key >> 32);
+                if (key == KEY_MAX || o < glo || o > ghi) continue;
+                int b = (int)((ord2f(o) - flo) * scale);
+                b = b > 255 ? 255 : (b < 0 ? 0 : b);
+                atomicAdd(&hist[b], 1);
+            }
+            __syncthreads();
+            const int c = hist[tid];
+            int inc = wave_incl_scan(c, lane);
+            if (lane == 63) sh4[wave] = inc;
+            __syncthreads();
+            for (int w = 0; w < wave; ++w) inc += sh4[w];
+            if (inc - c < need && need <= inc) {
+                sh_bin = tid;
+                sh_before = inc - c;
+                sh_inbin = c;
+            }
+            __syncthreads();
+            const int B = sh_bin;
+            need -= sh_before;
+            inbin = sh_inbin;
+            // the scores of bin B bound the next round
+            olo = 0xFFFFFFFFu;
+            ohi = 0u;
+            for (int t = tid; t < total; t += 256) {
+                const uint64_t key = keys[t];
+                const uint32_t o = (uint32_t)(key >> 32);
+                if (key == KEY_MAX || o < glo || o > ghi) continue;
+                int b = (int)((ord2f(o) - flo) * scale);
+                b = b > 255 ? 255 : (b < 0 ? 0 : b);
+                if (b == B) {
+                    olo = min(olo, o);
+                    ohi = max(ohi, o);
+                }
+            }
+            __syncthreads();
+            if (level == 7) { // publish the last range as well
+                if (tid == 0) {
+                    sh_lo = 0xFFFFFFFFu;
+                    sh_hi = 0u;
+                }
+                __syncthreads();
+                if (olo <= ohi) {
+                    atomicMin(&sh_lo, olo);
+                    atomicMax(&sh_hi, ohi);
+                }
+                __syncthreads();
+                olo = sh_lo;
+                ohi = sh_hi;
+            }
+        }
+        // the undecided keys: olo <= score <= ohi, `inbin` of them, the cut is the need-th smallest
+        if (tid == 0) sh_bin = 0;
+        __syncthreads();
+        if (inbin <= 256) {
+            uint64_t *ck = ckeys;
+            for (int t = tid; t < total; t += 256) {
+                const uint64_t key = keys[t];
+                const uint32_t o = (uint32_t)(key >> 32);
+                if (key == KEY_MAX || o < olo || o > ohi) continue;
+                ck[atomicAdd(&sh_bin, 1)] = key;
+            }
+            __syncthreads();
+            const int c = sh_bin;
+            if (tid < c) {
+                const uint64_t mine = ck[tid];
+                int rank = 0;
+                for (int j = 0; j < c; ++j) rank += ck[j] < mine;
+                if (rank == need - 1) sh_cut = mine;
+            }
+            __syncthreads();
+            cut = sh_cut;
+        } else if (olo == ohi) {
+            // more than 256 keys share one score: the smaller labels win
+            const uint32_t lcut = select32(true, olo, need - 1);
+            cut = ((uint64_t)olo << 32) | lcut;
+        } else {
+            // the range would not narrow (non-finite scores): radix select over all keys
+            const uint32_t v = select32(false, 0u, w2eff - 1);
+            uint32_t lcut = 0xFFFFFFFFu;
+            if (res_inbin != res_rank + 1) lcut = select32(true, v, res_rank);
+            cut = ((uint64_t)v << 32) | lcut;
+        }
     }
+    // every thread takes a contiguous range of positions, so the compacted order is that of the
+    // positions: sub-regions of nearer cells first, which tightens the scan's bound early
+    const int per = (total + 255) / 256;
+    const int tb = tid * per, te = min(total, tb + per);
     int mysel = 0;
     if (w2eff > 0)
-        for (int t = tid; t < total; t += 256) mysel += keys[t] <= cut;
+        for (int t = tb; t < te; ++t) mysel += keys[t] <= cut;
     int base = wave_incl_scan(mysel, lane);
     if (lane == 63) sh4[wave] = base;
     __syncthreads();
     for (int w = 0; w < wave; ++w) base += sh4[w];
     base -= mysel;
     if (w2eff > 0)
-        for (int t = tid; t < total; t += 256)
+        for (int t = tb; t < te; ++t)
             if (keys[t] <= cut) selpos[base++] = t;
     __syncthreads();
 
@@ -309,119 +436,109 @@ __global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, co
     }
 }
 
+#define ND_PCH 32 // pairs per workgroup
+
+// The pairs, ordered by cell, are cut into runs of ND_PCH; a workgroup walks its run cell by
+// cell (a popular cell spreads over many workgroups, a run of rarely probed cells costs one
+// reload of the rows per cell).  A wave per pair, four rows per pass.
 __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict__ Q, int D,
                                                          const float *__restrict__ C,
-                                                         const int32_t *__restrict__ S, int n, int w1,
+                                                         const int32_t *__restrict__ S, int n, int k, int w1,
+                                                         const int32_t *__restrict__ cells,
                                                          const int64_t *__restrict__ poff,
                                                          const int32_t *__restrict__ pairs,
                                                          float *__restrict__ bq)
 {
     extern __shared__ float nrows[]; // [n][D]
-    const int cell = blockIdx.x, tid = threadIdx.x;
-    const int64_t p0 = poff[cell], p1 = poff[cell + 1];
-    if (p0 == p1) return;
-    const bool vec = (D % 4 == 0) && ((((uintptr_t)C) | ((uintptr_t)Q)) % 16 == 0);
-    if (vec) {
-        const int d4 = D / 4;
-        for (int t = tid; t < n * d4; t += 256) {
-            const int j = t / d4, c = t - j * d4;
-            const int s = S[(int64_t)cell * n + j];
-            ((f32x4 *)nrows)[t] = ((const f32x4 *)(C + (int64_t)s * D))[c];
-        }
-    } else {
-        for (int t = tid; t < n * D; t += 256) {
-            const int j = t / D, d = t - j * D;
-            nrows[t] = C[(int64_t)S[(int64_t)cell * n + j] * D + d];
-        }
+    __shared__ int sp[ND_PCH], sc[ND_PCH];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane >> 4, l16 = lane & 15;
+    const int64_t np = poff[k]; // pairs with a valid cell
+    const int64_t pbeg = (int64_t)blockIdx.x * ND_PCH;
+    if (pbeg >= np) return;
+    const int cntp = (int)min((int64_t)ND_PCH, np - pbeg);
+    if (tid < cntp) {
+        const int p = pairs[pbeg + tid];
+        sp[tid] = p;
+        sc[tid] = cells[p];
     }
     __syncthreads();
-    const int lane = tid & 63, wave = tid >> 6;
-    const int sub = lane >> 4, l16 = lane & 15;
-    if (vec && D <= 128) {
-        // a wave per pair, four rows per pass; the lane's two chunks of the query stay in
-        // registers, the next pair's are asked for before this pair's rows are worked on
-        const int d0 = l16 * 4, d1 = 64 + l16 * 4;
-        const bool has0 = d0 < D, has1 = d1 < D;
-        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        int64_t pi = p0 + wave;
-        int p = pi < p1 ? pairs[pi] : -1;
-        f32x4 y0 = zero, y1 = zero;
-        if (p >= 0) {
+    const bool vec = (D % 4 == 0) && ((((uintptr_t)C) | ((uintptr_t)Q)) % 16 == 0);
+    const bool fast = vec && D <= 128;
+    const int d0 = l16 * 4, d1 = 64 + l16 * 4;
+    const bool has0 = fast && d0 < D, has1 = fast && d1 < D;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    int i = 0;
+    while (i < cntp) {
+        const int cell = sc[i];
+        int e = i + 1;
+        while (e < cntp && sc[e] == cell) ++e;
+        __syncthreads(); // the previous cell's rows are no longer read
+        if (vec) {
+            const int d4 = D / 4;
+            for (int t = tid; t < n * d4; t += 256) {
+                const int j = t / d4, c = t - j * d4;
+                const int s = S[(int64_t)cell * n + j];
+                ((f32x4 *)nrows)[t] = ((const f32x4 *)(C + (int64_t)s * D))[c];
+            }
+        } else {
+            for (int t = tid; t < n * D; t += 256) {
+                const int j = t / D, d = t - j * D;
+                nrows[t] = C[(int64_t)S[(int64_t)cell * n + j] * D + d];
+            }
+        }
+        __syncthreads();
+        for (int pi = i + wave; pi < e; pi += 4) {
+            const int p = sp[pi];
             const float *y = Q + (int64_t)(p / w1) * D;
+            f32x4 y0 = zero, y1 = zero;
             if (has0) y0 = *(const f32x4 *)(y + d0);
             if (has1) y1 = *(const f32x4 *)(y + d1);
-        }
-        while (p >= 0) {
-            const int64_t pin = pi + 4;
-            const int pn = pin < p1 ? pairs[pin] : -1;
-            f32x4 n0 = zero, n1 = zero;
-            if (pn >= 0) {
-                const float *y = Q + (int64_t)(pn / w1) * D;
-                if (has0) n0 = *(const f32x4 *)(y + d0);
-                if (has1) n1 = *(const f32x4 *)(y + d1);
-            }
             for (int j0 = 0; j0 < n; j0 += 4) {
                 const int j = j0 + sub;
                 float acc = 0.f;
                 if (j < n) {
                     const float *row = nrows + j * D;
-                    if (has0) {
-                        const f32x4 cv = *(const f32x4 *)(row + d0);
-                        const float t0v = y0.x - cv.x, t1v = y0.y - cv.y, t2v = y0.z - cv.z, t3v = y0.w - cv.w;
-                        acc = fmaf(t0v, t0v, acc);
-                        acc = fmaf(t1v, t1v, acc);
-                        acc = fmaf(t2v, t2v, acc);
-                        acc = fmaf(t3v, t3v, acc);
-                    }
-                    if (has1) {
-                        const f32x4 cv = *(const f32x4 *)(row + d1);
-                        const float t0v = y1.x - cv.x, t1v = y1.y - cv.y, t2v = y1.z - cv.z, t3v = y1.w - cv.w;
-                        acc = fmaf(t0v, t0v, acc);
-                        acc = fmaf(t1v, t1v, acc);
-                        acc = fmaf(t2v, t2v, acc);
-                        acc = fmaf(t3v, t3v, acc);
+                    if (fast) {
+                        if (has0) {
+                            const f32x4 cv = *(const f32x4 *)(row + d0);
+                            const float t0v = y0.x - cv.x, t1v = y0.y - cv.y, t2v = y0.z - cv.z, t3v = y0.w - cv.w;
+                            acc = fmaf(t0v, t0v, acc);
+                            acc = fmaf(t1v, t1v, acc);
+                            acc = fmaf(t2v, t2v, acc);
+                            acc = fmaf(t3v, t3v, acc);
+                        }
+                        if (has1) {
+                            const f32x4 cv = *(const f32x4 *)(row + d1);
+                            const float t0v = y1.x - cv.x, t1v = y1.y - cv.y, t2v = y1.z - cv.z, t3v = y1.w - cv.w;
+                            acc = fmaf(t0v, t0v, acc);
+                            acc = fmaf(t1v, t1v, acc);
+                            acc = fmaf(t2v, t2v, acc);
+                            acc = fmaf(t3v, t3v, acc);
+                        }
+                    } else if (vec) {
+                        for (int d = l16 * 4; d < D; d += 64) {
+                            const f32x4 cv = *(const f32x4 *)(row + d);
+                            const f32x4 yv = *(const f32x4 *)(y + d);
+                            const float t0v = yv.x - cv.x, t1v = yv.y - cv.y, t2v = yv.z - cv.z, t3v = yv.w - cv.w;
+                            acc = fmaf(t0v, t0v, acc);
+                            acc = fmaf(t1v, t1v, acc);
+                            acc = fmaf(t2v, t2v, acc);
+                            acc = fmaf(t3v, t3v, acc);
+                        }
+                    } else {
+                        for (int d = l16; d < D; d += 16) {
+                            const float tv = y[d] - row[d];
+                            acc = fmaf(tv, tv, acc);
+                        }
                     }
                 }
 #pragma unroll
                 for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
                 if (l16 == 0 && j < n) bq[(int64_t)p * n + j] = acc;
             }
-            p = pn;
-            pi = pin;
-            y0 = n0;
-            y1 = n1;
         }
-        return;
-    }
-    for (int64_t pi = p0 + wave; pi < p1; pi += 4) {
-        const int p = pairs[pi];
-        const float *y = Q + (int64_t)(p / w1) * D;
-        for (int j0 = 0; j0 < n; j0 += 4) {
-            const int j = j0 + sub;
-            float acc = 0.f;
-            if (j < n) {
-                const float *row = nrows + j * D;
-                if (vec) {
-                    for (int d = l16 * 4; d < D; d += 64) {
-                        const f32x4 cv = *(const f32x4 *)(row + d);
-                        const f32x4 yv = *(const f32x4 *)(y + d);
-                        const float t0v = yv.x - cv.x, t1v = yv.y - cv.y, t2v = yv.z - cv.z, t3v = yv.w - cv.w;
-                        acc = fmaf(t0v, t0v, acc);
-                        acc = fmaf(t1v, t1v, acc);
-                        acc = fmaf(t2v, t2v, acc);
-                        acc = fmaf(t3v, t3v, acc);
-                    }
-                } else {
-                    for (int d = l16; d < D; d += 16) {
-                        const float tv = y[d] - row[d];
-                        acc = fmaf(tv, tv, acc);
-                    }
-                }
-            }
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-            if (l16 == 0 && j < n) bq[(int64_t)p * n + j] = acc;
-        }
+        i = e;
     }
 }
 
@@ -471,8 +588,8 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         const size_t rows_bytes = (size_t)n * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
-        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)k), dim3(256), rows_bytes, st, Q, D, C, S, n, w1, poff,
-                           pairs, bq);
+        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)((np + ND_PCH - 1) / ND_PCH)), dim3(256), rows_bytes, st, Q,
+                           D, C, S, n, k, w1, cells, poff, pairs, bq);
         bpre = bq;
     }
     int sz = next_pow2(w1 * n);
