@@ -36,6 +36,8 @@
 #define SS_WSZ 256   // per-wave keys: list + candidate buffer
 
 typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 // wave-private bitonic sort of SS_WSZ keys in LDS (LDS operations of one wave
 // complete in issue order, so no workgroup barrier is needed)
@@ -61,10 +63,10 @@ __device__ __forceinline__ void wave_sort256(volatile lds_u64 *wk, int lane)
 template <int M>
 __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint4 *__restrict__ desc)
 {
-    extern __shared__ unsigned char smem[];
-    uint64_t *keys = (uint64_t *)smem;                 // [NW][WSZ]
-    float *T = (float *)(keys + SS_NW * SS_WSZ);       // [M][256]
-    float *yv = T + M * 256;                           // [D]
+    // all LDS is static: the table sits at a fixed address, which folds into the lookups' offsets
+    __shared__ float T[M * 256];
+    __shared__ uint64_t keys[SS_NW * SS_WSZ];
+    __shared__ float yv[VLQ_MAX_DIM];
     __shared__ unsigned long long sh_thr;              // upper bound of the K-th smallest key of the workgroup
     __shared__ unsigned long long sh_q[SS_NW];         // every wave's ceil(K/8)-th key
     __shared__ int sh_next;                            // next list to hand out
@@ -131,10 +133,13 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
         const int len = (int)dsc.y;
         const float av = __uint_as_float(dsc.z), bav = __uint_as_float(dsc.w);
         if (len <= 0) continue;
-        const uint32_t *codes = (const uint32_t *)(a.codes + (int64_t)beg * M);
-        const uint8_t *lam = a.lam + beg;
-        const float *sx = a.sx + beg;
+        // range-checked raw buffers over the three streams of this list: reads past the end
+        // return zero and are masked out, so the chunk loop needs no address arithmetic
+        const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)(a.codes + (int64_t)beg * M), 0, len * M, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc((void *)(a.lam + beg), 0, len, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)(a.sx + beg), 0, len * 4, 0x00020000);
         thr = sh_thr;
+        float thr_f = thr == KEY_MAX ? INFINITY : ord2f((uint32_t)(thr >> 32));
         for (int base = 0; base < len; base += 64 * SS_CH) {
             // ---- all loads of up to SS_CH chunks ----
             uint32_t cw[SS_CH][M / 4];
@@ -143,13 +148,18 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
 #pragma unroll
             for (int u = 0; u < SS_CH; ++u) {
                 if (base + 64 * u < len) { // uniform over the wave
-                    int within = base + 64 * u + lane;
-                    within = within < len ? within : len - 1; // stay inside the list
-                    const uint32_t *cp = codes + (int64_t)within * (M / 4);
+                    const int so = base + 64 * u;
+                    if (M == 8) {
+                        const u32x2_t c2 = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_raw_buffer_load_b64(rc, lane * 8, so * 8, 0));
+                        cw[u][0] = c2.x;
+                        cw[u][1] = c2.y;
+                    } else {
+                        const u32x4_t c4 = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rc, lane * 16, so * 16, 0));
 #pragma unroll
-                    for (int x = 0; x < M / 4; ++x) cw[u][x] = cp[x];
-                    lb[u] = lam[within];
-                    sv[u] = sx[within];
+                        for (int x = 0; x < M / 4; ++x) cw[u][x] = c4[x];
+                    }
+                    lb[u] = __builtin_amdgcn_raw_buffer_load_b8(rl, lane, so, 0);
+                    sv[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, lane * 4, so * 4, 0));
                 }
             }
             // ---- score ----
@@ -158,25 +168,28 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
                 if (base + 64 * u < len) {
                     const int within = base + 64 * u + lane;
                     const bool live = within < len;
-                    float t[M];
+                    float ts = 0.f;
 #pragma unroll
                     for (int x = 0; x < M / 4; ++x)
 #pragma unroll
-                        for (int bb = 0; bb < 4; ++bb)
-                            t[x * 4 + bb] = T[(x * 4 + bb) * 256 + ((cw[u][x] >> (8 * bb)) & 255u)];
-                    float ts = 0.f;
-#pragma unroll
-                    for (int x = 0; x < M; ++x) ts += t[x];
+                        for (int bb = 0; bb < 4; ++bb) {
+                            const uint32_t byte_off = ((cw[u][x] >> (8 * bb)) & 255u) << 2;
+                            ts += *(const float *)((const char *)(T + (x * 4 + bb) * 256) + byte_off);
+                        }
                     const float l = ((float)lb[u] - a.lam_zero) * a.lam_step;
                     const float dist = (sv[u] - ts) + fmaf(l, bav, av);
-                    const uint64_t key = make_key(dist, beg + (uint32_t)within);
-                    bool pass = live && key < thr;
+                    // cheap test on the distance alone; the exact (distance, position) key only for the few that pass
+                    bool pass = live && dist <= thr_f;
                     uint64_t mask = __ballot(pass);
                     if (mask) {
+                        const uint64_t key = make_key(dist, beg + (uint32_t)within);
+                        pass = pass && key < thr;
+                        mask = __ballot(pass);
                         int np = __popcll(mask);
-                        if (wcnt + np > SS_WSZ - SS_KP) {
+                        if (np && wcnt + np > SS_WSZ - SS_KP) {
                             merge_wave();
                             thr = sh_thr;
+                            thr_f = thr == KEY_MAX ? INFINITY : ord2f((uint32_t)(thr >> 32));
                             pass = pass && key < thr;
                             mask = __ballot(pass);
                             np = __popcll(mask);
@@ -217,10 +230,7 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     }
 }
 
-static size_t scan_stream_smem(int M, int D)
-{
-    return (size_t)SS_NW * SS_WSZ * 8 + (size_t)M * 256 * 4 + (size_t)D * 4;
-}
+static size_t scan_stream_smem(int, int) { return 0; } // all LDS is static
 
 // Shapes served by this kernel; everything else takes the generic kernel.
 bool scan_stream_supported(const ScanArgs &a)
