@@ -95,6 +95,19 @@ def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
             "sample": f"first {ns} of the {len(Y)} queries, index and graph copied from the library, same w1/w2/K; {t:.1f} s of oracle search"}, out_i, ns
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the scan kernel from the committed counter summary of this workload
+    (two rocprofv3 --pmc runs of this script, scaled by the copy yardstick); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"k_scan_stream_{workload}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +118,9 @@ def main():
     ap.add_argument("--points", type=int, default=0, help="build only the first POINTS vectors (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time the other w1 values of the configuration")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain streaming kernel of known size (torch.frac over 2^28 floats: 1 GiB read, "
+                         "1 GiB written), the yardstick for the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1")
@@ -166,6 +182,13 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": scan_avg_s * 1e3},
     }
+    result["roofline"]["traffic"] = measured_traffic(cfg.name)
+    if args.copy_calibration:
+        src = torch.rand(1 << 28, device=dev)
+        dst = torch.empty_like(src)
+        torch.frac(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     if args.sweep:
         sweep = []
         for w in cfg.w1:

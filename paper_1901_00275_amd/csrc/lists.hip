@@ -51,30 +51,42 @@ void launch_list_histogram(const int32_t *label, int64_t N, int32_t *cnt, hipStr
     hipLaunchKernelGGL(k_list_histogram, dim3((unsigned)blocks), dim3(256), 0, st, label, N, cnt);
 }
 
-// off[i] = sum of cnt[0..i), off[nl] = total; one workgroup.
+// off[i] = sum of cnt[0..i), off[nl] = total; one workgroup walks the array in tiles of 4096
+// (four consecutive counts per thread, so loads and stores are coalesced), carrying the sum.
 __global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restrict__ cnt, int64_t nl,
                                                          int64_t *__restrict__ off)
 {
-    __shared__ int64_t part[1024];
-    const int tid = threadIdx.x;
-    const int64_t chunk = (nl + 1023) / 1024;
-    const int64_t b = tid * chunk, e = min(nl, b + chunk);
-    int64_t s = 0;
-    for (int64_t i = b; i < e; ++i) s += cnt[i];
-    part[tid] = s;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        int64_t v = tid >= o ? part[tid - o] : 0;
+    __shared__ int64_t wsum[16];
+    __shared__ int64_t carry_sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int64_t carry = 0;
+    for (int64_t t0 = 0; t0 < nl; t0 += 4096) {
+        const int64_t i0 = t0 + 4 * tid;
+        int32_t c[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = i0 + e < nl ? cnt[i0 + e] : 0;
+        const int64_t mine = (int64_t)c[0] + c[1] + c[2] + c[3];
+        int64_t inc = mine; // inclusive scan over the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int64_t v = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += v;
+        }
+        if (lane == 63) wsum[wave] = inc;
         __syncthreads();
-        part[tid] += v;
+        int64_t before = carry;
+        for (int w = 0; w < wave; ++w) before += wsum[w];
+        int64_t run = before + inc - mine;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (i0 + e < nl) off[i0 + e] = run;
+            run += c[e];
+        }
+        if (tid == 1023) carry_sh = run;
         __syncthreads();
+        carry = carry_sh;
     }
-    int64_t run = part[tid] - s;
-    for (int64_t i = b; i < e; ++i) {
-        off[i] = run;
-        run += cnt[i];
-    }
-    if (tid == 1023) off[nl] = part[1023];
+    if (tid == 0) off[nl] = carry;
 }
 void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStream_t st)
 {
