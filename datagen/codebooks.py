@@ -92,3 +92,45 @@ def train(Xtrain: torch.Tensor, k: int, n: int, m: int, iters: int = 10, seed: i
     ds = D // m
     P = torch.stack([lloyd(R[:, p * ds : (p + 1) * ds].contiguous(), 256, iters, seed, 1 + p) for p in range(m)])
     return Cb, P.contiguous()
+
+
+def _seeded_init(X: torch.Tensor, k: int, seed: int, stream: int) -> torch.Tensor:
+    """The initial codebook of `lloyd`: k seeded rows of X (jittered copies if X has fewer rows)."""
+    g = _gen("cpu", seed, STREAM_KMEANS, stream)
+    nt = X.shape[0]
+    if nt >= k:
+        init = torch.randperm(nt, generator=g)[:k]
+    else:
+        init = torch.randint(0, nt, (k,), generator=g)
+    Cb = X[init.to(X.device)].clone()
+    if nt < k:
+        Cb += 1e-3 * torch.randn(Cb.shape, generator=g).to(X.device) * (X.std() + 1e-6)
+    return Cb.contiguous()
+
+
+def train_with_library(vlq, Xtrain: torch.Tensor, k: int, n: int, m: int, iters: int = 10, seed: int = MASTER_SEED,
+                       pq_sample: int = 1 << 18):
+    """The same recipe as `train`, every step run by the GPU library: Lloyd iterations by
+    vlq_kmeans, the n-NN graph by vlq_build_index, line-quantisation residuals by
+    vlq_line_residuals, and one 256-word codebook per sub-space by vlq_kmeans again."""
+    nt, D = Xtrain.shape
+    assert D % m == 0
+    ds = D // m
+    Cb = _seeded_init(Xtrain, k, seed, 0)
+    vlq.vlq_kmeans(Xtrain, nt, D, k, iters, Cb)
+    # an index over the trained centroids (placeholder PQ codebooks) gives cells, lines and lambda bytes
+    idx = vlq.vlq_build_index(vlq.vlq_params_t(D, k, n, m, 0.0, 0.0), Cb, torch.zeros(m, 256, ds, device=Xtrain.device))
+    try:
+        ns = min(nt, pq_sample)
+        R = torch.empty(ns, D, device=Xtrain.device)
+        vlq.vlq_line_residuals(idx, Xtrain[:ns].contiguous(), ns, R)
+    finally:
+        vlq.vlq_index_free(idx)
+    P = []
+    for p in range(m):
+        Rp = R[:, p * ds:(p + 1) * ds].contiguous()
+        Pp = _seeded_init(Rp, 256, seed, 1 + p)
+        vlq.vlq_kmeans(Rp, ns, ds, 256, iters, Pp)
+        P.append(Pp)
+    torch.cuda.synchronize()
+    return Cb, torch.stack(P).contiguous()

@@ -76,7 +76,7 @@ def materialise(vlq, cfg: Config, device="cuda:0", n_points: int | None = None, 
     t0 = time.time()
     mix = Mixture(cfg.kind, cfg.G, seed=MASTER_SEED)
     T = mix.train_sample(cfg.ntrain, device)
-    C, P = codebooks.train(T, cfg.k, cfg.n, cfg.m, iters=iters, seed=MASTER_SEED)
+    C, P = codebooks.train_with_library(vlq, T, cfg.k, cfg.n, cfg.m, iters=iters, seed=MASTER_SEED)
     del T
     torch.cuda.synchronize()
     t_train = time.time() - t0

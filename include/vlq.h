@@ -107,6 +107,29 @@ int vlq_encode(const vlq_index_t *idx, const float *d_x, int64_t nb, int32_t *d_
                int32_t *d_edge, uint8_t *d_lambda, uint8_t *d_codes, void *stream);
 
 /*
+ * Residuals of line quantisation for a batch (Eq. 12): d_res[t] = x_t - ((1 - l) c_i + l s_ij)
+ * with the cell, edge and dequantised lambda byte that vlq_encode gives for x_t.  These are the
+ * vectors the PQ codebooks are trained on (Sec. 3.2).  d_res [nb x d] is caller-owned device
+ * memory; the index is not modified.
+ */
+int vlq_line_residuals(const vlq_index_t *idx, const float *d_x, int64_t nb, float *d_res,
+                       void *stream);
+
+/*
+ * Lloyd iterations for a codebook (the paper trains the first-level codebook and the 256-word
+ * PQ codebooks by k-means, Sec. 2.1 / Sec. 5).  d_centroids [k x d] holds the initial
+ * codebook on entry and the trained one on return.  One iteration: every row of d_x [nt x d]
+ * goes to its nearest centroid (Eq. 2, ties to the smaller index); a centroid with members
+ * moves to their mean, one without members stays.  The means do not depend on the order of
+ * summation (64-bit fixed-point sums).  Optional outputs, both with respect to the RETURNED
+ * codebook: d_assign [nt] nearest centroid of every row, d_counts [k] members per centroid.
+ * iters = 0 only assigns.  Device pointers throughout; temporaries are allocated and freed
+ * inside the call, which returns after the stream has drained.  Needs no index.
+ */
+int vlq_kmeans(const float *d_x, int64_t nt, int32_t d, int32_t k, int32_t iters,
+               float *d_centroids, int32_t *d_assign, int32_t *d_counts, void *stream);
+
+/*
  * Streamed build (the paper builds the database in batches, Sec. 5): encode nb
  * vectors and stage them.  d_ids NULL numbers them after the points already
  * added.  The index must be finalised again before the next search.

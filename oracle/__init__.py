@@ -154,6 +154,31 @@ def vq_assign(Cb, X):
     return cell, cd
 
 
+def lloyd_step(Cb, X):
+    """One Lloyd iteration of k-means (the training of the codebooks, Sec. 2.1 / Sec. 5): rows
+    of X go to their nearest centroid (Eq. 2, ties to the smaller index), every centroid with
+    members becomes their mean (fp64), one without stays.  Returns (new centroids fp64,
+    assignment, best / second-best objective per row)."""
+    cell, cd = vq_assign(Cb, X)
+    k, D = np.shape(Cb)
+    new = np.array(Cb, np.float64)
+    X64 = np.asarray(X, np.float64)
+    for i in range(k):
+        members = X64[cell == i]
+        if len(members):
+            new[i] = members.sum(0) / len(members)
+    return new, cell, cd
+
+
+def line_residual(Cb, S, X, cell, edge, lamq, lo=LAMBDA_LO, hi=LAMBDA_HI):
+    """x - ((1 - l) c_i + l s_ij) with l the value of the lambda byte (Eq. 12), fp64."""
+    Cb64 = np.asarray(Cb, np.float64)
+    ci = Cb64[cell]
+    sj = Cb64[np.asarray(S)[cell, edge]]
+    lam = np.array([lambda_dequant(int(q), lo, hi) for q in lamq])[:, None]
+    return np.asarray(X, np.float64) - ((1.0 - lam) * ci + lam * sj)
+
+
 def encode(Cb, S, E, P, X, lo=LAMBDA_LO, hi=LAMBDA_HI) -> Encoded:
     """Alg. 1 + Alg. 2 for every row of X.  P: [m, 256, D/m]."""
     Cb, X, P = _f32(Cb), _f32(X), _f32(P)

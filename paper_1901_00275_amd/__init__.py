@@ -46,6 +46,8 @@ def lib():
         sig = {
             "vlq_build_index": [C.POINTER(vlq_params_t), vp, vp, vp, i64, vp, vp, C.POINTER(vp)],
             "vlq_encode": [vp, vp, i64, vp, vp, vp, vp, vp],
+            "vlq_line_residuals": [vp, vp, i64, vp, vp],
+            "vlq_kmeans": [vp, i64, i32, i32, i32, vp, vp, vp, vp],
             "vlq_index_add": [vp, vp, i64, vp, vp],
             "vlq_index_add_encoded": [vp, vp, vp, vp, vp, vp, i64, vp],
             "vlq_index_reserve": [vp, i64],
@@ -118,6 +120,15 @@ def vlq_index_free(idx):
 def vlq_encode(idx, d_x, nb, d_cell, d_edge, d_lambda, d_codes, stream=None):
     _chk(lib().vlq_encode(idx, _ptr(d_x, torch.float32), int(nb), _ptr(d_cell, torch.int32), _ptr(d_edge, torch.int32),
                           _ptr(d_lambda, torch.uint8), _ptr(d_codes, torch.uint8), _stream(stream)))
+
+
+def vlq_line_residuals(idx, d_x, nb, d_res, stream=None):
+    _chk(lib().vlq_line_residuals(idx, _ptr(d_x, torch.float32), int(nb), _ptr(d_res, torch.float32), _stream(stream)))
+
+
+def vlq_kmeans(d_x, nt, d, k, iters, d_centroids, d_assign=None, d_counts=None, stream=None):
+    _chk(lib().vlq_kmeans(_ptr(d_x, torch.float32), int(nt), int(d), int(k), int(iters), _ptr(d_centroids, torch.float32),
+                          _ptr(d_assign, torch.int32), _ptr(d_counts, torch.int32), _stream(stream)))
 
 
 def vlq_index_add(idx, d_x, nb, d_ids=None, stream=None):

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvlq.so")
-SOURCES = ["api.hip", "coarse.hip", "coarse_bf16.hip", "search.hip", "scan_stream.hip", "encode.hip", "lists.hip"]
+SOURCES = ["api.hip", "coarse.hip", "coarse_bf16.hip", "train.hip", "search.hip", "scan_stream.hip", "encode.hip", "lists.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 instructions are not to be generated on the test machines

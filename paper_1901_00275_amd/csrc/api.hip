@@ -268,7 +268,7 @@ extern "C" int vlq_index_params(const vlq_index_t *idx, vlq_params_t *out)
 #define ENC_CHUNK ((int64_t)1 << 18)
 
 static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_cell, int32_t *d_edge,
-                       uint8_t *d_lambda, uint8_t *d_codes, int32_t *d_label, hipStream_t st)
+                       uint8_t *d_lambda, uint8_t *d_codes, int32_t *d_label, hipStream_t st, float *d_res = nullptr)
 {
     const int k = idx->p.nlist, D = idx->p.d, n = idx->p.n_edges, m = idx->p.m;
     const int64_t chunk = nb < ENC_CHUNK ? nb : ENC_CHUNK;
@@ -331,6 +331,7 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
         a.edge = d_edge ? d_edge + s : (d_label ? tedge : nullptr);
         a.lamq = d_lambda ? d_lambda + s : nullptr;
         a.codes = d_codes ? d_codes + s * m : nullptr;
+        a.res = d_res ? d_res + s * D : nullptr;
         launch_encode_finish(a, st);
         LAUNCHCHK();
         if (d_label) {
@@ -350,6 +351,145 @@ extern "C" int vlq_encode(const vlq_index_t *cidx, const float *d_x, int64_t nb,
     if (nb == 0) return VLQ_OK;
     if (!d_x) return fail(VLQ_EINVAL, "d_x is NULL");
     return encode_impl(idx, d_x, nb, d_cell, d_edge, d_lambda, d_codes, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int vlq_line_residuals(const vlq_index_t *cidx, const float *d_x, int64_t nb, float *d_res, void *stream)
+{
+    vlq_index *idx = const_cast<vlq_index *>(cidx);
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (nb < 0) return fail(VLQ_EINVAL, "nb = %lld is negative", (long long)nb);
+    if (nb == 0) return VLQ_OK;
+    if (!d_x || !d_res) return fail(VLQ_EINVAL, "d_x and d_res must not be NULL");
+    return encode_impl(idx, d_x, nb, nullptr, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream, d_res);
+}
+
+// ---------------------------------------------------------------------------
+// k-means
+// ---------------------------------------------------------------------------
+namespace {
+struct DevBuf { // device allocations of one call, freed on every way out
+    std::vector<void *> ptrs;
+    ~DevBuf()
+    {
+        for (void *p : ptrs) (void)hipFree(p);
+    }
+    template <typename T>
+    hipError_t get(T **out, size_t count)
+    {
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, count * sizeof(T) + 256);
+        if (e == hipSuccess) ptrs.push_back(p);
+        *out = (T *)p;
+        return e;
+    }
+};
+} // namespace
+
+extern "C" int vlq_kmeans(const float *d_x, int64_t nt, int32_t d, int32_t k, int32_t iters, float *d_centroids,
+                          int32_t *d_assign, int32_t *d_counts, void *stream)
+{
+    if (!d_x || !d_centroids) return fail(VLQ_EINVAL, "d_x and d_centroids must not be NULL");
+    if (d < 1 || d > VLQ_MAX_DIM) return fail(VLQ_EINVAL, "d = %d outside [1, %d]", d, VLQ_MAX_DIM);
+    if (k < 1) return fail(VLQ_EINVAL, "k = %d must be positive", k);
+    if (nt < 1 || nt > 0x7FFFFFFF) return fail(VLQ_EINVAL, "nt = %lld outside [1, 2^31)", (long long)nt);
+    if (iters < 0) return fail(VLQ_EINVAL, "iters = %d is negative", iters);
+    hipStream_t st = (hipStream_t)stream;
+    const int D = d;
+    const int64_t chunk = nt < ENC_CHUNK ? nt : ENC_CHUNK;
+    const int nsplit = coarse_gemm_nn_splits((int)chunk, k);
+    const char *env = getenv("VLQ_COARSE_FP32");
+    const bool bf16 = coarse_bf16_supported(D) && !(env && env[0] == '1');
+    int shift = 62;
+    while (shift > 0 && ((int64_t)1 << (62 - shift)) < nt) --shift;
+
+    DevBuf buf;
+    float *xn, *cn;
+    uint64_t *cand;
+    int32_t *assign, *cnt, *flag;
+    long long *sums;
+    uint32_t *absmax;
+    uint8_t *ximg = nullptr, *cimg = nullptr;
+    HIPCHK(buf.get(&xn, (size_t)chunk));
+    HIPCHK(buf.get(&cn, (size_t)k));
+    HIPCHK(buf.get(&cand, (size_t)chunk * nsplit * VLQ_NN_CANDS));
+    HIPCHK(buf.get(&assign, (size_t)nt));
+    HIPCHK(buf.get(&cnt, (size_t)k));
+    HIPCHK(buf.get(&flag, 64));
+    HIPCHK(buf.get(&sums, (size_t)k * D));
+    HIPCHK(buf.get(&absmax, 64));
+    if (bf16) {
+        HIPCHK(buf.get(&ximg, coarse_bf16_image_bytes(chunk, D)));
+        HIPCHK(buf.get(&cimg, coarse_bf16_image_bytes(k, D)));
+    }
+    HIPCHK(hipMemsetAsync(absmax, 0, 4, st));
+    launch_absmax(d_x, nt * D, absmax, st);
+    LAUNCHCHK();
+
+    // nearest centroid of every vector (Eq. 2): the encoder's shortlist + exact re-evaluation
+    auto assign_all = [&]() -> int {
+        launch_row_norms(d_centroids, k, D, cn, st);
+        LAUNCHCHK();
+        if (bf16) {
+            launch_split_bf16(d_centroids, k, D, cimg, flag, st);
+            LAUNCHCHK();
+        }
+        for (int64_t s = 0; s < nt; s += chunk) {
+            const int64_t n = nt - s < chunk ? nt - s : chunk;
+            const float *x = d_x + s * D;
+            launch_row_norms(x, n, D, xn, st);
+            LAUNCHCHK();
+            EncodeArgs a = {};
+            if (bf16) {
+                launch_split_bf16(x, n, D, ximg, flag + 1, st);
+                LAUNCHCHK();
+                HIPCHK((hipError_t)launch_coarse_gemm_nn_bf16(ximg, flag + 1, (int)n, cimg, k, D, xn, cn, cand, nsplit,
+                                                              &a.band_norm, &a.band_dist, st));
+            } else {
+                launch_coarse_gemm_nn(x, (int)n, d_centroids, k, D, xn, cn, cand, nsplit, st);
+                a.band_norm = VLQ_FP32_BAND_NORM;
+                a.band_dist = 0.f;
+            }
+            LAUNCHCHK();
+            a.X = x;
+            a.nb = n;
+            a.D = D;
+            a.k = k;
+            a.n = 0;
+            a.m = 1;
+            a.C = d_centroids;
+            a.cand = cand;
+            a.nsplit = nsplit;
+            a.cell = assign + s;
+            launch_encode_finish(a, st);
+            LAUNCHCHK();
+        }
+        return VLQ_OK;
+    };
+    for (int it = 0; it < iters; ++it) {
+        int rc = assign_all();
+        if (rc) return rc;
+        HIPCHK(hipMemsetAsync(cnt, 0, (size_t)k * 4, st));
+        HIPCHK(hipMemsetAsync(sums, 0, (size_t)k * D * 8, st));
+        launch_kmeans_accumulate(d_x, nt, D, assign, absmax, shift, sums, cnt, st);
+        LAUNCHCHK();
+        launch_kmeans_update(d_centroids, k, D, sums, cnt, absmax, shift, st);
+        LAUNCHCHK();
+    }
+    if (d_assign || d_counts) {
+        int rc = assign_all();
+        if (rc) return rc;
+        if (d_assign) HIPCHK(hipMemcpyAsync(d_assign, assign, (size_t)nt * 4, hipMemcpyDeviceToDevice, st));
+        if (d_counts) {
+            // counts only: the accumulation kernel is run over a one-dimensional view of the sample
+            HIPCHK(hipMemsetAsync(cnt, 0, (size_t)k * 4, st));
+            HIPCHK(hipMemsetAsync(sums, 0, (size_t)k * 8, st));
+            launch_kmeans_accumulate(d_x, nt, 1, assign, absmax, shift, sums, cnt, st);
+            LAUNCHCHK();
+            HIPCHK(hipMemcpyAsync(d_counts, cnt, (size_t)k * 4, hipMemcpyDeviceToDevice, st));
+        }
+    }
+    HIPCHK(hipStreamSynchronize(st)); // the temporaries are freed on return
+    return VLQ_OK;
 }
 
 static int grow_staging(vlq_index *idx, int64_t need, hipStream_t st)

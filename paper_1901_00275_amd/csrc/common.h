@@ -230,8 +230,17 @@ struct EncodeArgs {
     float band_norm, band_dist; // error band of the shortlist's distances
     int32_t *cell, *edge;
     uint8_t *lamq, *codes;
+    float *res; // optional [nb x D]: the residual x - ((1 - l) c_i + l s_ij) of Eq. 12
 };
+// S == nullptr: only the nearest centroid is determined (a.cell must be given)
 void launch_encode_finish(const EncodeArgs &a, hipStream_t st);
+
+// Lloyd iteration pieces (train.hip)
+void launch_absmax(const float *X, int64_t count, uint32_t *out_bits, hipStream_t st);
+void launch_kmeans_accumulate(const float *X, int64_t nb, int D, const int32_t *assign, const uint32_t *absmax_bits,
+                              int shift, long long *sums, int32_t *cnt, hipStream_t st);
+void launch_kmeans_update(float *C, int k, int D, const long long *sums, const int32_t *cnt,
+                          const uint32_t *absmax_bits, int shift, hipStream_t st);
 
 // inverted lists
 void launch_iota_i32(int32_t *p, int64_t n, int32_t start, hipStream_t st);

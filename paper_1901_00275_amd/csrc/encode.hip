@@ -64,6 +64,10 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
         }
         const int cell = (int)(uint32_t)bk;
         const float av = ord2f((uint32_t)(bk >> 32));
+        if (!a.S) { // nearest centroid only (Lloyd iterations)
+            if (lane == 0) a.cell[gid] = cell;
+            continue;
+        }
         // line quantisation inside the cell
         int bj = 0;
         float bl = 0.f, bd2 = INFINITY;
@@ -86,7 +90,9 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
         const float *sj = a.C + (int64_t)a.S[(int64_t)cell * n + bj] * D;
         for (int d = lane; d < D; d += 64) {
             const float c = ci[d];
-            x[d] = x[d] - fmaf(lh, sj[d] - c, c);
+            const float r = x[d] - fmaf(lh, sj[d] - c, c);
+            x[d] = r;
+            if (a.res) a.res[gid * D + d] = r;
         }
         if (lane == 0) {
             if (a.cell) a.cell[gid] = cell;

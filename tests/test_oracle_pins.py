@@ -425,3 +425,56 @@ def test_memory_figures(oracle_mod):
     assert oracle_mod.second_level_vq_bytes(2 ** 16, 32, 128) // oracle_mod.graph_bytes(2 ** 16, 32) == 64  # "1/64"
     # Table 4 prints 13.55 GB for k = 2^16; the formula gives that to 0.1 GB with n = 32
     assert oracle_mod.index_bytes(10 ** 9, 2 ** 16, 32, 128, 8) / 1e9 == pytest.approx(13.55, abs=0.1)
+
+
+# ---------------------------------------------------------------------------
+# training helpers (Sec. 2.1 / Sec. 5: codebooks by k-means; Eq. 12 residuals)
+# ---------------------------------------------------------------------------
+def test_lloyd_step_hand_example_and_textbook_routine(oracle_mod):
+    # four points on a line, two centroids: {0, 1} and {10, 11} -> means 0.5 and 10.5
+    X = np.array([[0.0], [1.0], [10.0], [11.0]], np.float32)
+    C0 = np.array([[0.0], [10.0]], np.float32)
+    C1, cell, _ = oracle_mod.lloyd_step(C0, X)
+    assert cell.tolist() == [0, 0, 1, 1] and np.allclose(C1[:, 0], [0.5, 10.5])
+    # a centroid without members stays; an exact tie goes to the smaller index
+    C0 = np.array([[0.0], [2.0], [100.0]], np.float32)
+    X = np.array([[1.0], [-1.0]], np.float32)
+    C1, cell, _ = oracle_mod.lloyd_step(C0, X)
+    assert cell.tolist() == [0, 0] and np.allclose(C1[:, 0], [0.0, 2.0, 100.0])
+    # against scikit-learn's Lloyd, one iteration from the same initial centroids
+    from sklearn.cluster import KMeans
+
+    rng = np.random.default_rng(5)
+    X = rng.normal(size=(3000, 12)).astype(np.float32) + rng.integers(0, 6, size=(3000, 1)).astype(np.float32) * 3
+    C0 = X[rng.choice(3000, 40, replace=False)].copy()
+    C1, cell, _ = oracle_mod.lloyd_step(C0, X)
+    km = KMeans(n_clusters=40, init=C0.astype(np.float64), n_init=1, max_iter=1, algorithm="lloyd", tol=0.0).fit(X.astype(np.float64))
+    assert np.allclose(km.cluster_centers_, C1, rtol=1e-6, atol=1e-6)
+    # the k-means objective never increases from one iteration to the next
+    obj = []
+    Cc = C0.astype(np.float64)
+    for _ in range(4):
+        Cn, cell, cd = oracle_mod.lloyd_step(Cc.astype(np.float32), X)
+        obj.append(cd[:, 0].sum())
+        Cc = Cn
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(obj, obj[1:]))
+
+
+def test_line_residual_is_the_vector_from_the_anchor(oracle_mod):
+    pr = problem(N=600, k=16, n=4, m=4, G=4, nq=5, D=8)
+    S, E = oracle_mod.graph(pr.C, pr.n)
+    enc = oracle_mod.encode(pr.C, S, E, pr.P, pr.X)
+    R = oracle_mod.line_residual(pr.C, S, pr.X, enc.cell, enc.edge, enc.lamq)
+    # anchor + residual gives the vector back; reconstruct() = anchor + codewords, so
+    # x - reconstruct = residual - codewords
+    cw = np.stack([pr.P[p][enc.codes[:, p]] for p in range(pr.m)], 1).reshape(len(pr.X), -1)
+    Xh = oracle_mod.reconstruct(pr.C, S, pr.P, enc.cell, enc.edge, enc.lamq, enc.codes)
+    assert np.allclose(pr.X - Xh, R - cw, atol=1e-9)
+    # the anchor lies on the line through c_i and s_ij: (x - r - c_i) is parallel to (s_ij - c_i)
+    anchor = pr.X - R
+    v = anchor - pr.C[enc.cell]
+    e = pr.C[S[enc.cell, enc.edge]] - pr.C[enc.cell]
+    cross = (v * v).sum(1) * (e * e).sum(1) - ((v * e).sum(1)) ** 2
+    assert (np.abs(cross) <= 1e-6 * (1 + (v * v).sum(1) * (e * e).sum(1))).all()
+    # and never farther from x than the centroid (the grid contains 0)
+    assert ((R * R).sum(1) <= ((pr.X - pr.C[enc.cell]) ** 2).sum(1) * (1 + 1e-9) + 1e-9).all()
