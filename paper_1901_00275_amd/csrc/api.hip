@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -596,7 +597,7 @@ extern "C" int vlq_index_add_encoded(vlq_index_t *idx, const int32_t *d_cell, co
 // ---------------------------------------------------------------------------
 // finalize
 // ---------------------------------------------------------------------------
-#define MAX_LONG 1024
+#define MAX_LONG (1 << 20)
 
 extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
 {
@@ -625,6 +626,7 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
     plan.take<int32_t>((size_t)nl);
     plan.take<int32_t>((size_t)nl);
     plan.take<int32_t>(MAX_LONG + 1);
+    plan.take<int32_t>(MAX_LONG + 1);
     int rc = ws_reserve(idx, plan.off + 256);
     if (rc) return rc;
     Bump b(idx->ws);
@@ -632,6 +634,8 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
     int32_t *cursor = b.take<int32_t>((size_t)nl);
     int32_t *longs = b.take<int32_t>(MAX_LONG + 1);
     int32_t *n_long = longs + MAX_LONG;
+    int32_t *longs2 = b.take<int32_t>(MAX_LONG + 1);
+    int32_t *n_long2 = longs2 + MAX_LONG;
     HIPCHK(hipMemsetAsync(cnt, 0, (size_t)nl * 4, st));
     HIPCHK(hipMemsetAsync(cursor, 0, (size_t)nl * 4, st));
     launch_list_histogram(idx->st_label, N, cnt, st);
@@ -641,6 +645,10 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
     launch_list_scatter(idx->st_label, idx->st_ids, idx->st_codes, idx->st_lam, N, m, idx->off, cursor, idx->ids,
                         idx->codes, idx->lam, st);
     LAUNCHCHK();
+    // Per-list order by id in three tiers: up to 1 024 points in a 64-thread workgroup's LDS; the
+    // longer ones it reports go to 256-thread workgroups with up to 150 KB of LDS; what is longer
+    // still is sorted in global memory, one list at a time.
+    std::vector<int64_t> hoff; // host copy of the offsets, fetched only if the third tier is needed
     for (int round = 0; round < 1 << 20; ++round) {
         HIPCHK(hipMemsetAsync(n_long, 0, 4, st));
         launch_list_sort(idx->off, nl, m, idx->ids, idx->codes, idx->lam, longs, n_long, MAX_LONG, st);
@@ -649,24 +657,43 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
         HIPCHK(hipMemcpyAsync(&hn, n_long, 4, hipMemcpyDeviceToHost, st));
         HIPCHK(hipStreamSynchronize(st));
         if (hn == 0) break;
-        const int take = hn < MAX_LONG ? hn : MAX_LONG;
-        std::vector<int32_t> hl(take);
-        HIPCHK(hipMemcpy(hl.data(), longs, (size_t)take * 4, hipMemcpyDeviceToHost));
-        for (int i = 0; i < take; ++i) {
-            int64_t be[2];
-            HIPCHK(hipMemcpy(be, idx->off + hl[i], 16, hipMemcpyDeviceToHost));
-            const int64_t len = be[1] - be[0];
-            int64_t sz = 1;
-            while (sz < len) sz <<= 1;
+        int take = hn < MAX_LONG ? hn : MAX_LONG;
+        if (list_sort_mid_max(m) > 0) {
+            HIPCHK(hipMemsetAsync(n_long2, 0, 4, st));
+            launch_list_sort_mid(idx->off, m, longs, take, idx->ids, idx->codes, idx->lam, longs2, n_long2, MAX_LONG, st);
+            LAUNCHCHK();
+            int32_t hn2 = 0;
+            HIPCHK(hipMemcpyAsync(&hn2, n_long2, 4, hipMemcpyDeviceToHost, st));
+            HIPCHK(hipStreamSynchronize(st));
+            take = hn2; // at most `take` <= MAX_LONG lists went in
+        }
+        if (take > 0) {
+            std::vector<int32_t> hl(take);
+            HIPCHK(hipMemcpy(hl.data(), list_sort_mid_max(m) > 0 ? longs2 : longs, (size_t)take * 4, hipMemcpyDeviceToHost));
+            if (hoff.empty()) {
+                hoff.resize((size_t)nl + 1);
+                HIPCHK(hipMemcpy(hoff.data(), idx->off, ((size_t)nl + 1) * 8, hipMemcpyDeviceToHost));
+            }
+            int64_t maxlen = 0;
+            for (int i = 0; i < take; ++i) maxlen = std::max(maxlen, hoff[hl[i] + 1] - hoff[hl[i]]);
+            int64_t maxsz = 1;
+            while (maxsz < maxlen) maxsz <<= 1;
             uint64_t *skeys = nullptr;
             uint8_t *spay = nullptr;
-            HIPCHK(hipMalloc(&skeys, (size_t)sz * 8));
-            HIPCHK(hipMalloc(&spay, (size_t)len * (m + 1)));
-            launch_long_list_sort_at(be[0], len, m, idx->ids, idx->codes, idx->lam, skeys, spay, st);
-            LAUNCHCHK();
-            HIPCHK(hipStreamSynchronize(st));
-            HIPCHK(hipFree(skeys));
-            HIPCHK(hipFree(spay));
+            HIPCHK(hipMalloc(&skeys, (size_t)maxsz * 8));
+            hipError_t e2 = hipMalloc(&spay, (size_t)maxlen * (m + 1));
+            if (e2 != hipSuccess) {
+                (void)hipFree(skeys);
+                HIPCHK(e2);
+            }
+            for (int i = 0; i < take; ++i) // same stream: the scratch is reused list after list
+                launch_long_list_sort_at(hoff[hl[i]], hoff[hl[i] + 1] - hoff[hl[i]], m, idx->ids, idx->codes, idx->lam,
+                                         skeys, spay, st);
+            hipError_t e3 = hipStreamSynchronize(st);
+            (void)hipFree(skeys);
+            (void)hipFree(spay);
+            HIPCHK(e3);
+            HIPCHK(hipGetLastError());
         }
         if (hn <= MAX_LONG) break;
     }

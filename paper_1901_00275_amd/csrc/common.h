@@ -257,5 +257,9 @@ void launch_list_static(const int64_t *off, int64_t nl, int n, int D, int m, con
                         float lam_zero, float *sx, hipStream_t st);
 void launch_list_sort(const int64_t *off, int64_t nl, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
                       int32_t *long_lists, int32_t *n_long, int max_long, hipStream_t st);
+// second tier of the per-list sort: the reported lists of up to list_sort_mid_max(m) points (0: tier unavailable)
+int list_sort_mid_max(int m);
+void launch_list_sort_mid(const int64_t *off, int m, const int32_t *in_lists, int n_in, int32_t *ids, uint8_t *codes,
+                          uint8_t *lam, int32_t *out_lists, int32_t *n_out, int max_out, hipStream_t st);
 void launch_long_list_sort_at(int64_t beg, int64_t len, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
                               uint64_t *scratch_keys, uint8_t *scratch_payload, hipStream_t st);

@@ -183,6 +183,65 @@ void launch_list_sort(const int64_t *off, int64_t nl, int m, int32_t *ids, uint8
                        n_long, max_long);
 }
 
+// Second tier: the lists the 64-thread pass reported (more than SORT_MAX points), one
+// 256-thread workgroup each, keys and payload in up to 150 KB of LDS.  Lists beyond mid_max
+// points are passed on to the third tier.
+__global__ __launch_bounds__(256) void k_list_sort_mid(const int64_t *__restrict__ off, int m, int mid_max,
+                                                       const int32_t *__restrict__ in_lists, int n_in,
+                                                       int32_t *__restrict__ ids, uint8_t *__restrict__ codes,
+                                                       uint8_t *__restrict__ lam, int32_t *__restrict__ out_lists,
+                                                       int32_t *__restrict__ n_out, int max_out)
+{
+    extern __shared__ unsigned char smem[];
+    uint64_t *keys = (uint64_t *)smem;           // [mid_max]
+    uint8_t *pay = (uint8_t *)(keys + mid_max);  // [mid_max * (m + 1)]
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x >= n_in) return;
+    const int64_t l = in_lists[blockIdx.x];
+    const int64_t beg = off[l];
+    const int64_t len = off[l + 1] - beg;
+    if (len > mid_max) {
+        if (tid == 0) {
+            const int p = atomicAdd(n_out, 1);
+            if (p < max_out) out_lists[p] = (int32_t)l;
+        }
+        return;
+    }
+    const int sz = next_pow2_dev((int)len);
+    for (int i = tid; i < sz; i += 256)
+        keys[i] = i < len ? (((uint64_t)(uint32_t)ids[beg + i] << 32) | (uint32_t)i) : KEY_MAX;
+    for (int64_t i = tid; i < len * m; i += 256) pay[i] = codes[beg * m + i];
+    for (int i = tid; i < len; i += 256) pay[len * m + i] = lam[beg + i];
+    __syncthreads();
+    block_bitonic_sort<256>(keys, sz, tid);
+    for (int i = tid; i < len; i += 256) {
+        const uint64_t key = keys[i];
+        const int src = (int)(uint32_t)key;
+        ids[beg + i] = (int32_t)(uint32_t)(key >> 32);
+        lam[beg + i] = pay[len * m + src];
+        for (int p = 0; p < m; ++p) codes[(beg + i) * m + p] = pay[src * m + p];
+    }
+}
+
+int list_sort_mid_max(int m)
+{
+    // keys (8 B) + payload (m + 1 B) per point within 150 KB, as a power of two, at least 2 * SORT_MAX
+    int mm = 8192;
+    while (mm > 2 * SORT_MAX && (size_t)mm * (8 + m + 1) > 150 * 1024) mm >>= 1;
+    return (size_t)mm * (8 + m + 1) <= 150 * 1024 ? mm : 0;
+}
+
+void launch_list_sort_mid(const int64_t *off, int m, const int32_t *in_lists, int n_in, int32_t *ids, uint8_t *codes,
+                          uint8_t *lam, int32_t *out_lists, int32_t *n_out, int max_out, hipStream_t st)
+{
+    const int mm = list_sort_mid_max(m);
+    if (n_in <= 0 || mm == 0) return;
+    const size_t smem = (size_t)mm * (8 + m + 1);
+    (void)hipFuncSetAttribute((const void *)k_list_sort_mid, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(k_list_sort_mid, dim3((unsigned)n_in), dim3(256), smem, st, off, m, mm, in_lists, n_in, ids,
+                       codes, lam, out_lists, n_out, max_out);
+}
+
 // A list too long for LDS: bitonic sort of (id, position) keys in global memory
 // by a single workgroup, then the payload is permuted through a scratch copy.
 __global__ __launch_bounds__(1024) void k_long_list_sort(int64_t beg, int64_t len, int64_t sz, int m,

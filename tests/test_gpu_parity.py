@@ -357,10 +357,12 @@ def test_edge_cases(vlq, oracle_mod):
         vlq.vlq_index_free(idx)
 
 
-def test_degenerate_data(vlq, oracle_mod):
-    """All base vectors identical: one long list, every distance tied, order by id."""
+@pytest.mark.parametrize("copies", [5000, 20000])
+def test_degenerate_data(vlq, oracle_mod, copies):
+    """All base vectors identical: one long list (sorted by id in the second / third tier of the
+    per-list sort), every distance tied, order by id."""
     pr = problem(N=3000, k=32, n=4, m=8, G=8, nq=40, D=32)
-    X = np.repeat(pr.X[:1], 5000, axis=0)
+    X = np.repeat(pr.X[:1], copies, axis=0)
     idx = make_index(vlq, pr, base=X)
     try:
         S, E = oracle_mod.graph(pr.C, pr.n)
