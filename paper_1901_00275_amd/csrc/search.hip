@@ -436,7 +436,7 @@ __global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, co
     }
 }
 
-#define ND_PCH 32 // pairs per workgroup
+#define ND_PCH 32 // most pairs per workgroup
 
 // The pairs, ordered by cell, are cut into runs of ND_PCH; a workgroup walks its run cell by
 // cell (a popular cell spreads over many workgroups, a run of rarely probed cells costs one
@@ -444,7 +444,7 @@ __global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, co
 __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict__ Q, int D,
                                                          const float *__restrict__ C,
                                                          const int32_t *__restrict__ S, int n, int k, int w1,
-                                                         const int32_t *__restrict__ cells,
+                                                         int pch, const int32_t *__restrict__ cells,
                                                          const int64_t *__restrict__ poff,
                                                          const int32_t *__restrict__ pairs,
                                                          float *__restrict__ bq)
@@ -454,9 +454,9 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane >> 4, l16 = lane & 15;
     const int64_t np = poff[k]; // pairs with a valid cell
-    const int64_t pbeg = (int64_t)blockIdx.x * ND_PCH;
+    const int64_t pbeg = (int64_t)blockIdx.x * pch;
     if (pbeg >= np) return;
-    const int cntp = (int)min((int64_t)ND_PCH, np - pbeg);
+    const int cntp = (int)min((int64_t)pch, np - pbeg);
     if (tid < cntp) {
         const int p = pairs[pbeg + tid];
         sp[tid] = p;
@@ -544,8 +544,9 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
 
 bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1)
 {
-    // worth it once a cell is probed about twice per batch; the neighbour rows must fit in LDS
-    return (int64_t)nq * w1 >= 2 * (int64_t)k && (size_t)n * D * 4 <= 65536;
+    // the neighbour rows of a cell must fit in LDS
+    (void)nq; (void)k; (void)w1;
+    return (size_t)n * D * 4 <= 65536;
 }
 
 size_t neighbour_dists_workspace(int nq, int k, int n, int w1)
@@ -588,8 +589,12 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         const size_t rows_bytes = (size_t)n * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
-        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)((np + ND_PCH - 1) / ND_PCH)), dim3(256), rows_bytes, st, Q,
-                           D, C, S, n, k, w1, cells, poff, pairs, bq);
+        // runs of 32 pairs for large batches; shorter runs (down to one pair per workgroup) keep
+        // all CUs busy when the batch is small
+        int pch = (int)(np / 1024);
+        pch = pch < 1 ? 1 : (pch > ND_PCH ? ND_PCH : pch);
+        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)((np + pch - 1) / pch)), dim3(256), rows_bytes, st, Q, D,
+                           C, S, n, k, w1, pch, cells, poff, pairs, bq);
         bpre = bq;
     }
     int sz = next_pow2(w1 * n);
