@@ -148,7 +148,9 @@ int vlq_index_reserve(vlq_index_t *idx, int64_t total);
 /*
  * Build the inverted lists from everything staged so far (Sec. 4: list lengths,
  * ids, codes and lambda bytes; list l = cell * n + edge; ascending id inside a
- * list).  Synchronises the stream.
+ * list), and per stored point the query-independent part of its ADC distance
+ * (||q2||^2 + 2<q1,q2> + (l^2 - l) c of Eq. 15-17, 4 bytes) that the scan streams
+ * with the code.  Synchronises the stream.
  */
 int vlq_index_finalize(vlq_index_t *idx, void *stream);
 
@@ -162,9 +164,14 @@ int vlq_index_params(const vlq_index_t *idx, vlq_params_t *out);
  *   w1 nearest cells by ||y - c||^2, 1 <= w1 <= nlist;
  *   among their w1*n sub-regions the w2 with the smallest distance from y to the
  *   line l(c_i, s_ij) (Eq. 7 at y's own lambda, Eq. 8), 1 <= w2 <= w1*n;
- *   for every point of those lists the distance of Eq. 14, evaluated through
- *   per-query lookup tables (Eq. 16-17 regrouped, 2m lookups per point);
- *   the K smallest by (distance, id).
+ *   for every point of those lists the distance of Eq. 14, evaluated as
+ *   s_x + a + l (b - a) - sum_p T[p][code_p]: the stored per-point term, the two
+ *   coarse distances of the sub-region, and one per-query table of 2 <y^p, codeword>
+ *   (Eq. 16-17 regrouped; m lookups per point.  Shapes outside m in {8, 16},
+ *   K <= 128 use per-cell / per-sub-region tables with 2m lookups);
+ *   the K smallest by (distance, id); among points whose fp32 distances are
+ *   exactly equal at the K-th place the earlier list position is kept.
+ * The result of a query does not depend on the other queries of the batch.
  * Outputs row-major [nq x K], ascending; rows with fewer than K candidates are
  * padded with (+inf, -1).  nq = 0 is a no-op.  Does not synchronise.
  */
