@@ -1,5 +1,6 @@
-"""Full-size check of the mid SIFT-like configuration (10^7 points, k = 16 384, n = 32, m = 8,
-10 000 queries, w1 = 64, w2 = 512, K = 100) in the launch configuration that bench.py times.
+"""Full-size checks of the mid SIFT-like configuration (10^7 points, D = 128, k = 16 384, n = 32,
+m = 8) and the mid DEEP-like one (10^8 points, D = 96, k = 65 536, n = 32, m = 16), 10 000 queries,
+w1 = 64, w2 = 512, K = 100, in the launch configuration that bench.py times.
 The oracle cannot encode 10^7 points, so it is used on samples it can compute one by one; all of its
 inputs come from the seeded generators (raw vectors are regenerated from the seed by id):
 
@@ -52,11 +53,12 @@ def _oracle_encode(oracle, pr, X):
     return oracle.encode(pr.C, S, E, pr.P, X), S, E
 
 
-def test_mid_sift_sampled(vlq, oracle_mod):
-    cfg = workloads.CONFIGS["mid_sift"]
+@pytest.mark.parametrize("name", ["mid_sift", "mid_deep"])
+def test_mid_configurations_sampled(vlq, oracle_mod, name):
+    cfg = workloads.CONFIGS[name]
     wl = workloads.materialise(vlq, cfg, DEV, log=lambda *a: print(*a, flush=True))
     try:
-        pr = Problem("sift", None, wl.Y.cpu().numpy(), wl.C.cpu().numpy(), wl.P.cpu().numpy(), cfg.n)
+        pr = Problem(cfg.kind, None, wl.Y.cpu().numpy(), wl.C.cpu().numpy(), wl.P.cpu().numpy(), cfg.n)
         rng = np.random.default_rng(7)
 
         # ---- encoding of sampled base vectors ----
