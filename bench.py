@@ -167,7 +167,7 @@ def main():
     achieved = nbytes / scan_avg_s / 1e9
     stage_ms = {s: round(v[0] / args.steps, 4) for s, v in prof.items()}
     result = {
-        "metric": "queries/sec at Recall@10 (VLQ-ADC search, 1 GPU); ADC-scan HBM GB/s vs peak",
+        "metric": "queries/sec at Recall@10 (1B pts, 1 GPU); ADC-scan HBM GB/s vs peak",
         "value": nq * args.steps / dt,
         "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
