@@ -310,7 +310,7 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
                                                           nsplit, &a.band_norm, &a.band_dist, st));
         } else {
             launch_coarse_gemm_nn(x, (int)cnt, idx->C, k, D, xn, idx->cn, cand, nsplit, st);
-            a.band_norm = VLQ_FP32_BAND_NORM;
+            a.band_norm = vlq_fp32_band_norm(D);
             a.band_dist = 0.f;
         }
         LAUNCHCHK();
@@ -447,7 +447,7 @@ extern "C" int vlq_kmeans(const float *d_x, int64_t nt, int32_t d, int32_t k, in
                                                               &a.band_norm, &a.band_dist, st));
             } else {
                 launch_coarse_gemm_nn(x, (int)n, d_centroids, k, D, xn, cn, cand, nsplit, st);
-                a.band_norm = VLQ_FP32_BAND_NORM;
+                a.band_norm = vlq_fp32_band_norm(D);
                 a.band_dist = 0.f;
             }
             LAUNCHCHK();

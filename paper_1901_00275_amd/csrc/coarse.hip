@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
                                                         const float *__restrict__ an,
                                                         const float *__restrict__ bn,
                                                         uint64_t *__restrict__ cand, int nsplit,
-                                                        int tiles_per_split, int vec)
+                                                        int tiles_per_split, int vec, float band_norm)
 {
     __shared__ float As[GT][GLD];
     __shared__ float Bs[GT][GLD];
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
             if (mn == KEY_MAX) continue;
             const float dmin = __uint_as_float((uint32_t)(mn >> 32));
             // rounding band of the GEMM form: a few ulp of ||a||^2 + ||b||^2 <= 3||a||^2 + 2 d
-            const float band = dmin + VLQ_FP32_BAND_NORM * (3.f * ra[i][r] + 2.f * dmin);
+            const float band = dmin + band_norm * (3.f * ra[i][r] + 2.f * dmin);
             uint64_t ks[2] = {b1[i][r], b2[i][r]};
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
@@ -275,7 +275,8 @@ void launch_coarse_gemm_nn(const float *A, int M, const float *B, int N, int D, 
     const int ntiles = (N + GT - 1) / GT;
     const int per = (ntiles + nsplit - 1) / nsplit;
     dim3 grid((unsigned)((M + GT - 1) / GT), (unsigned)nsplit);
-    hipLaunchKernelGGL(k_coarse_gemm_nn, grid, dim3(256), 0, st, A, M, B, N, D, an, bn, cand, nsplit, per, vec);
+    hipLaunchKernelGGL(k_coarse_gemm_nn, grid, dim3(256), 0, st, A, M, B, N, D, an, bn, cand, nsplit, per, vec,
+                       vlq_fp32_band_norm(D));
 }
 
 // ---------------------------------------------------------------------------
@@ -310,6 +311,7 @@ __global__ __launch_bounds__(256) void k_select_cells(const float *__restrict__ 
     const float *drow = dist + (int64_t)row * ld;
     const int self = self0 >= 0 ? self0 + row : -1;
     const int want = w + (self >= 0 ? 1 : 0); // the row itself is among its own nearest
+    const float bandn = 2.f * (float)(D + 8) * 5.9604645e-8f; // vlq_fp32_band_norm(D)
 
     for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)row * D + d];
 
@@ -348,7 +350,7 @@ __global__ __launch_bounds__(256) void k_select_cells(const float *__restrict__ 
     __syncthreads();
     for (int i = tid; i < k; i += 256) {
         const float d = drow[i];
-        if (d <= v + 4e-6f * (rq + cn[i])) {
+        if (d <= v + bandn * (rq + cn[i])) {
             int pos = atomicAdd(&sh_cnt, 1);
             if (pos < SEL_CAP) keys[pos] = (uint64_t)(uint32_t)i;
         }
@@ -501,6 +503,7 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
     const float *drow = dist + (int64_t)row * ld;
     const int self = self0 >= 0 ? self0 + row : -1;
     const int want = w + (self >= 0 ? 1 : 0);
+    const float bandn = 2.f * (float)(D + 8) * 5.9604645e-8f; // vlq_fp32_band_norm(D)
 
     for (int d = tid; d < D; d += SEL2_NT) yv[d] = Q[(int64_t)row * D + d];
     // raw buffer over the row: base, stride 0, size in bytes, dword data format
@@ -620,12 +623,12 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
     // ||c|| <= ||y|| + sqrt(d) bounds the centroid norm without touching memory; the exact
     // band (with the centroid's own norm) is applied to the few survivors below
     const float sq = sqrtf(rq) + sqrtf(vw);
-    const float wide = vw * (1.f + 1e-5f) + 4e-6f * (rq + sq * sq) * 1.5f;
+    const float wide = vw * (1.f + 1e-5f) + bandn * (rq + sq * sq) * 1.5f;
 #pragma unroll
     for (int e = 0; e < VPT; ++e) {
         if (!(selm >> e & 1) && v[e] <= wide) {
             const int i = e * SEL2_NT + tid;
-            if (v[e] <= vw + 4e-6f * (rq + cn[i])) {
+            if (v[e] <= vw + bandn * (rq + cn[i])) {
                 const int pos = atomicAdd(&sh_cnt, 1);
                 if (pos < SEL_CAP) keys[pos] = ((uint64_t)__float_as_uint(v[e]) << 32) | (uint32_t)i;
             }
@@ -641,7 +644,7 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
         uint64_t key = c < cnt ? keys[c] : KEY_MAX;
         const int i = (int)(uint32_t)key;
         bool inband = false;
-        if (c < cnt) inband = __uint_as_float((uint32_t)(key >> 32)) <= vw + 4e-6f * (rq + cn[i]);
+        if (c < cnt) inband = __uint_as_float((uint32_t)(key >> 32)) <= vw + bandn * (rq + cn[i]);
         float acc = 0.f;
         if (inband) {
             const float *rowp = C + (int64_t)i * D;

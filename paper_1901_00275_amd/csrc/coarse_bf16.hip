@@ -101,9 +101,16 @@ void launch_split_bf16(const float *X, int64_t rows, int D, void *img, int *any_
                        (u32x4 *)img, any_lo);
 }
 
-// Error of the split product relative to ||a||^2 + ||b||^2 <= 3 ||a||^2 + 2 d: minimum and
-// candidate each carry 2 * 3 * 2^-18 |a| |b| <= 3 * 2^-18 (||a||^2 + ||b||^2), rounded up.
-#define BF16_BAND_NORM 3e-5f
+// Error budget of one approximate value e = ||b||^2 - 2 <a, b>, D <= 128, worst case:
+//   representation: |v - hi - lo| <= 2^-18 |v| on both operands and the dropped lo.lo term give
+//     3 * 2^-18 |a||b| on the inner product, twice that on e                      (2.3e-5 |a||b|);
+//   fp32 accumulation of the 3 D products in any order: <= 3 D 2^-24 |a||b| on the inner
+//     product, twice that on e                                                     (4.6e-5 |a||b|);
+//   together < 7e-5 |a||b| <= 3.5e-5 (||a||^2 + ||b||^2).  A comparison involves two values, and
+//   ||a||^2 + ||b||^2 <= 3 ||a||^2 + 2 d for a column at distance d, hence the band
+//   7e-5 (3 ||a||^2 + 2 d).  (Typical errors are a factor sqrt(3 D) smaller; the band only
+//   decides how many columns are re-evaluated exactly, never the result.)
+#define BF16_BAND_NORM 7e-5f
 // Columns past the end of B get this "norm": finite, so that index bits can be planted
 // in the key, and beyond BF16_NO_KEY, from where on a key counts as absent.
 #define BF16_NO_COLUMN 3e38f

@@ -139,7 +139,11 @@ void launch_coarse_gemm_full(const float *A, int M, const float *B, int N, int D
 #define VLQ_NN_CANDS 8
 // Width of the band around the smallest distance d of a row a:
 // band_norm * (3 ||a||^2 + 2 d) + band_dist * (||a||^2 + d); the fp32 product has band_dist = 0.
-#define VLQ_FP32_BAND_NORM 4e-6f
+// fp32 product: each value ||a||^2 + ||b||^2 - 2 <a, b> is off by at most
+// (D + 8) 2^-24 (||a||^2 + ||b||^2): fp32 accumulation of D products in any order, doubled by
+// the factor -2 (2 D 2^-24 |a||b|), plus the rounding of the two norms and of the final sums.
+// A comparison involves two values, and ||a||^2 + ||b||^2 <= 3 ||a||^2 + 2 d.
+static inline float vlq_fp32_band_norm(int D) { return 2.f * (float)(D + 8) * 5.9604645e-8f; }
 int coarse_gemm_nn_splits(int M, int N);
 void launch_coarse_gemm_nn(const float *A, int M, const float *B, int N, int D, const float *an,
                            const float *bn, uint64_t *cand, int nsplit, hipStream_t st);
