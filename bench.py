@@ -195,6 +195,26 @@ def main():
             d2, p2, r2, w22 = timed(w, max(2, args.steps // 2), 1)
             sweep.append({"w1": w, "w2": w22, "queries_per_s": nq * max(2, args.steps // 2) / d2, **r2})
         result["config"]["sweep"] = sweep
+        # batch-size and K sweeps of the configuration (at the headline w1): the first nb queries of the batch
+        bs = []
+        for nb in cfg.batches:
+            for Kx in (cfg.Ks or (K,)):
+                Yb = wl.Y[:nb].contiguous()
+                odb = torch.empty(nb, Kx, device=dev)
+                oib = torch.empty(nb, Kx, dtype=torch.int32, device=dev)
+                reps = 20 if nb <= 256 else max(2, args.steps // 2)
+                for _ in range(2):
+                    vlq.vlq_search(wl.idx, Yb, nb, w1, w2, Kx, odb, oib)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    vlq.vlq_search(wl.idx, Yb, nb, w1, w2, Kx, odb, oib)
+                torch.cuda.synchronize()
+                d3 = (time.perf_counter() - t0) / reps
+                bs.append({"queries": nb, "K": Kx, "ms_per_call": d3 * 1e3, "queries_per_s": nb / d3,
+                           f"R@{Kx}": datagen.recall_at(oib, wl.gt[:nb], Kx)})
+        if bs:
+            result["config"]["batch_sweep"] = bs
     if not args.no_cpu_baseline:
         base, o_ids, ns = cpu_baseline(vlq, wl, w1, w2, torch)
         result["cpu_baseline"] = base

@@ -30,6 +30,8 @@ class Config:
     alpha: float = 0.25  # w2 = alpha * w1 * n (Sec. 3.3.1)
     w2_fixed: int = 0  # a stated number of sub-regions overrides alpha
     ntrain: int = 0
+    batches: tuple = ()  # query batch sizes of the configuration's batch sweep
+    Ks: tuple = ()  # result counts of the configuration's K sweep
 
     @property
     def D(self):
@@ -44,7 +46,8 @@ CONFIGS = {c.name: c for c in (
     Config("mid_sift", "sift", 10_000_000, 1_024, 10_000, 16_384, 32, 8, (8, 16, 32, 64), ntrain=1_000_000),
     Config("mid_deep", "deep", 100_000_000, 4_096, 10_000, 65_536, 32, 16, (16, 32, 64), ntrain=2_000_000),
     Config("billion_sift", "sift", 1_000_000_000, 16_384, 10_000, 65_536, 32, 8, (16, 32, 64), ntrain=2_000_000),
-    Config("billion_deep", "deep", 1_000_000_000, 16_384, 10_000, 65_536, 64, 16, (32, 64), ntrain=2_000_000),
+    Config("billion_deep", "deep", 1_000_000_000, 16_384, 10_000, 65_536, 64, 16, (32, 64), ntrain=2_000_000,
+           batches=(1, 16, 256, 10_000), Ks=(1, 10, 100)),
 )}
 
 
