@@ -24,8 +24,10 @@
  *  - Every function returns VLQ_OK (0) or a negative VLQ_E* code and never
  *    throws or aborts; on error no output is written and vlq_last_error()
  *    describes the failure (per thread).
- *  - An index may be used by one host thread at a time: search and encode
- *    use scratch memory owned by the index.
+ *  - An index may be used by one host thread at a time, and calls on one index
+ *    must be queued on one stream (or ordered by the caller): search and encode
+ *    use scratch memory owned by the index, which grows on demand (the first
+ *    call with a larger batch allocates device memory and synchronises).
  *  - Distances are squared L2 distances to the reconstructed point (Eq. 14).
  */
 #ifndef VLQ_H
