@@ -854,19 +854,42 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     return VLQ_OK;
 }
 
+// Batches beyond SEARCH_TILE queries are served tile by tile (every query is independent of the
+// rest of its batch), which bounds the scratch memory: the argument checks of the first tile
+// cover the whole call, so nothing is written when they fail.
+#define SEARCH_TILE 32768
+
+static int search_tiled(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2, int32_t K,
+                        float *d_out_dist, int32_t *d_out_ids, int32_t *d_cells, float *d_cell_dist, int32_t *d_sub,
+                        float *d_sub_score, hipStream_t st)
+{
+    if (nq <= SEARCH_TILE || !idx)
+        return search_impl(idx, d_q, nq, w1, w2, K, d_out_dist, d_out_ids, d_cells, d_cell_dist, d_sub, d_sub_score, st);
+    const int D = idx->p.d;
+    for (int64_t q0 = 0; q0 < nq; q0 += SEARCH_TILE) {
+        const int32_t n = (int32_t)(nq - q0 < SEARCH_TILE ? nq - q0 : SEARCH_TILE);
+        int rc = search_impl(idx, d_q ? d_q + q0 * D : nullptr, n, w1, w2, K, d_out_dist ? d_out_dist + q0 * K : nullptr,
+                             d_out_ids ? d_out_ids + q0 * K : nullptr, d_cells ? d_cells + q0 * w1 : nullptr,
+                             d_cell_dist ? d_cell_dist + q0 * w1 : nullptr, d_sub ? d_sub + q0 * w2 : nullptr,
+                             d_sub_score ? d_sub_score + q0 * w2 : nullptr, st);
+        if (rc) return rc;
+    }
+    return VLQ_OK;
+}
+
 extern "C" int vlq_search(const vlq_index_t *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2,
                           int32_t K, float *d_out_dist, int32_t *d_out_ids, void *stream)
 {
-    return search_impl(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, nullptr, nullptr,
-                       nullptr, nullptr, (hipStream_t)stream);
+    return search_tiled(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, nullptr, nullptr,
+                        nullptr, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int vlq_search_debug(const vlq_index_t *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2,
                                 int32_t K, float *d_out_dist, int32_t *d_out_ids, int32_t *d_cells,
                                 float *d_cell_dist, int32_t *d_sub, float *d_sub_score, void *stream)
 {
-    return search_impl(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, d_cells, d_cell_dist,
-                       d_sub, d_sub_score, (hipStream_t)stream);
+    return search_tiled(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, d_cells, d_cell_dist,
+                        d_sub, d_sub_score, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------

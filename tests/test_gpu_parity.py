@@ -259,6 +259,30 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
         vlq.vlq_index_free(idx)
 
 
+def test_large_batches_are_tiled_without_changing_results(vlq):
+    """More queries than one internal tile (32 768): the same rows as when the queries are sent in
+    pieces (a query's result does not depend on its batch)."""
+    pr = problem(N=3000, k=32, n=4, m=8, G=8, nq=40, D=32)
+    idx = make_index(vlq, pr, base=pr.X)
+    try:
+        rng = np.random.default_rng(3)
+        nq = 70001
+        Y = pr.Y[rng.integers(0, len(pr.Y), nq)] + rng.normal(scale=0.5, size=(nq, pr.D)).astype(np.float32)
+        Yd = dev(Y)
+        od = torch.empty(nq, 10, device=DEV)
+        oi = torch.empty(nq, 10, dtype=torch.int32, device=DEV)
+        vlq.vlq_search(idx, Yd, nq, 4, 6, 10, od, oi)
+        torch.cuda.synchronize()
+        for lo, hi in [(0, 5), (32760, 32780), (65530, 65545), (69990, 70001)]:
+            od2 = torch.empty(hi - lo, 10, device=DEV)
+            oi2 = torch.empty(hi - lo, 10, dtype=torch.int32, device=DEV)
+            vlq.vlq_search(idx, Yd[lo:hi].contiguous(), hi - lo, 4, 6, 10, od2, oi2)
+            torch.cuda.synchronize()
+            assert torch.equal(oi[lo:hi], oi2) and torch.equal(od[lo:hi], od2)
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_lists_layout_matches_oracle(vlq, oracle_mod):
     """vlq_index_add + finalize: the four list arrays of Sec. 4, ids ascending inside a list."""
     pr = problem(N=20011, k=100, n=7, m=8, G=16, nq=77)
