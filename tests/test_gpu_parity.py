@@ -238,6 +238,18 @@ def test_cell_selection_with_many_centroids(vlq, oracle_mod, monkeypatch, dup, f
             if dup:
                 ref = oracle_mod.select_smallest(dist[:20], w1)
                 assert (cells[:20] == ref).all()  # exact ties are ordered by index
+        if dup:
+            # hundreds of exactly equal line scores (the probed cells coincide, their edges have length
+            # zero, so every score is the cell distance): the cut is taken by label
+            w1, w2 = 100, 300
+            od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y[:20], w1, w2, 10)
+            Sg, Eg = gpu_graph(vlq, idx, pr2)
+            score, label = oracle_mod.subregion_scores(dist[:20], Sg, Eg.astype(np.float64), cells)
+            pick = oracle_mod.select_smallest(score, w2, key=label)
+            for q in range(20):
+                assert (cells[q] == oracle_mod.select_smallest(dist[q:q + 1], w1)[0]).all()
+                want = pick[q]  # with a key the oracle returns the keys (labels) of the selection
+                assert sorted(sub[q].tolist()) == sorted(want.tolist()), f"query {q}: sub-regions at an exact tie"
     finally:
         vlq.vlq_index_free(idx)
 
