@@ -72,3 +72,16 @@ def test_missing_library_fails_loudly(vlq, monkeypatch):
     monkeypatch.setattr(vlq, "LIB_PATH", "/nonexistent/libvlq.so")
     with pytest.raises(FileNotFoundError):
         vlq.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one GPU only: bench.py --gpus N (N > 1) exits with a message saying so,
+    before anything touches the GPU."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
