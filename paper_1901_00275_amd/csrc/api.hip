@@ -824,6 +824,13 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     a.lam = idx->lam;
     a.sx = idx->sx;
     a.desc = desc;
+    {
+        // lists of a few tens of points: several of them share a chunk of 64 lanes (the environment can
+        // force either form, which the tests use to cover both)
+        const char *pk = getenv("VLQ_SCAN_PACKED");
+        const int64_t nl = (int64_t)k * n;
+        a.packed = pk ? (pk[0] == '1') : (idx->ntotal < 64 * nl);
+    }
     a.lam_step = idx->lam_step;
     a.lam_zero = idx->lam_zero;
     a.scan_label = slab;

@@ -206,6 +206,7 @@ struct ScanArgs {
     const float *sx;   // per point: query-independent part of the distance (streaming scan)
     float lam_step, lam_zero;
     const uint4 *desc; // [nq x w2] {begin, length, a, b - a} per visited sub-region (streaming scan)
+    int packed;        // streaming scan: short lists, several per chunk of lanes
     const int32_t *scan_label;
     const float *scan_g;
     uint64_t *partial; // [nq x nsplit x K] when nsplit > 1

@@ -34,6 +34,8 @@
 #define SS_CH 8      // chunks of 64 points loaded ahead per wave
 #define SS_KP 128    // per-wave sorted list (K <= 128)
 #define SS_WSZ 256   // per-wave keys: list + candidate buffer
+#define SS_GL 16     // packed form: lists taken at a time
+#define SS_PCH 4     // packed form: chunks loaded ahead
 
 typedef __attribute__((address_space(3))) unsigned long long lds_u64;
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
@@ -60,7 +62,10 @@ __device__ __forceinline__ void wave_sort256(volatile lds_u64 *wk, int lane)
         }
 }
 
-template <int M>
+// PACKED: the lists are short (a few tens of points): a wave takes SS_GL lists at a time and lays
+// their points end to end over its lanes, so that a chunk of 64 lanes holds several lists; each
+// lane finds its list from the running lengths and carries its own a, b - a.
+template <int M, bool PACKED>
 __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint4 *__restrict__ desc)
 {
     // all LDS is static: the table sits at a fixed address, which folds into the lookups' offsets
@@ -123,6 +128,103 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     };
 
     uint64_t thr = KEY_MAX;
+    float thr_f = INFINITY;
+    // one chunk of 64 points: m table reads per point, the distance, and the candidates that pass
+    auto score_chunk = [&](const uint32_t (&cw)[M / 4], uint32_t lbv, float sxv, float av, float bav, uint32_t gpos,
+                           bool live) __attribute__((always_inline)) {
+        float ts = 0.f;
+#pragma unroll
+        for (int x = 0; x < M / 4; ++x)
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) {
+                const uint32_t byte_off = ((cw[x] >> (8 * bb)) & 255u) << 2;
+                ts += *(const float *)((const char *)(T + (x * 4 + bb) * 256) + byte_off);
+            }
+        const float l = ((float)lbv - a.lam_zero) * a.lam_step;
+        const float dist = (sxv - ts) + fmaf(l, bav, av);
+        // cheap test on the distance alone; the exact (distance, position) key only for the few that pass
+        bool pass = live && dist <= thr_f;
+        uint64_t mask = __ballot(pass);
+        if (mask) {
+            const uint64_t key = make_key(dist, gpos);
+            pass = pass && key < thr;
+            mask = __ballot(pass);
+            int np = __popcll(mask);
+            if (np && wcnt + np > SS_WSZ - SS_KP) {
+                merge_wave();
+                thr = sh_thr;
+                thr_f = thr == KEY_MAX ? INFINITY : ord2f((uint32_t)(thr >> 32));
+                pass = pass && key < thr;
+                mask = __ballot(pass);
+                np = __popcll(mask);
+            }
+            if (pass) wk[SS_KP + wcnt + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+            wcnt += np;
+        }
+    };
+    if (PACKED) {
+        // up to SS_GL lists per turn, fewer when the workgroup has few lists, so that all waves get some
+        int gl = (r1 - r0) / SS_NW;
+        gl = gl < 1 ? 1 : (gl > SS_GL ? SS_GL : gl);
+        for (;;) {
+            int s = 0;
+            if (lane == 0) s = atomicAdd(&sh_next, gl);
+            s = __builtin_amdgcn_readfirstlane(s);
+            if (s >= r1) break;
+            // lane i < gl holds the descriptor of list s + i
+            uint4 dsc = make_uint4(0u, 0u, 0u, 0u);
+            if (lane < gl && s + lane < r1) dsc = desc[(int64_t)q * a.w2 + s + lane];
+            const int len = max((int)dsc.y, 0);
+            int end = len; // inclusive prefix sum: where the list ends in the concatenation
+#pragma unroll
+            for (int o = 1; o < SS_GL; o <<= 1) {
+                const int t = __shfl_up(end, o, 64);
+                if (lane >= o) end += t;
+            }
+            const int start = end - len;
+            const int total = __builtin_amdgcn_readlane(end, SS_GL - 1);
+            if (total <= 0) continue;
+            int ends[SS_GL]; // uniform copies
+#pragma unroll
+            for (int i = 0; i < SS_GL; ++i) ends[i] = __builtin_amdgcn_readlane(end, i);
+            thr = sh_thr;
+            thr_f = thr == KEY_MAX ? INFINITY : ord2f((uint32_t)(thr >> 32));
+            for (int base = 0; base < total; base += 64 * SS_PCH) {
+                uint32_t cw[SS_PCH][M / 4];
+                uint32_t lb[SS_PCH], gp[SS_PCH];
+                float sv[SS_PCH], fav[SS_PCH], fbav[SS_PCH];
+#pragma unroll
+                for (int u = 0; u < SS_PCH; ++u) {
+                    if (base + 64 * u < total) { // uniform over the wave
+                        const int p = min(base + 64 * u + lane, total - 1); // idle lanes repeat the last point
+                        int j = 0; // the list that holds position p: the lists before it end at or before p
+#pragma unroll
+                        for (int i = 0; i < SS_GL - 1; ++i) j += ends[i] <= p;
+                        const uint32_t g = (uint32_t)__shfl((int)dsc.x, j, 64) + (uint32_t)(p - __shfl(start, j, 64));
+                        fav[u] = __uint_as_float((uint32_t)__shfl((int)dsc.z, j, 64));
+                        fbav[u] = __uint_as_float((uint32_t)__shfl((int)dsc.w, j, 64));
+                        gp[u] = g;
+                        const uint32_t *cp = (const uint32_t *)(a.codes + (size_t)g * M);
+                        if (M == 8) {
+                            const u32x2_t c2 = *(const u32x2_t *)cp;
+                            cw[u][0] = c2.x;
+                            cw[u][1] = c2.y;
+                        } else {
+                            const u32x4_t c4 = *(const u32x4_t *)cp;
+#pragma unroll
+                            for (int x = 0; x < M / 4; ++x) cw[u][x] = c4[x];
+                        }
+                        lb[u] = a.lam[g];
+                        sv[u] = a.sx[g];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < SS_PCH; ++u)
+                    if (base + 64 * u < total)
+                        score_chunk(cw[u], lb[u], sv[u], fav[u], fbav[u], gp[u], base + 64 * u + lane < total);
+            }
+        }
+    } else {
     for (;;) {
         int s = 0;
         if (lane == 0) s = atomicAdd(&sh_next, 1);
@@ -139,7 +241,7 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
         const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc((void *)(a.lam + beg), 0, len, 0x00020000);
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)(a.sx + beg), 0, len * 4, 0x00020000);
         thr = sh_thr;
-        float thr_f = thr == KEY_MAX ? INFINITY : ord2f((uint32_t)(thr >> 32));
+        thr_f = thr == KEY_MAX ? INFINITY : ord2f((uint32_t)(thr >> 32));
         for (int base = 0; base < len; base += 64 * SS_CH) {
             // ---- all loads of up to SS_CH chunks ----
             uint32_t cw[SS_CH][M / 4];
@@ -164,42 +266,13 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
             }
             // ---- score ----
 #pragma unroll
-            for (int u = 0; u < SS_CH; ++u) {
+            for (int u = 0; u < SS_CH; ++u)
                 if (base + 64 * u < len) {
                     const int within = base + 64 * u + lane;
-                    const bool live = within < len;
-                    float ts = 0.f;
-#pragma unroll
-                    for (int x = 0; x < M / 4; ++x)
-#pragma unroll
-                        for (int bb = 0; bb < 4; ++bb) {
-                            const uint32_t byte_off = ((cw[u][x] >> (8 * bb)) & 255u) << 2;
-                            ts += *(const float *)((const char *)(T + (x * 4 + bb) * 256) + byte_off);
-                        }
-                    const float l = ((float)lb[u] - a.lam_zero) * a.lam_step;
-                    const float dist = (sv[u] - ts) + fmaf(l, bav, av);
-                    // cheap test on the distance alone; the exact (distance, position) key only for the few that pass
-                    bool pass = live && dist <= thr_f;
-                    uint64_t mask = __ballot(pass);
-                    if (mask) {
-                        const uint64_t key = make_key(dist, beg + (uint32_t)within);
-                        pass = pass && key < thr;
-                        mask = __ballot(pass);
-                        int np = __popcll(mask);
-                        if (np && wcnt + np > SS_WSZ - SS_KP) {
-                            merge_wave();
-                            thr = sh_thr;
-                            thr_f = thr == KEY_MAX ? INFINITY : ord2f((uint32_t)(thr >> 32));
-                            pass = pass && key < thr;
-                            mask = __ballot(pass);
-                            np = __popcll(mask);
-                        }
-                        if (pass) wk[SS_KP + wcnt + __popcll(mask & ((1ull << lane) - 1ull))] = key;
-                        wcnt += np;
-                    }
+                    score_chunk(cw[u], lb[u], sv[u], av, bav, beg + (uint32_t)within, within < len);
                 }
-            }
         }
+    }
     }
 
     // ---- merge the eight wave lists; resolve ids; order by (distance, id) ----
@@ -230,7 +303,6 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     }
 }
 
-static size_t scan_stream_smem(int, int) { return 0; } // all LDS is static
 
 // Shapes served by this kernel; everything else takes the generic kernel.
 bool scan_stream_supported(const ScanArgs &a)
@@ -242,13 +314,17 @@ bool scan_stream_supported(const ScanArgs &a)
 void launch_scan_stream(const ScanArgs &a, hipStream_t st)
 {
     if (a.nq <= 0) return;
-    const size_t smem = scan_stream_smem(a.m, a.D);
     const dim3 grid((unsigned)(a.nq * a.nsplit));
+    const uint4 *desc = (const uint4 *)a.desc;
     if (a.m == 8) {
-        (void)hipFuncSetAttribute((const void *)k_scan_stream<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        hipLaunchKernelGGL((k_scan_stream<8>), grid, dim3(SS_NT), smem, st, a, (const uint4 *)a.desc);
+        if (a.packed)
+            hipLaunchKernelGGL((k_scan_stream<8, true>), grid, dim3(SS_NT), 0, st, a, desc);
+        else
+            hipLaunchKernelGGL((k_scan_stream<8, false>), grid, dim3(SS_NT), 0, st, a, desc);
     } else {
-        (void)hipFuncSetAttribute((const void *)k_scan_stream<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        hipLaunchKernelGGL((k_scan_stream<16>), grid, dim3(SS_NT), smem, st, a, (const uint4 *)a.desc);
+        if (a.packed)
+            hipLaunchKernelGGL((k_scan_stream<16, true>), grid, dim3(SS_NT), 0, st, a, desc);
+        else
+            hipLaunchKernelGGL((k_scan_stream<16, false>), grid, dim3(SS_NT), 0, st, a, desc);
     }
 }

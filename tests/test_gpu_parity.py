@@ -271,6 +271,33 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
         vlq.vlq_index_free(idx)
 
 
+@pytest.mark.parametrize("name", ["sift_ragged", "deep_m16"])
+def test_packed_and_per_list_scan_agree(vlq, monkeypatch, name):
+    """The streaming scan in its two forms - several short lists laid end to end over the lanes of a
+    wave, or one list at a time - computes the same keys: every output is identical.  (Indexes with
+    fewer than 64 points per list take the packed form by default, so the parity cases above run it;
+    this pins the other form to it, at m = 8 and m = 16.)"""
+    kw, w1, w2, K = CASES[name]
+    pr = problem(**kw)
+    idx = make_index(vlq, pr, base=pr.X)
+    try:
+        monkeypatch.setenv("VLQ_SCAN_PACKED", "1")
+        a = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        monkeypatch.setenv("VLQ_SCAN_PACKED", "0")
+        b = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+        # a single query is split over several workgroups in both forms
+        monkeypatch.setenv("VLQ_SCAN_PACKED", "1")
+        a = gpu_search(vlq, idx, pr.Y[:1], w1, w2, K)
+        monkeypatch.setenv("VLQ_SCAN_PACKED", "0")
+        b = gpu_search(vlq, idx, pr.Y[:1], w1, w2, K)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_large_batches_are_tiled_without_changing_results(vlq):
     """More queries than one internal tile (32 768): the same rows as when the queries are sent in
     pieces (a query's result does not depend on its batch)."""
