@@ -19,9 +19,10 @@
 //
 // Product kernel.  Workgroup = 256 threads = 4 waves, 128 rows of A against all
 // columns of its split; each wave owns a 64 x 64 quadrant (2 x 2 MFMA blocks).  The
-// 128 rows of A stay in LDS for the whole sweep (D <= 128: 64 KB); the pages of B
-// stream global -> registers (four steps ahead) -> a two-page-pair ring in LDS, one
-// barrier per step.  Two workgroups share a CU (2 x 80 KB of LDS), so one's
+// 128 rows of A are staged in LDS once (D <= 128: 64 KB) and every wave then keeps the hi
+// fragments of its 64 rows in registers for the whole sweep (the lo fragments, needed only for
+// real-valued rows, are read from LDS); the pages of B stream global -> registers (four steps
+// ahead) -> a two-page-pair ring in LDS, one barrier per step.  Two workgroups share a CU (2 x 80 KB of LDS), so one's
 // selection epilogue overlaps the other's MFMAs.
 #include "common.h"
 
@@ -225,6 +226,13 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     __syncthreads();
+    // the hi fragments of the wave's 64 rows for all steps: the same for every tile, kept in registers
+    bf16x8 ahr[SPT][2];
+#pragma unroll
+    for (int u = 0; u < SPT; ++u) {
+        ahr[u][0] = __builtin_bit_cast(bf16x8, Apages[u * 2 * PAGE + fa0]);
+        ahr[u][1] = __builtin_bit_cast(bf16x8, Apages[u * 2 * PAGE + fa1]);
+    }
     for (int tl = 0; tl < ntl; ++tl) {
         // column norms of this tile, asked for now and used after its last step
         const int64_t n0 = (int64_t)(t0 + tl) * BT;
@@ -248,8 +256,8 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             const u32x4 *ap = Apages + u * 2 * PAGE;
             const u32x4 *bp = ring + (u & 1) * 2 * PAGE;
             bf16x8 ah[2], bh[2], bl[2];
-            ah[0] = __builtin_bit_cast(bf16x8, ap[fa0]);
-            ah[1] = __builtin_bit_cast(bf16x8, ap[fa1]);
+            ah[0] = ahr[u][0];
+            ah[1] = ahr[u][1];
             bh[0] = __builtin_bit_cast(bf16x8, bp[fb0]);
             bh[1] = __builtin_bit_cast(bf16x8, bp[fb1]);
             bl[0] = __builtin_bit_cast(bf16x8, bp[PAGE + fb0]);
