@@ -298,6 +298,22 @@ def test_packed_and_per_list_scan_agree(vlq, monkeypatch, name):
         vlq.vlq_index_free(idx)
 
 
+def test_largest_supported_shapes(vlq, oracle_mod):
+    """The limits of include/vlq.h together: D = 1 024, m = 64, w1 = 512, w1 * n = 8 192 sub-regions ranked,
+    w2 = 2 048 visited, K = 1 024 (fp32 coarse product, generic scan)."""
+    pr = problem(N=4000, k=520, n=16, m=64, G=12, nq=4, D=1024, iters=2)
+    idx = make_index(vlq, pr)
+    try:
+        S, E = oracle_mod.graph(pr.C, pr.n)
+        enc, _ = check_encode(oracle_mod, pr, S, E, pr.X, gpu_encode(vlq, idx, pr.X, pr.m))
+        load_oracle_index(vlq, idx, enc)
+        lists = oracle_mod.make_lists(pr.k, pr.n, enc.cell, enc.edge, enc.lamq, enc.codes)
+        w1, w2, K = 512, 2048, 1024
+        check_search(oracle_mod, pr, S, E, lists, pr.Y, w1, w2, K, gpu_search(vlq, idx, pr.Y, w1, w2, K), max_soft=1.0)
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_large_batches_are_tiled_without_changing_results(vlq):
     """More queries than one internal tile (32 768): the same rows as when the queries are sent in
     pieces (a query's result does not depend on its batch)."""
