@@ -174,6 +174,9 @@ int vlq_index_params(const vlq_index_t *idx, vlq_params_t *out);
  *   the K smallest by (distance, id); among points whose fp32 distances are
  *   exactly equal at the K-th place the earlier list position is kept.
  * The result of a query does not depend on the other queries of the batch.
+ * Once a call with the same (or larger) nq, w1, w2, K has sized the index's scratch memory, the
+ * call only launches kernels on `stream` (no allocation, no memset, no synchronisation), so it
+ * can be recorded in a HIP graph and replayed.
  * Outputs row-major [nq x K], ascending; rows with fewer than K candidates are
  * padded with (+inf, -1).  nq = 0 is a no-op.  Does not synchronise.
  */

@@ -314,6 +314,39 @@ def test_largest_supported_shapes(vlq, oracle_mod):
         vlq.vlq_index_free(idx)
 
 
+def test_search_can_be_captured_in_a_graph(vlq):
+    """After one call has sized the scratch memory, vlq_search only launches kernels on the given
+    stream: it can be captured in a HIP graph.  Every replay (with new queries written into the
+    captured input buffer, and ordinary work and synchronisations between replays) gives the rows
+    of a plain call."""
+    pr = problem(kind="deep", N=15000, k=96, n=8, m=16, G=32, nq=50)
+    idx = make_index(vlq, pr, base=pr.X)
+    try:
+        nq, w1, w2, K = 50, 8, 20, 50
+        rng = np.random.default_rng(9)
+        Yin = dev(pr.Y.copy())
+        od = torch.empty(nq, K, device=DEV)
+        oi = torch.empty(nq, K, dtype=torch.int32, device=DEV)
+        vlq.vlq_search(idx, Yin, nq, w1, w2, K, od, oi)  # sizes the scratch
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            vlq.vlq_search(idx, Yin, nq, w1, w2, K, od, oi)
+        for rep in range(4):
+            Y = pr.Y[rng.permutation(nq)] + rng.normal(scale=0.01, size=pr.Y.shape).astype(np.float32)
+            Yin.copy_(dev(Y))
+            graph.replay()
+            torch.cuda.synchronize()
+            got_d, got_i = od.clone(), oi.clone()
+            od2 = torch.empty(nq, K, device=DEV)
+            oi2 = torch.empty(nq, K, dtype=torch.int32, device=DEV)
+            vlq.vlq_search(idx, dev(Y), nq, w1, w2, K, od2, oi2)
+            torch.cuda.synchronize()
+            assert torch.equal(got_i, oi2) and torch.equal(got_d, od2), f"replay {rep}"
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_large_batches_are_tiled_without_changing_results(vlq):
     """More queries than one internal tile (32 768): the same rows as when the queries are sent in
     pieces (a query's result does not depend on its batch)."""
