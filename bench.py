@@ -91,8 +91,19 @@ def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
     t, _ = run(Y[:nprobe])
     ns = int(min(len(Y), max(nprobe, target_s / max(t / nprobe, 1e-9))))
     t, out_i = run(Y[:ns])
-    return {"value": ns / t, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"first {ns} of the {len(Y)} queries, index and graph copied from the library, same w1/w2/K; {t:.1f} s of oracle search"}, out_i, ns
+    cores = oracle.num_threads()
+    base = {"value": ns / t, "unit": "queries/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {ns} of the {len(Y)} queries, index and graph copied from the library, same w1/w2/K; {t:.1f} s of oracle search"}
+    if cores > 1:  # the same code on one thread, on a sample sized for about a third of the time
+        n1 = int(min(ns, max(4, ns / cores * 0.35)))
+        oracle.set_num_threads(1)
+        try:
+            t1, _ = run(Y[:n1])
+        finally:
+            oracle.set_num_threads(cores)
+        base["one_core"] = {"value": n1 / t1, "unit": "queries/s", "cores": 1,
+                            "sample": f"first {n1} queries, {t1:.1f} s"}
+    return base, out_i, ns
 
 
 def measured_traffic(workload):
@@ -141,8 +152,8 @@ def main():
     od = torch.empty(nq, K, device=dev)
     oi = torch.empty(nq, K, dtype=torch.int32, device=dev)
 
-    def timed(w1, steps, warmup):
-        w2 = cfg.w2(w1)
+    def timed(w1, steps, warmup, w2=None):
+        w2 = w2 or cfg.w2(w1)
         for _ in range(warmup):
             vlq.vlq_search(wl.idx, wl.Y, nq, w1, w2, K, od, oi)
         torch.cuda.synchronize()
@@ -193,8 +204,18 @@ def main():
         sweep = []
         for w in cfg.w1:
             d2, p2, r2, w22 = timed(w, max(2, args.steps // 2), 1)
-            sweep.append({"w1": w, "w2": w22, "queries_per_s": nq * max(2, args.steps // 2) / d2, **r2})
+            pts = scan_bytes(vlq, wl, w, w22, torch)[1]
+            sweep.append({"w1": w, "w2": w22, "queries_per_s": nq * max(2, args.steps // 2) / d2,
+                          "points_scanned_per_query": pts / nq, **r2})
         result["config"]["sweep"] = sweep
+        # the share alpha of the w1 * n sub-regions that is scanned (Sec. 5, parameter study), at the headline w1
+        if not cfg.w2_fixed and cfg.n > 1:
+            asw = []
+            for alpha in (0.25, 0.4, 0.5):
+                w2a = max(1, int(alpha * w1 * cfg.n))
+                d2, p2, r2, _ = timed(w1, max(2, args.steps // 2), 1, w2a)
+                asw.append({"alpha": alpha, "w1": w1, "w2": w2a, "queries_per_s": nq * max(2, args.steps // 2) / d2, **r2})
+            result["config"]["alpha_sweep"] = asw
         # batch-size and K sweeps of the configuration (at the headline w1): the first nb queries of the batch
         bs = []
         for nb in cfg.batches:

@@ -109,7 +109,7 @@ def _seeded_init(X: torch.Tensor, k: int, seed: int, stream: int) -> torch.Tenso
 
 
 def train_with_library(vlq, Xtrain: torch.Tensor, k: int, n: int, m: int, iters: int = 10, seed: int = MASTER_SEED,
-                       pq_sample: int = 1 << 18):
+                       pq_sample: int = 1 << 18, grid=(0.0, 0.0)):
     """The same recipe as `train`, every step run by the GPU library: Lloyd iterations by
     vlq_kmeans, the n-NN graph by vlq_build_index, line-quantisation residuals by
     vlq_line_residuals, and one 256-word codebook per sub-space by vlq_kmeans again."""
@@ -119,7 +119,7 @@ def train_with_library(vlq, Xtrain: torch.Tensor, k: int, n: int, m: int, iters:
     Cb = _seeded_init(Xtrain, k, seed, 0)
     vlq.vlq_kmeans(Xtrain, nt, D, k, iters, Cb)
     # an index over the trained centroids (placeholder PQ codebooks) gives cells, lines and lambda bytes
-    idx = vlq.vlq_build_index(vlq.vlq_params_t(D, k, n, m, 0.0, 0.0), Cb, torch.zeros(m, 256, ds, device=Xtrain.device))
+    idx = vlq.vlq_build_index(vlq.vlq_params_t(D, k, n, m, grid[0], grid[1]), Cb, torch.zeros(m, 256, ds, device=Xtrain.device))
     try:
         ns = min(nt, pq_sample)
         R = torch.empty(ns, D, device=Xtrain.device)

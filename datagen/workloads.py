@@ -32,6 +32,8 @@ class Config:
     ntrain: int = 0
     batches: tuple = ()  # query batch sizes of the configuration's batch sweep
     Ks: tuple = ()  # result counts of the configuration's K sweep
+    lam_lo: float = 0.0  # byte grid of lambda; (0, 0) = the library's default grid
+    lam_hi: float = 0.0
 
     @property
     def D(self):
@@ -45,6 +47,11 @@ CONFIGS = {c.name: c for c in (
     Config("tiny_sift", "sift", 100_000, 64, 1_000, 256, 8, 8, (8,), w2_fixed=32, ntrain=20_000),
     Config("mid_sift", "sift", 10_000_000, 1_024, 10_000, 16_384, 32, 8, (8, 16, 32, 64), ntrain=1_000_000),
     Config("mid_deep", "deep", 100_000_000, 4_096, 10_000, 65_536, 32, 16, (16, 32, 64), ntrain=2_000_000),
+    # the inverted-file baseline the paper compares against, expressed in this library's terms: four times the
+    # centroids, one edge per cell and a lambda grid whose 256 values are all (numerically) zero, so every
+    # anchor is the cell centroid, every probed cell is one list and the codes are residuals to the centroid
+    Config("mid_sift_ivf", "sift", 10_000_000, 1_024, 10_000, 65_536, 1, 8, (8, 16, 32, 64, 128), alpha=1.0,
+           ntrain=1_000_000, lam_lo=0.0, lam_hi=1e-20),
     Config("billion_sift", "sift", 1_000_000_000, 16_384, 10_000, 65_536, 32, 8, (16, 32, 64), ntrain=2_000_000),
     Config("billion_deep", "deep", 1_000_000_000, 16_384, 10_000, 65_536, 64, 16, (32, 64), ntrain=2_000_000,
            batches=(1, 16, 256, 10_000), Ks=(1, 10, 100)),
@@ -79,13 +86,14 @@ def materialise(vlq, cfg: Config, device="cuda:0", n_points: int | None = None, 
     t0 = time.time()
     mix = Mixture(cfg.kind, cfg.G, seed=MASTER_SEED)
     T = mix.train_sample(cfg.ntrain, device)
-    C, P = codebooks.train_with_library(vlq, T, cfg.k, cfg.n, cfg.m, iters=iters, seed=MASTER_SEED)
+    C, P = codebooks.train_with_library(vlq, T, cfg.k, cfg.n, cfg.m, iters=iters, seed=MASTER_SEED,
+                                        grid=(cfg.lam_lo, cfg.lam_hi))
     del T
     torch.cuda.synchronize()
     t_train = time.time() - t0
     log(f"[{cfg.name}] codebooks trained in {t_train:.1f} s")
     Y = mix.queries(cfg.nq, device)
-    prm = vlq.vlq_params_t(cfg.D, cfg.k, cfg.n, cfg.m, 0.0, 0.0)
+    prm = vlq.vlq_params_t(cfg.D, cfg.k, cfg.n, cfg.m, cfg.lam_lo, cfg.lam_hi)
     t0 = time.time()
     idx = vlq.vlq_build_index(prm, C, P)
     N = cfg.N if n_points is None else n_points

@@ -69,11 +69,11 @@ def gpu_encode(vlq, idx, X, m):
     return cell.cpu().numpy(), edge.cpu().numpy(), lam.cpu().numpy(), codes.cpu().numpy()
 
 
-def check_encode(oracle, pr, S, E, X, got, max_soft=0.01):
+def check_encode(oracle, pr, S, E, X, got, max_soft=0.01, grid=()):
     """Stage by stage; a point whose upstream choice differs inside the tie band is
     not compared further downstream (counted instead)."""
     cell, edge, lamq, codes = got
-    enc = oracle.encode(pr.C, S, E, pr.P, X)
+    enc = oracle.encode(pr.C, S, E, pr.P, X, *grid)
     N = len(X)
     soft = 0
     ok = np.ones(N, bool)
@@ -134,14 +134,14 @@ def gpu_search(vlq, idx, Y, w1, w2, K):
     return [t.cpu().numpy() for t in (od, oi, cells, cd, sub, ss)]
 
 
-def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15):
+def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15, grid=()):
     """Stage by stage.  Where the oracle itself sees a tie (mirrored lines
     l(c_i,c_j) / l(c_j,c_i) tie exactly in exact arithmetic) the GPU's choice is
     first checked to lie inside the oracle's tie band, then the next stage is
     compared for that choice."""
     od, oi, cells, cd, sub, ss = got
     extra = 16
-    tr = oracle.search(pr.C, S, E, pr.P, lists, Y, w1, w2, K + extra)
+    tr = oracle.search(pr.C, S, E, pr.P, lists, Y, w1, w2, K + extra, *grid)
     nq = len(Y)
     soft = 0
     for q in range(nq):
@@ -158,7 +158,7 @@ def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15):
         o_d, o_i = tr.out_d[q], tr.out_id[q]
         if not (same_cells and same_sub):
             soft += 1
-            o_d, o_i, _ = (x[0] for x in oracle.scan(pr.C, S, pr.P, lists, Y[q:q + 1], sub[q:q + 1], K + extra))
+            o_d, o_i, _ = (x[0] for x in oracle.scan(pr.C, S, pr.P, lists, Y[q:q + 1], sub[q:q + 1], K + extra, *grid))
         check_topk(od[q], oi[q], o_d, o_i, K, what=what)
     assert soft <= max(3, max_soft * nq), f"{soft} of {nq} queries fell into tie bands"
     return tr, soft
@@ -192,6 +192,32 @@ def test_build_encode_search_against_oracle(vlq, oracle_mod, name):
         # tiny codebooks: most graph edges are mutual, so mirrored-line ties at the cut are frequent
         soft = 0.6 if pr.k < 30 else 0.15
         check_search(oracle_mod, pr, S, E, lists, pr.Y, w1, w2, K, gpu_search(vlq, idx, pr.Y, w1, w2, K), max_soft=soft)
+    finally:
+        vlq.vlq_index_free(idx)
+
+
+@pytest.mark.parametrize("lo,hi,n", [(-0.125, 0.5, 6), (-1.0, 0.5, 6), (0.0, 1e-20, 1)])
+def test_other_lambda_grids(vlq, oracle_mod, lo, hi, n):
+    """The byte grid of lambda is an index parameter: a finer grid, a wider one, and the
+    degenerate grid whose 256 values are all (numerically) zero with one edge per cell, which
+    turns the index into a plain inverted file with residuals to the cell centroid."""
+    pr = problem(N=6000, k=48, n=n, m=8, G=12, nq=40)
+    lo, hi = float(np.float32(lo)), float(np.float32(hi))  # the values the library receives
+    idx = make_index(vlq, pr, lo=lo, hi=hi)
+    try:
+        S, E = oracle_mod.graph(pr.C, pr.n)
+        enc, _ = check_encode(oracle_mod, pr, S, E, pr.X, gpu_encode(vlq, idx, pr.X, pr.m), grid=(lo, hi))
+        if hi < 1e-10:  # every anchor is the centroid itself
+            rec = oracle_mod.reconstruct(pr.C, S, pr.P, enc.cell, enc.edge, enc.lamq, enc.codes, lo, hi)
+            rec0 = pr.C[enc.cell].astype(np.float64) + np.concatenate(
+                [pr.P[p][enc.codes[:, p]] for p in range(pr.m)], axis=1).astype(np.float64)
+            assert np.allclose(rec, rec0, rtol=0, atol=1e-12)
+        load_oracle_index(vlq, idx, enc)
+        lists = oracle_mod.make_lists(pr.k, pr.n, enc.cell, enc.edge, enc.lamq, enc.codes)
+        w1 = 7
+        w2 = 7 if n == 1 else 15
+        check_search(oracle_mod, pr, S, E, lists, pr.Y, w1, w2, 30, gpu_search(vlq, idx, pr.Y, w1, w2, 30),
+                     max_soft=0.3, grid=(lo, hi))
     finally:
         vlq.vlq_index_free(idx)
 
