@@ -1,6 +1,7 @@
 """Full-size checks of the mid SIFT-like configuration (10^7 points, D = 128, k = 16 384, n = 32,
-m = 8) and the mid DEEP-like one (10^8 points, D = 96, k = 65 536, n = 32, m = 16), 10 000 queries,
-w1 = 64, w2 = 512, K = 100, in the launch configuration that bench.py times.
+m = 8), the mid DEEP-like one (10^8 points, D = 96, k = 65 536, n = 32, m = 16), 10 000 queries,
+w1 = 64, w2 = 512, K = 100, and (on request, see below) the billion SIFT-like one, each in the launch
+configuration that bench.py times.
 The oracle cannot encode 10^7 points, so it is used on samples it can compute one by one; all of its
 inputs come from the seeded generators (raw vectors are regenerated from the seed by id):
 
@@ -12,6 +13,8 @@ inputs come from the seeded generators (raw vectors are regenerated from the see
  * completeness probe: the exact nearest neighbour of a sampled query, if its list is visited and
    its ADC distance beats the K-th result, must be among the results.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -53,7 +56,14 @@ def _oracle_encode(oracle, pr, X):
     return oracle.encode(pr.C, S, E, pr.P, X), S, E
 
 
-@pytest.mark.parametrize("name", ["mid_sift", "mid_deep"])
+# The same checks on the 10^9-point configuration that bench.py times by default take about four
+# minutes (two of them building the index, silently unless pytest runs with -s), so they run on request:
+#   VLQ_TEST_BILLION=1 python -u -m pytest tests/test_gpu_fullsize.py -s -k billion
+BILLION = pytest.param("billion_sift", marks=pytest.mark.skipif(
+    not os.environ.get("VLQ_TEST_BILLION"), reason="set VLQ_TEST_BILLION=1 (about four minutes on the GPU)"))
+
+
+@pytest.mark.parametrize("name", ["mid_sift", "mid_deep", BILLION])
 def test_mid_configurations_sampled(vlq, oracle_mod, name):
     cfg = workloads.CONFIGS[name]
     wl = workloads.materialise(vlq, cfg, DEV, log=lambda *a: print(*a, flush=True))
