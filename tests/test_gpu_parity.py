@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity import DTOL, GAP, check_selection, check_topk
+from parity import DTOL, EPS32, GAP, RES_ROUNDINGS, check_selection, check_topk
 from util import Problem, problem
 
 pytestmark = pytest.mark.gpu
@@ -101,9 +101,17 @@ def check_encode(oracle, pr, S, E, X, got, max_soft=0.01, grid=()):
     soft += len(bad)
     # PQ (Alg. 2): gap relative to the sub-space distance
     diff = (codes != enc.codes) & ok[:, None]
+    ds = pr.D // pr.m
     for t, p in zip(*np.nonzero(diff)):
-        assert enc.code_d[t, p, 1] - enc.code_d[t, p, 0] <= GAP * max(enc.code_d[t, p, 1], 1e-30) + 1e-12, \
-            f"code of point {t}, sub-space {p}"
+        d0, d1 = enc.code_d[t, p]
+        if d1 - d0 <= GAP * max(d1, 1e-30) + 1e-12:
+            continue
+        # the residual itself is only known to fp32 rounding of the vector and its anchor
+        xp = X[t, p * ds:(p + 1) * ds].astype(np.float64)
+        rp = oracle.line_residual(pr.C, S, X[t:t + 1], enc.cell[t:t + 1], enc.edge[t:t + 1], enc.lamq[t:t + 1],
+                                  *grid)[0, p * ds:(p + 1) * ds]
+        dr = RES_ROUNDINGS * EPS32 * (np.linalg.norm(xp) + np.linalg.norm(xp - rp))
+        assert np.sqrt(d1) - np.sqrt(d0) <= dr, f"code of point {t}, sub-space {p}"
     soft += int(diff.any(1).sum())
     assert soft <= max(2, max_soft * N), f"{soft} of {N} points fell into tie bands"
     return enc, soft
@@ -159,7 +167,7 @@ def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15, grid
         if not (same_cells and same_sub):
             soft += 1
             o_d, o_i, _ = (x[0] for x in oracle.scan(pr.C, S, pr.P, lists, Y[q:q + 1], sub[q:q + 1], K + extra, *grid))
-        check_topk(od[q], oi[q], o_d, o_i, K, what=what)
+        check_topk(od[q], oi[q], o_d, o_i, K, what=what, scale=a_max)
     assert soft <= max(3, max_soft * nq), f"{soft} of {nq} queries fell into tie bands"
     return tr, soft
 

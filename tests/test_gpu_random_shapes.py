@@ -1,0 +1,61 @@
+"""Seeded random shapes through the build / encode / search parity checks of test_gpu_parity.py:
+dimensions that are not multiples of four, one-dimensional sub-spaces, m = 1 … 64, n = 1 … 33, empty and
+one-point indexes, K = 1 … 1 024, w2 from 1 to all w1 * n sub-regions."""
+import random
+
+import numpy as np
+import pytest
+
+import test_gpu_parity as T
+from test_gpu_parity import vlq  # noqa: F401  (fixture)
+from util import Problem, problem
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw(rng, seed):
+    D = rng.choice([4, 6, 12, 16, 20, 32, 48, 64, 96, 100, 128, 160, 256, 384])
+    m = rng.choice([x for x in (1, 2, 3, 4, 5, 6, 8, 12, 16, 32, 64) if D % x == 0])
+    k = rng.choice([9, 17, 40, 64, 130, 300, 700])
+    n = rng.choice([x for x in (1, 2, 3, 5, 8, 16, 33) if x < k])
+    N = rng.choice([0, 1, 50, 999, 3000, 7001])
+    w1 = rng.choice([x for x in (1, 2, 5, 16, 40, 64, 200) if x <= k and x * n <= 8192])
+    w2 = rng.choice(sorted({1, max(1, w1 * n // 4), max(1, w1 * n // 2), w1 * n} & set(range(1, 2049))) or [1])
+    kw = dict(kind=rng.choice(["sift", "deep"]), N=max(N, 1), k=k, n=n, m=m, G=rng.choice([3, 8, 30]),
+              nq=rng.choice([1, 2, 7, 33, 64]), D=D, seed=seed)
+    return kw, N, w1, w2, rng.choice([1, 3, 10, 100, 257, 1024])
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes(vlq, oracle_mod, seed):
+    rng = random.Random(seed)
+    done = 0
+    for ci in range(40):
+        kw, N, w1, w2, K = _draw(rng, 1000 * seed + ci)
+        case = f"case {ci} of seed {seed}: {kw} N={N} w1={w1} w2={w2} K={K}"
+        pr = problem(**kw)
+        if N == 0:
+            pr = Problem(pr.kind, pr.X[:0], pr.Y, pr.C, pr.P, pr.n)
+        idx = T.make_index(vlq, pr)
+        try:
+            Sg, Eg = T.gpu_graph(vlq, idx, pr)
+            T.check_graph(oracle_mod, pr, Sg, Eg)
+            S, E = oracle_mod.graph(pr.C, pr.n)
+            if not np.array_equal(S, Sg):
+                continue  # neighbours tied within rounding are numbered differently: edges not comparable
+            if N > 0:
+                enc, _ = T.check_encode(oracle_mod, pr, S, E, pr.X, T.gpu_encode(vlq, idx, pr.X, pr.m), max_soft=0.05)
+                T.load_oracle_index(vlq, idx, enc)
+                lists = oracle_mod.make_lists(pr.k, pr.n, enc.cell, enc.edge, enc.lamq, enc.codes)
+            else:
+                vlq.vlq_index_finalize(idx)
+                z = np.zeros(0, np.int32)
+                lists = oracle_mod.make_lists(pr.k, pr.n, z, z, np.zeros(0, np.uint8), np.zeros((0, pr.m), np.uint8))
+            T.check_search(oracle_mod, pr, S, E, lists, pr.Y, w1, w2, K, T.gpu_search(vlq, idx, pr.Y, w1, w2, K),
+                           max_soft=1.0)
+            done += 1
+        except AssertionError as e:
+            raise AssertionError(f"{case}: {e}") from e
+        finally:
+            vlq.vlq_index_free(idx)
+    assert done >= 30
