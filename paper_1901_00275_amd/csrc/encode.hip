@@ -134,9 +134,240 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
     for (int i = tid; i < np * m; i += ENC_NT) a.codes[g0 * m + i] = (uint8_t)(best[i] & 0xFFu);
 }
 
+
+// ---------------------------------------------------------------------------
+// The same two phases arranged for the common shapes (D <= 128 and a multiple
+// of four, sub-spaces of up to 16 dimensions), 64 vectors per workgroup.
+//  phase 1 (a wave per vector, as above) forms the n line distances four rows at
+//    a time: 16 lanes per neighbour row, each lane eight components, so a pass
+//    costs one short reduction instead of four wave-wide ones.
+//  phase 2 turns the work round: a lane is a vector, a wave takes whole
+//    sub-spaces, and the 256 codewords come in one after the other through uniform
+//    loads.  Every lane keeps its own running (distance, codeword) minimum, so the
+//    step has no cross-lane reduction at all; strict "<" in ascending codeword
+//    order keeps the smaller codeword of a tie (Alg. 2).
+// ---------------------------------------------------------------------------
+#define ENC2_PB 64
+typedef const float __attribute__((address_space(4))) cfloat;
+
+template <int DS>
+__global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
+{
+    extern __shared__ unsigned char smem[];
+    const int D = a.D, m = a.m, n = a.n;
+    const int RS = D + 1; // odd row stride: lane = vector reads are conflict-free
+    float *res = (float *)smem;                        // [ENC2_PB][RS]
+    uint8_t *cod = (uint8_t *)(res + ENC2_PB * RS);    // [ENC2_PB][m]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = lane >> 4, l16 = lane & 15;
+    const int64_t g0 = (int64_t)blockIdx.x * ENC2_PB;
+    const int np = (int)min((int64_t)ENC2_PB, a.nb - g0);
+    const int d0 = l16 * 4, d1 = 64 + l16 * 4;
+    const bool has0 = d0 < D, has1 = d1 < D;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    for (int pt = wave; pt < np; pt += ENC_NT / 64) {
+        const int64_t gid = g0 + pt;
+        float *x = res + pt * RS;
+        float xn = 0.f;
+        for (int d = lane; d < D; d += 64) {
+            const float v = a.X[gid * D + d];
+            x[d] = v;
+            xn = fmaf(v, v, xn);
+        }
+        xn = wave_sum(xn);
+        const int nc = a.nsplit * VLQ_NN_CANDS;
+        const uint64_t *cd = a.cand + gid * nc;
+        uint64_t mn = KEY_MAX;
+        for (int c = lane; c < nc; c += 64) {
+            const uint64_t key = cd[c];
+            mn = key < mn ? key : mn;
+        }
+        mn = wave_min_u64(mn);
+        const float dmin = __uint_as_float((uint32_t)(mn >> 32));
+        const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
+        uint64_t bk = KEY_MAX;
+        for (int c0 = 0; c0 < nc; c0 += 64) { // the few candidates inside the band, found 64 keys at a time
+            const uint64_t key = c0 + lane < nc ? cd[c0 + lane] : KEY_MAX;
+            const bool inb = key != KEY_MAX && !(__uint_as_float((uint32_t)(key >> 32)) > band);
+            uint64_t mask = __ballot(inb);
+            while (mask) {
+                const int src = __ffsll((unsigned long long)mask) - 1;
+                mask &= mask - 1;
+                const uint32_t idx = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, src);
+                const float d = wave_sqdist(x, a.C + (int64_t)idx * D, D, lane);
+                const uint64_t ek = make_key(d, idx);
+                bk = ek < bk ? ek : bk;
+            }
+        }
+        if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
+            const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
+            bk = make_key(wave_sqdist(x, a.C + (int64_t)idx * D, D, lane), idx);
+        }
+        const int cell = (int)(uint32_t)bk;
+        const float av = ord2f((uint32_t)(bk >> 32));
+        // line quantisation inside the cell, four neighbour rows per pass
+        const float *xg = a.X + gid * D;
+        f32x4 y0 = zero, y1 = zero;
+        if (has0) y0 = *(const f32x4 *)(xg + d0);
+        if (has1) y1 = *(const f32x4 *)(xg + d1);
+        float bd2 = INFINITY, bl = 0.f;
+        int bj = 0x7FFFFFFF;
+        for (int j0 = 0; j0 < n; j0 += 16) { // 16 rows per round: their loads are all under way together
+            int sidx[4];
+            float ev[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + 4 * u + sub;
+                const bool live = j < n;
+                sidx[u] = live ? a.S[(int64_t)cell * n + j] : cell;
+                ev[u] = live ? a.E[(int64_t)cell * n + j] : 0.f;
+            }
+            f32x4 c0[4], c1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float *row = a.C + (int64_t)sidx[u] * D;
+                c0[u] = has0 ? *(const f32x4 *)(row + d0) : zero;
+                c1[u] = has1 ? *(const f32x4 *)(row + d1) : zero;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + 4 * u + sub;
+                float acc = 0.f;
+                {
+                    const float t0 = y0.x - c0[u].x, t1 = y0.y - c0[u].y, t2 = y0.z - c0[u].z, t3 = y0.w - c0[u].w;
+                    acc = fmaf(t0, t0, acc);
+                    acc = fmaf(t1, t1, acc);
+                    acc = fmaf(t2, t2, acc);
+                    acc = fmaf(t3, t3, acc);
+                }
+                {
+                    const float t0 = y1.x - c1[u].x, t1 = y1.y - c1[u].y, t2 = y1.z - c1[u].z, t3 = y1.w - c1[u].w;
+                    acc = fmaf(t0, t0, acc);
+                    acc = fmaf(t1, t1, acc);
+                    acc = fmaf(t2, t2, acc);
+                    acc = fmaf(t3, t3, acc);
+                }
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+                if (j < n) {
+                    const float c = ev[u];
+                    const float lam = c > 0.f ? 0.5f * (av + c - acc) / c : 0.f;
+                    const float d2 = av - c * lam * lam;
+                    if (d2 < bd2) { // rows of a lane group come in ascending j
+                        bd2 = d2;
+                        bj = j;
+                        bl = lam;
+                    }
+                }
+            }
+        }
+        // the four lane groups hold the best of their rows: smallest (distance, j) overall
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+            const float od = __shfl_xor(bd2, o, 64), ol = __shfl_xor(bl, o, 64);
+            const int oj = __shfl_xor(bj, o, 64);
+            if (od < bd2 || (od == bd2 && oj < bj)) {
+                bd2 = od;
+                bj = oj;
+                bl = ol;
+            }
+        }
+        if (bj == 0x7FFFFFFF) { // every line distance was NaN (non-finite input): keep the index in range
+            bj = 0;
+            bl = 0.f;
+        }
+        float qf = rintf(bl / a.lam_step) + a.lam_zero;
+        qf = fminf(fmaxf(qf, 0.f), 255.f);
+        const float lh = (qf - a.lam_zero) * a.lam_step;
+        const float *ci = a.C + (int64_t)cell * D;
+        const float *sj = a.C + (int64_t)a.S[(int64_t)cell * n + bj] * D;
+        for (int d = lane; d < D; d += 64) {
+            const float c = ci[d];
+            const float r = x[d] - fmaf(lh, sj[d] - c, c);
+            x[d] = r;
+            if (a.res) a.res[gid * D + d] = r;
+        }
+        if (lane == 0) {
+            if (a.cell) a.cell[gid] = cell;
+            if (a.edge) a.edge[gid] = bj;
+            if (a.lamq) a.lamq[gid] = (uint8_t)qf;
+        }
+    }
+    __syncthreads();
+
+    // phase 2: lane = vector, wave = sub-space, codewords in ascending order
+    for (int p = wave; p < m; p += ENC_NT / 64) {
+        float r[DS];
+#pragma unroll
+        for (int d = 0; d < DS; ++d) r[d] = res[lane * RS + p * DS + d];
+        // the codebooks are never written while the kernel runs: reading them through the constant
+        // address space lets the uniform loads take the scalar path and the operands stay in SGPRs
+        const cfloat *w = (const cfloat *)(uintptr_t)(a.P + (int64_t)p * 256 * DS);
+        float best = INFINITY;
+        int bt = 0;
+        // CB codewords per batch (other waves of the SIMD cover the latency of the uniform loads:
+        // issuing a batch a whole round ahead measured no faster)
+        constexpr int CB = DS >= 12 ? 2 : (DS >= 6 ? 4 : 8);
+        float wc[CB * DS], wn[CB * DS];
+#pragma unroll
+        for (int i = 0; i < CB * DS; ++i) wc[i] = w[i];
+        for (int t = 0; t < 256; t += CB) {
+            const int tn = t + CB < 256 ? t + CB : t;
+#pragma unroll
+            for (int i = 0; i < CB * DS; ++i) wn[i] = w[tn * DS + i];
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                float s = 0.f;
+#pragma unroll
+                for (int d = 0; d < DS; ++d) {
+                    const float tv = r[d] - wc[u * DS + d];
+                    s = fmaf(tv, tv, s);
+                }
+                if (s < best) {
+                    best = s;
+                    bt = t + u;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < CB * DS; ++i) wc[i] = wn[i];
+        }
+        cod[lane * m + p] = (uint8_t)bt;
+    }
+    __syncthreads();
+    for (int i = tid; i < np * m; i += ENC_NT) a.codes[g0 * m + i] = cod[i];
+}
+
+static bool encode_lanes_supported(const EncodeArgs &a)
+{
+    if (!a.S || !a.codes) return false;
+    if (a.D > 128 || a.D % 4) return false;
+    if ((((uintptr_t)a.X) | ((uintptr_t)a.C)) % 16) return false;
+    const int ds = a.D / a.m;
+    return ds == 4 || ds == 6 || ds == 8 || ds == 12 || ds == 16;
+}
+
 void launch_encode_finish(const EncodeArgs &a, hipStream_t st)
 {
     if (a.nb <= 0) return;
+    const char *env = getenv("VLQ_ENCODE_WAVE"); // 1: the wave-per-vector kernel for every shape (testing)
+    const bool wave_per_vector_only = env && atoi(env) != 0;
+    if (!wave_per_vector_only && encode_lanes_supported(a)) {
+        const size_t smem2 = (size_t)ENC2_PB * (a.D + 1) * 4 + (size_t)ENC2_PB * a.m;
+        const unsigned grid2 = (unsigned)((a.nb + ENC2_PB - 1) / ENC2_PB);
+#define ENC2_LAUNCH(DSV)                                                                                       \
+    hipLaunchKernelGGL(k_encode_finish_lanes<DSV>, dim3(grid2), dim3(ENC_NT), smem2, st, a)
+        switch (a.D / a.m) {
+        case 4: ENC2_LAUNCH(4); break;
+        case 6: ENC2_LAUNCH(6); break;
+        case 8: ENC2_LAUNCH(8); break;
+        case 12: ENC2_LAUNCH(12); break;
+        default: ENC2_LAUNCH(16); break;
+        }
+#undef ENC2_LAUNCH
+        return;
+    }
     int PB = (int)(65536 / ((size_t)a.D * 4));
     if (PB > ENC_PB_MAX) PB = ENC_PB_MAX;
     if (PB < 1) PB = 1;

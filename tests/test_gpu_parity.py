@@ -305,6 +305,32 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
         vlq.vlq_index_free(idx)
 
 
+@pytest.mark.parametrize("name", ["sift_ragged", "deep_m16", "small_d32"])
+def test_both_encode_kernels_agree(vlq, oracle_mod, monkeypatch, name):
+    """Encoding has a kernel for the common shapes (a lane per vector in the product-quantisation step,
+    four neighbour rows per pass in the line step) and a general one (a wave per vector).  The parity
+    cases above run whichever serves their shape; here both run on the same vectors.  The line
+    distances are summed in a different order, so an edge or a lambda byte may differ where the oracle
+    sees a tie; everything else is identical, and each kernel passes the oracle check on its own."""
+    kw = CASES[name][0]
+    pr = problem(**kw)
+    idx = make_index(vlq, pr)
+    try:
+        S, E = oracle_mod.graph(pr.C, pr.n)
+        monkeypatch.setenv("VLQ_ENCODE_WAVE", "0")
+        a = gpu_encode(vlq, idx, pr.X, pr.m)
+        monkeypatch.setenv("VLQ_ENCODE_WAVE", "1")
+        b = gpu_encode(vlq, idx, pr.X, pr.m)
+        check_encode(oracle_mod, pr, S, E, pr.X, a)
+        check_encode(oracle_mod, pr, S, E, pr.X, b)
+        assert np.array_equal(a[0], b[0])
+        same = (a[1] == b[1]) & (a[2] == b[2])
+        assert same.mean() > 0.999
+        assert np.array_equal(a[3][same], b[3][same])
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 @pytest.mark.parametrize("name", ["sift_ragged", "deep_m16"])
 def test_packed_and_per_list_scan_agree(vlq, monkeypatch, name):
     """The streaming scan in its two forms - several short lists laid end to end over the lanes of a
