@@ -29,6 +29,10 @@
  *    use scratch memory owned by the index, which grows on demand (the first
  *    call with a larger batch allocates device memory and synchronises).
  *  - Distances are squared L2 distances to the reconstructed point (Eq. 14).
+ *  - Vector components, centroids and codewords must be finite.  The contents of
+ *    device buffers are not inspected on the host, so a NaN or an infinity is not
+ *    reported: the outputs of the vectors (queries) that contain one are
+ *    unspecified, those of the other vectors of the batch are unaffected.
  */
 #ifndef VLQ_H
 #define VLQ_H
