@@ -32,6 +32,21 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// ---- sum over each row of 16 lanes, identical in all 16: lane-crossing operands of the adder
+// (neighbour in the pair, other pair of the quad, other quad of the half, other half of the row),
+// no LDS traffic.  The order of the additions is fixed. ----
+__device__ __forceinline__ float row16_sum(float v)
+{
+#define VLQ_DPP_ADD(ctrl)                                                                                      \
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xF, 0xF, true))
+    VLQ_DPP_ADD(0xB1);  // quad_perm [1, 0, 3, 2]
+    VLQ_DPP_ADD(0x4E);  // quad_perm [2, 3, 0, 1]
+    VLQ_DPP_ADD(0x141); // row_half_mirror
+    VLQ_DPP_ADD(0x140); // row_mirror
+#undef VLQ_DPP_ADD
+    return v;
+}
+
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o)
 {
     uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);

@@ -249,8 +249,7 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
                     acc = fmaf(t2, t2, acc);
                     acc = fmaf(t3, t3, acc);
                 }
-#pragma unroll
-                for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+                acc = row16_sum(acc);
                 if (j < n) {
                     const float c = ev[u];
                     const float lam = c > 0.f ? 0.5f * (av + c - acc) / c : 0.f;

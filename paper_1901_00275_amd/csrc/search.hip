@@ -2,6 +2,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include <type_traits>
 
 // ---------------------------------------------------------------------------
 // Sub-region scores (Sec. 3.3.1): the query is line-quantised against every edge
@@ -120,10 +121,7 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                 part[g] = acc;
             }
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-#pragma unroll
-                for (int o = 8; o > 0; o >>= 1) part[g] += __shfl_xor(part[g], o, 64);
-            }
+            for (int g = 0; g < 4; ++g) part[g] = row16_sum(part[g]);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int t = t0 + g * 4 + sub16;
@@ -488,35 +486,80 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
             }
         }
         __syncthreads();
+        if (fast) {
+            // two pairs of the cell per wave where there are that many: a row read from LDS serves both
+            auto run = [&](auto two_c, int pa, int pb) {
+                constexpr bool TWO = decltype(two_c)::value;
+                const float *ya = Q + (int64_t)(pa / w1) * D, *yb = Q + (int64_t)(pb / w1) * D;
+                f32x4 a0 = zero, a1 = zero, b0 = zero, b1 = zero;
+                if (has0) {
+                    a0 = *(const f32x4 *)(ya + d0);
+                    if (TWO) b0 = *(const f32x4 *)(yb + d0);
+                }
+                if (has1) {
+                    a1 = *(const f32x4 *)(ya + d1);
+                    if (TWO) b1 = *(const f32x4 *)(yb + d1);
+                }
+                for (int j0 = 0; j0 < n; j0 += 4) {
+                    const int j = j0 + sub;
+                    float acca = 0.f, accb = 0.f;
+                    if (j < n) {
+                        const float *row = nrows + j * D;
+                        if (has0) {
+                            const f32x4 cv = *(const f32x4 *)(row + d0);
+                            float t0v = a0.x - cv.x, t1v = a0.y - cv.y, t2v = a0.z - cv.z, t3v = a0.w - cv.w;
+                            acca = fmaf(t0v, t0v, acca);
+                            acca = fmaf(t1v, t1v, acca);
+                            acca = fmaf(t2v, t2v, acca);
+                            acca = fmaf(t3v, t3v, acca);
+                            if (TWO) {
+                                t0v = b0.x - cv.x, t1v = b0.y - cv.y, t2v = b0.z - cv.z, t3v = b0.w - cv.w;
+                                accb = fmaf(t0v, t0v, accb);
+                                accb = fmaf(t1v, t1v, accb);
+                                accb = fmaf(t2v, t2v, accb);
+                                accb = fmaf(t3v, t3v, accb);
+                            }
+                        }
+                        if (has1) {
+                            const f32x4 cv = *(const f32x4 *)(row + d1);
+                            float t0v = a1.x - cv.x, t1v = a1.y - cv.y, t2v = a1.z - cv.z, t3v = a1.w - cv.w;
+                            acca = fmaf(t0v, t0v, acca);
+                            acca = fmaf(t1v, t1v, acca);
+                            acca = fmaf(t2v, t2v, acca);
+                            acca = fmaf(t3v, t3v, acca);
+                            if (TWO) {
+                                t0v = b1.x - cv.x, t1v = b1.y - cv.y, t2v = b1.z - cv.z, t3v = b1.w - cv.w;
+                                accb = fmaf(t0v, t0v, accb);
+                                accb = fmaf(t1v, t1v, accb);
+                                accb = fmaf(t2v, t2v, accb);
+                                accb = fmaf(t3v, t3v, accb);
+                            }
+                        }
+                    }
+                    acca = row16_sum(acca);
+                    if (TWO) accb = row16_sum(accb);
+                    if (l16 == 0 && j < n) {
+                        bq[(int64_t)pa * n + j] = acca;
+                        if (TWO) bq[(int64_t)pb * n + j] = accb;
+                    }
+                }
+            };
+            for (int pi = i + wave; pi < e; pi += 8) {
+                if (pi + 4 < e)
+                    run(std::true_type{}, sp[pi], sp[pi + 4]);
+                else
+                    run(std::false_type{}, sp[pi], sp[pi]);
+            }
+        } else
         for (int pi = i + wave; pi < e; pi += 4) {
             const int p = sp[pi];
             const float *y = Q + (int64_t)(p / w1) * D;
-            f32x4 y0 = zero, y1 = zero;
-            if (has0) y0 = *(const f32x4 *)(y + d0);
-            if (has1) y1 = *(const f32x4 *)(y + d1);
             for (int j0 = 0; j0 < n; j0 += 4) {
                 const int j = j0 + sub;
                 float acc = 0.f;
                 if (j < n) {
                     const float *row = nrows + j * D;
-                    if (fast) {
-                        if (has0) {
-                            const f32x4 cv = *(const f32x4 *)(row + d0);
-                            const float t0v = y0.x - cv.x, t1v = y0.y - cv.y, t2v = y0.z - cv.z, t3v = y0.w - cv.w;
-                            acc = fmaf(t0v, t0v, acc);
-                            acc = fmaf(t1v, t1v, acc);
-                            acc = fmaf(t2v, t2v, acc);
-                            acc = fmaf(t3v, t3v, acc);
-                        }
-                        if (has1) {
-                            const f32x4 cv = *(const f32x4 *)(row + d1);
-                            const float t0v = y1.x - cv.x, t1v = y1.y - cv.y, t2v = y1.z - cv.z, t3v = y1.w - cv.w;
-                            acc = fmaf(t0v, t0v, acc);
-                            acc = fmaf(t1v, t1v, acc);
-                            acc = fmaf(t2v, t2v, acc);
-                            acc = fmaf(t3v, t3v, acc);
-                        }
-                    } else if (vec) {
+                    if (vec) {
                         for (int d = l16 * 4; d < D; d += 64) {
                             const f32x4 cv = *(const f32x4 *)(row + d);
                             const f32x4 yv = *(const f32x4 *)(y + d);
@@ -533,8 +576,7 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                         }
                     }
                 }
-#pragma unroll
-                for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+                acc = row16_sum(acc);
                 if (l16 == 0 && j < n) bq[(int64_t)p * n + j] = acc;
             }
         }
