@@ -664,8 +664,7 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
                 }
             }
         }
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        acc = row16_sum(acc);
         if (l16 == 0 && c < cnt) keys[c] = (inband && i != self) ? make_key(acc, (uint32_t)i) : KEY_MAX;
     }
     sz = next_pow2_dev(cnt);

@@ -492,9 +492,7 @@ __device__ __forceinline__ float sqdist16(const float *yv, const float *__restri
             acc = fmaf(t, t, acc);
         }
     }
-#pragma unroll
-    for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    return acc;
+    return row16_sum(acc);
 }
 
 #define CELLS_FB 2048 // buffer of the exact ranking over all columns

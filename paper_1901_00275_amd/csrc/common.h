@@ -24,13 +24,6 @@ __device__ __forceinline__ float ord2f(uint32_t o)
 }
 __device__ __forceinline__ uint64_t make_key(float d, uint32_t lo) { return ((uint64_t)f2ord(d) << 32) | lo; }
 
-// ---- wave-wide sum, identical in every lane ----
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
 
 // ---- sum over each row of 16 lanes, identical in all 16: lane-crossing operands of the adder
 // (neighbour in the pair, other pair of the quad, other quad of the half, other half of the row),
@@ -44,6 +37,15 @@ __device__ __forceinline__ float row16_sum(float v)
     VLQ_DPP_ADD(0x141); // row_half_mirror
     VLQ_DPP_ADD(0x140); // row_mirror
 #undef VLQ_DPP_ADD
+    return v;
+}
+
+// ---- wave-wide sum, identical in every lane: rows of 16 first, then the four rows ----
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v = row16_sum(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
     return v;
 }
 
