@@ -79,7 +79,9 @@ __global__ __launch_bounds__(256) void k_split_bf16(const float *__restrict__ X,
         img[page * PAGE + pos] = ph;
         img[(page + 1) * PAGE + pos] = pl;
     }
-    if (__ballot(nz) != 0 && (threadIdx.x & 63) == 0) atomicOr(any_lo, 1);
+    // one look at the flag per workgroup, and a write only while it is still down: with
+    // non-integer data every workgroup has something to report, all to the same address
+    if (__syncthreads_or(nz) && threadIdx.x == 0 && *(volatile int *)any_lo == 0) atomicOr(any_lo, 1);
 }
 
 __global__ void k_zero_flag(int *p) { *p = 0; }
