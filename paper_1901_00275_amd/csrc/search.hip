@@ -41,15 +41,19 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                                                     const float *__restrict__ bpre)
 {
     extern __shared__ unsigned char smem[];
+    // With the distances precomputed and only the scan's descriptors asked for, the keys and the
+    // positions of the selected sub-regions are all that lives in LDS (twice the workgroups per CU).
+    const bool lean = bpre && !sub && !sub_score && !scan_label;
     uint64_t *keys = (uint64_t *)smem;          // [sz]
-    float *bval = (float *)(keys + sz);          // [sz]
-    float *yv = bval + sz;                       // [D]
-    uint16_t *pos = (uint16_t *)(yv + D);        // [sz]
+    float *bval = (float *)(keys + sz);          // [sz]   (not lean)
+    float *yv = bval + sz;                       // [D]    (not lean)
+    uint16_t *pos = (uint16_t *)(yv + D);        // [sz]   (not lean)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = blockIdx.x;
     const int total = w1 * n;
 
-    int *nbr = (int *)(pos + sz);                // [sz] neighbour centroid of every sub-region
+    // [sz] neighbour centroid of every sub-region; later the positions of the selected ones
+    int *nbr = lean ? (int *)(keys + sz) : (int *)(pos + sz);
     __shared__ int hist[256];
     __shared__ int sh4[4];
     __shared__ int sh_bin, sh_before, sh_inbin;
@@ -57,7 +61,8 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
     __shared__ unsigned long long sh_cut;
     __shared__ uint64_t ckeys[256];
 
-    for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)q * D + d];
+    if (!lean)
+        for (int d = tid; d < D; d += 256) yv[d] = Q[(int64_t)q * D + d];
     if (!bpre)
         for (int t = tid; t < total; t += 256) {
             const int e = t / n, j = t - e * n;
@@ -80,8 +85,10 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
             key = make_key(score, (uint32_t)(i * n + j));
         }
         keys[t] = key;
-        bval[t] = b;
-        pos[t] = (uint16_t)t;
+        if (!lean) {
+            bval[t] = b;
+            pos[t] = (uint16_t)t;
+        }
     };
     if (bpre) {
         // the distances were computed cell by cell beforehand (k_neighbour_dists)
@@ -331,7 +338,8 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                 const int label = (int)(uint32_t)keys[t];
                 const float a = cell_dist[(int64_t)q * w1 + t / n];
                 const int64_t b0 = off[label], b1 = off[label + 1];
-                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(bval[t] - a));
+                const float b = lean ? bpre[(int64_t)q * total + t] : bval[t];
+                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(b - a));
             }
             desc[(int64_t)q * w2 + r] = dsc;
         }
@@ -642,7 +650,8 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
     int sz = next_pow2(w1 * n);
     if (sz < next_pow2(w2)) sz = next_pow2(w2);
     if (sz < 2) sz = 2;
-    size_t smem = (size_t)sz * (8 + 4 + 2 + 4) + (size_t)D * 4;
+    const bool lean = bpre && !sub && !sub_score && !scan_label;
+    size_t smem = lean ? (size_t)sz * (8 + 4) : (size_t)sz * (8 + 4 + 2 + 4) + (size_t)D * 4;
     (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
                        cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g, off, desc, bpre);
