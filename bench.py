@@ -92,7 +92,15 @@ def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
     ns = int(min(len(Y), max(nprobe, target_s / max(t / nprobe, 1e-9))))
     t, out_i = run(Y[:ns])
     cores = oracle.num_threads()
-    base = {"value": ns / t, "unit": "queries/s", "cores": cores, "kind": "oracle",
+    cpu = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    base = {"value": ns / t, "unit": "queries/s", "cores": cores, "kind": "oracle", "cpu": cpu,
             "sample": f"first {ns} of the {len(Y)} queries, index and graph copied from the library, same w1/w2/K; {t:.1f} s of oracle search"}
     if cores > 1:  # the same code on one thread, on a sample sized for about a third of the time
         n1 = int(min(ns, max(4, ns / cores * 0.35)))
