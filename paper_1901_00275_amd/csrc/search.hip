@@ -423,22 +423,25 @@ __global__ void k_zero_i32(int32_t *p, int64_t n)
     if (i < n) p[i] = 0;
 }
 
-__global__ void k_pair_count(const int32_t *__restrict__ cells, int64_t np, int32_t *__restrict__ cnt)
+// Every pair learns its rank inside its cell while the cells are counted, so that the scatter
+// after the prefix sum needs no second round of atomics.
+__global__ void k_pair_count(const int32_t *__restrict__ cells, int64_t np, int32_t *__restrict__ cnt,
+                             int32_t *__restrict__ rank)
 {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p < np) {
         const int c = cells[p];
-        if (c >= 0) atomicAdd(&cnt[c], 1);
+        if (c >= 0) rank[p] = atomicAdd(&cnt[c], 1);
     }
 }
 
 __global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, const int64_t *__restrict__ poff,
-                               int32_t *__restrict__ cursor, int32_t *__restrict__ pairs)
+                               const int32_t *__restrict__ rank, int32_t *__restrict__ pairs)
 {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p < np) {
         const int c = cells[p];
-        if (c >= 0) pairs[poff[c] + atomicAdd(&cursor[c], 1)] = (int32_t)p;
+        if (c >= 0) pairs[poff[c] + rank[p]] = (int32_t)p;
     }
 }
 
@@ -602,8 +605,9 @@ bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1)
 size_t neighbour_dists_workspace(int nq, int k, int n, int w1)
 {
     size_t b = 0;
-    b += (((size_t)2 * k * 4) + 255) & ~(size_t)255;               // counts, cursors
+    b += (((size_t)k * 4) + 255) & ~(size_t)255;                   // counts
     b += (((size_t)(k + 1) * 8) + 255) & ~(size_t)255;             // offsets
+    b += (((size_t)nq * w1 * 4) + 255) & ~(size_t)255;             // ranks
     b += (((size_t)nq * w1 * 4) + 255) & ~(size_t)255;             // pairs
     b += (((size_t)nq * w1 * n * 4) + 255) & ~(size_t)255;         // distances
     return b;
@@ -624,18 +628,17 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
             base += (bytes + 255) & ~(size_t)255;
             return at;
         };
-        int32_t *cnt = (int32_t *)take((size_t)2 * k * 4);
-        int32_t *cursor = cnt + k;
+        int32_t *cnt = (int32_t *)take((size_t)k * 4);
         int64_t *poff = (int64_t *)take((size_t)(k + 1) * 8);
+        int32_t *rank = (int32_t *)take((size_t)nq * w1 * 4);
         int32_t *pairs = (int32_t *)take((size_t)nq * w1 * 4);
         float *bq = (float *)take((size_t)nq * w1 * n * 4);
         const int64_t np = (int64_t)nq * w1;
-        hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((2 * (int64_t)k + 255) / 256)), dim3(256), 0, st, cnt,
-                           (int64_t)2 * k);
-        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt);
+        hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)(((int64_t)k + 255) / 256)), dim3(256), 0, st, cnt, (int64_t)k);
+        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt, rank);
         launch_exclusive_scan(cnt, k, poff, st);
         hipLaunchKernelGGL(k_pair_scatter, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, poff,
-                           cursor, pairs);
+                           rank, pairs);
         const size_t rows_bytes = (size_t)n * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
