@@ -775,6 +775,14 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
 
     launch_row_norms(d_q, nq, D, qn, st);
     LAUNCHCHK();
+    // with the bf16 cell selection the (query, cell) pairs are counted per cell as the cells are written
+    PairWs pw = {};
+    bool pairs_counted = false;
+    if (by_cell) pw = neighbour_dists_carve(nws, nq, k, n, w1);
+    if (bf16 && by_cell) {
+        launch_pair_counts_zero(pw, k, st);
+        LAUNCHCHK();
+    }
     if (bf16) {
         {
             StageTimer t(idx, st, VLQ_STAGE_COARSE);
@@ -786,7 +794,9 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
         LAUNCHCHK();
         {
             StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS);
-            launch_cells_bf16_exact(d_q, nq, D, idx->C, k, w1, ccap, cws, csplit, cells, cell_dist, st);
+            launch_cells_bf16_exact(d_q, nq, D, idx->C, k, w1, ccap, cws, csplit, cells, cell_dist,
+                                    by_cell ? pw.cnt : nullptr, by_cell ? pw.rank : nullptr, st);
+            pairs_counted = by_cell;
         }
         LAUNCHCHK();
     } else {
@@ -843,7 +853,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
         // the streaming scan takes the visited sub-regions from desc alone, in any order
         const bool stream = scan_will_stream(a);
         launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, k, cells, cell_dist, w1, w2, d_sub, d_sub_score,
-                          stream ? nullptr : slab, stream ? nullptr : sg, idx->off, desc, nws, st);
+                          stream ? nullptr : slab, stream ? nullptr : sg, idx->off, desc, nws, pairs_counted, st);
     }
     LAUNCHCHK();
     {

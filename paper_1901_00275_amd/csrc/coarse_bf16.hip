@@ -503,7 +503,8 @@ __global__ __launch_bounds__(256) void k_cells_exact(const float *__restrict__ Q
                                                      const float *__restrict__ C, int k,
                                                      const int32_t *__restrict__ ccnt,
                                                      const int32_t *__restrict__ cidx, int cap, int w,
-                                                     int32_t *__restrict__ cells, float *__restrict__ cell_dist)
+                                                     int32_t *__restrict__ cells, float *__restrict__ cell_dist,
+                                                     int32_t *__restrict__ pair_cnt, int32_t *__restrict__ pair_rank)
 {
     extern __shared__ uint64_t ckeys[]; // [max(cap, CELLS_FB)] then yv [D]
     __shared__ int sh_n;
@@ -561,6 +562,8 @@ __global__ __launch_bounds__(256) void k_cells_exact(const float *__restrict__ Q
         const bool ok = e < cnt && key != KEY_MAX;
         cells[(int64_t)row * w + e] = ok ? (int32_t)(uint32_t)key : -1;
         if (cell_dist) cell_dist[(int64_t)row * w + e] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+        // (query, cell) pairs per cell, for the cell-major pass over the neighbour centroids
+        if (pair_cnt && ok) pair_rank[(int64_t)row * w + e] = atomicAdd(&pair_cnt[(uint32_t)key], 1);
     }
 }
 
@@ -630,12 +633,14 @@ int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, cons
 }
 
 void launch_cells_bf16_exact(const float *Q, int nq, int D, const float *C, int k, int w1, int cap, const void *ws,
-                             int nsplit, int32_t *cells, float *cell_dist, hipStream_t st)
+                             int nsplit, int32_t *cells, float *cell_dist, int32_t *pair_cnt, int32_t *pair_rank,
+                             hipStream_t st)
 {
     size_t og, ot, oc, oi;
     cells_bf16_workspace(nq, nsplit, cap, &og, &ot, &oc, &oi);
     const char *base = (const char *)ws;
     const int nkeys = cap > CELLS_FB ? cap : CELLS_FB;
     hipLaunchKernelGGL(k_cells_exact, dim3((unsigned)nq), dim3(256), (size_t)nkeys * 8 + (size_t)D * 4, st, Q, D, C, k,
-                       (const int32_t *)(base + oc), (const int32_t *)(base + oi), cap, w1, cells, cell_dist);
+                       (const int32_t *)(base + oc), (const int32_t *)(base + oi), cap, w1, cells, cell_dist, pair_cnt,
+                       pair_rank);
 }

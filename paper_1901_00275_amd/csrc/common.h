@@ -188,7 +188,8 @@ size_t cells_bf16_workspace(int nq, int nsplit, int cap, size_t *gmin_off, size_
 int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, const void *Cimg, int k, int D,
                              const float *qn, const float *cn, int w1, int nsplit, int cap, void *ws, hipStream_t st);
 void launch_cells_bf16_exact(const float *Q, int nq, int D, const float *C, int k, int w1, int cap, const void *ws,
-                             int nsplit, int32_t *cells, float *cell_dist, hipStream_t st);
+                             int nsplit, int32_t *cells, float *cell_dist, int32_t *pair_cnt, int32_t *pair_rank,
+                             hipStream_t st);
 
 // w smallest entries of each row of dist [rows x k] (GEMM-form values), re-evaluated
 // as direct sums of squared differences and ordered by (distance, index).
@@ -204,10 +205,22 @@ void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const f
 // that pays.
 bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1);
 size_t neighbour_dists_workspace(int nq, int k, int n, int w1);
+// The parts of that workspace.  A cell selection that can count the (query, cell) pairs per cell as
+// it writes them (and note each pair's rank inside its cell) gets `cnt`, zeroed by
+// launch_pair_counts_zero, and `rank`; launch_subregions is then told that the counting is done.
+struct PairWs {
+    int32_t *cnt;   // [k]
+    int64_t *poff;  // [k + 1]
+    int32_t *rank;  // [nq x w1]
+    int32_t *pairs; // [nq x w1]
+    float *bq;      // [nq x w1 x n]
+};
+PairWs neighbour_dists_carve(void *ws, int nq, int k, int n, int w1);
+void launch_pair_counts_zero(const PairWs &pw, int k, hipStream_t st);
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
                        int n, int k, const int32_t *cells, const float *cell_dist, int w1, int w2,
                        int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       const int64_t *off, uint4 *desc, void *ws, hipStream_t st);
+                       const int64_t *off, uint4 *desc, void *ws, bool pairs_counted, hipStream_t st);
 
 struct ScanArgs {
     const float *Q;

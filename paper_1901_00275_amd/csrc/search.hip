@@ -613,29 +613,46 @@ size_t neighbour_dists_workspace(int nq, int k, int n, int w1)
     return b;
 }
 
+PairWs neighbour_dists_carve(void *ws, int nq, int k, int n, int w1)
+{
+    char *base = (char *)ws;
+    auto take = [&](size_t bytes) {
+        char *at = base;
+        base += (bytes + 255) & ~(size_t)255;
+        return at;
+    };
+    PairWs pw;
+    pw.cnt = (int32_t *)take((size_t)k * 4);
+    pw.poff = (int64_t *)take((size_t)(k + 1) * 8);
+    pw.rank = (int32_t *)take((size_t)nq * w1 * 4);
+    pw.pairs = (int32_t *)take((size_t)nq * w1 * 4);
+    pw.bq = (float *)take((size_t)nq * w1 * n * 4);
+    return pw;
+}
+
+void launch_pair_counts_zero(const PairWs &pw, int k, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)(((int64_t)k + 255) / 256)), dim3(256), 0, st, pw.cnt, (int64_t)k);
+}
+
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
                        int n, int k, const int32_t *cells, const float *cell_dist, int w1, int w2,
                        int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       const int64_t *off, uint4 *desc, void *ws, hipStream_t st)
+                       const int64_t *off, uint4 *desc, void *ws, bool pairs_counted, hipStream_t st)
 {
     if (nq <= 0) return;
     const float *bpre = nullptr;
     if (ws) {
         // neighbour distances cell by cell; ws has neighbour_dists_workspace() bytes
-        char *base = (char *)ws;
-        auto take = [&](size_t bytes) {
-            char *at = base;
-            base += (bytes + 255) & ~(size_t)255;
-            return at;
-        };
-        int32_t *cnt = (int32_t *)take((size_t)k * 4);
-        int64_t *poff = (int64_t *)take((size_t)(k + 1) * 8);
-        int32_t *rank = (int32_t *)take((size_t)nq * w1 * 4);
-        int32_t *pairs = (int32_t *)take((size_t)nq * w1 * 4);
-        float *bq = (float *)take((size_t)nq * w1 * n * 4);
+        const PairWs pw = neighbour_dists_carve(ws, nq, k, n, w1);
+        int32_t *cnt = pw.cnt, *rank = pw.rank, *pairs = pw.pairs;
+        int64_t *poff = pw.poff;
+        float *bq = pw.bq;
         const int64_t np = (int64_t)nq * w1;
-        hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)(((int64_t)k + 255) / 256)), dim3(256), 0, st, cnt, (int64_t)k);
-        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt, rank);
+        if (!pairs_counted) {
+            launch_pair_counts_zero(pw, k, st);
+            hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt, rank);
+        }
         launch_exclusive_scan(cnt, k, poff, st);
         hipLaunchKernelGGL(k_pair_scatter, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, poff,
                            rank, pairs);
