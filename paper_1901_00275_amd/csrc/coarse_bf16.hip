@@ -136,6 +136,7 @@ struct Bf16Args {
     int M, N, D;
     const float *an, *bn;
     int nsplit, tiles_per_split;
+    int tile_stride; // a split takes every tile_stride-th tile of its range (1: all of them)
     // MODE_NN
     uint64_t *cand;
     int idx_bits; // low mantissa bits of a running key that hold (tile, column block)
@@ -165,7 +166,8 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     const int ntiles = (a.N + BT - 1) / BT;
     const int t0 = split * a.tiles_per_split;
     const int t1 = min(ntiles, t0 + a.tiles_per_split);
-    const int ntl = t1 > t0 ? t1 - t0 : 0;
+    const int tstride = a.tile_stride;
+    const int ntl = t1 > t0 ? (t1 - t0 + tstride - 1) / tstride : 0;
     const int last = ntl * SPT - 1; // last step of the split
     const bool use_lo = *a.a_any_lo != 0;
     u32x4 *Apages = lds;
@@ -178,13 +180,16 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
         for (int p = 0; p < SPT * 2; ++p) Apages[p * PAGE + tid] = src[p * PAGE + tid];
     }
 
-    // B pages: step j of this split is the page pair at (t0 * SPT + j) * 2.  Loads past the
-    // last step re-read the last pair, so that the number of loads in flight never varies.
+    // B pages: step j of this split is step j % SPT of its (j / SPT)-th tile, the page pair at
+    // ((t0 + (j / SPT) * tstride) * SPT + j % SPT) * 2.  Loads past the last step re-read the
+    // last pair, so that the number of loads in flight never varies.
     const u32x4 *bsrc = a.B + (int64_t)t0 * SPT * 2 * PAGE + tid;
     auto fetch = [&](u32x4 (&r)[2], int j) {
         j = min(j, last);
-        r[0] = bsrc[(int64_t)(2 * j) * PAGE];
-        r[1] = bsrc[(int64_t)(2 * j + 1) * PAGE];
+        const int jt = j / SPT;
+        const int64_t pg = (int64_t)(j + jt * (tstride - 1) * SPT) * 2;
+        r[0] = bsrc[pg * PAGE];
+        r[1] = bsrc[(pg + 1) * PAGE];
     };
     u32x4 rb[PDEPTH][2];
     if (ntl > 0) {
@@ -237,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     }
     for (int tl = 0; tl < ntl; ++tl) {
         // column norms of this tile, asked for now and used after its last step
-        const int64_t n0 = (int64_t)(t0 + tl) * BT;
+        const int64_t n0 = (int64_t)(t0 + tl * tstride) * BT;
         float cb[2];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -371,7 +376,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
                 const float e = __uint_as_float(u & keep);
                 if (e <= band) {
                     const uint32_t tj = u & ~keep;
-                    const uint32_t col = (uint32_t)(t0 + (int)(tj >> 1)) * BT + wn + 32 * (tj & 1) + (lane & 31);
+                    const uint32_t col = (uint32_t)(t0 + (int)(tj >> 1) * tstride) * BT + wn + 32 * (tj & 1) + (lane & 31);
                     if (col >= (uint32_t)a.N) continue;
                     const int pos = atomicAdd(&rowcnt[rl], 1);
                     const float d = fmaxf(e + ra, 0.f) + 0.f;
@@ -393,6 +398,7 @@ static int launch_mode(Bf16Args &a, hipStream_t st)
 {
     const int ntiles = (a.N + BT - 1) / BT;
     a.tiles_per_split = (ntiles + a.nsplit - 1) / a.nsplit;
+    if (a.tile_stride < 1) a.tile_stride = 1;
     const int spt = a.D / BSTEP;
     const size_t lds_bytes = (size_t)(spt * 2 + 4) * PAGE * 16;
     dim3 grid((unsigned)((a.M + BT - 1) / BT), (unsigned)a.nsplit);
@@ -624,7 +630,14 @@ int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, cons
     a.ccnt = (int32_t *)(base + oc);
     a.cidx = (int32_t *)(base + oi);
     a.cap = cap;
+    // The first sweep only has to bound the w1-th smallest distance from above, and the w1-th
+    // smallest over any subset of the columns does: with many tiles per split it looks at every
+    // other tile (half the work; about twice the columns pass the second sweep's threshold and are
+    // re-evaluated exactly, still well inside the candidate lists).
+    const int ntiles = (k + BT - 1) / BT;
+    a.tile_stride = (ntiles + nsplit - 1) / nsplit >= 8 ? 2 : 1;
     int rc = launch_mode<MODE_MIN>(a, st);
+    a.tile_stride = 1;
     if (rc) return rc;
     const int G = nsplit * 64;
     hipLaunchKernelGGL(k_cell_threshold, dim3((unsigned)nq), dim3(256), (size_t)next_pow2(G) * 8, st, a.gmin, G, w1,

@@ -288,6 +288,36 @@ def test_cell_selection_with_many_centroids(vlq, oracle_mod, monkeypatch, dup, f
         vlq.vlq_index_free(idx)
 
 
+@pytest.mark.parametrize("dup", [0, 600])
+def test_cell_selection_with_long_column_splits(vlq, oracle_mod, dup):
+    """A batch and a codebook large enough that each column split of the first sweep spans eight tiles
+    or more: the sweep then bounds the w1-th smallest distance from every other tile only, and the
+    second sweep lists about twice as many columns for the exact ranking.  Same checks as above on a
+    sample of the queries; with coinciding centroids the lists of the queries near them overflow."""
+    pr = problem(N=2000, k=8192, n=2, m=8, G=256, nq=8192, D=32, iters=1)
+    C = pr.C.copy()
+    Y = pr.Y.copy()
+    if dup:
+        C[100:100 + dup] = C[100]
+        Y[:20] = C[100] + np.arange(20, dtype=np.float32)[:, None]
+    pr2 = Problem(pr.kind, pr.X, Y, C, pr.P, pr.n)
+    idx = make_index(vlq, pr2, base=pr.X[:500])
+    try:
+        rng = np.random.default_rng(5)
+        qs = np.concatenate([np.arange(20), rng.choice(len(Y), 180, replace=False)])
+        dist = oracle_mod.coarse(C, Y[qs])
+        for w1 in (16, 64):
+            od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y, w1, 2 * w1, 10)
+            assert (cells >= 0).all() and (np.sort(cells, axis=1)[:, 1:] != np.sort(cells, axis=1)[:, :-1]).all()
+            for r, q in enumerate(qs):
+                check_selection(cells[q], dict(enumerate(dist[r])), w1, what=f"w1 {w1} query {q} cells")
+                assert np.allclose(cd[q], dist[r][cells[q]], rtol=DTOL, atol=1e-3)
+            if dup:
+                assert (cells[:20] == oracle_mod.select_smallest(dist[:20], w1)).all()
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
     """The distances to the neighbour centroids (Alg. 3, second loop) computed cell by cell over the
     batch and computed inside the per-query kernel are the same sums: every output is identical.
