@@ -240,6 +240,8 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
         ahr[u][0] = __builtin_bit_cast(bf16x8, Apages[u * 2 * PAGE + fa0]);
         ahr[u][1] = __builtin_bit_cast(bf16x8, Apages[u * 2 * PAGE + fa1]);
     }
+    int64_t pend_row = -1; // MODE_EMIT: a reported column whose place in the list is on its way
+    int pend_col = 0, pend_pos = 0;
     for (int tl = 0; tl < ntl; ++tl) {
         // column norms of this tile, asked for now and used after its last step
         const int64_t n0 = (int64_t)(t0 + tl * tstride) * BT;
@@ -314,6 +316,12 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
                 }
         }
         if (MODE == MODE_EMIT) {
+            // A lane rarely has more than one column to report per tile.  The place of the first
+            // one is asked for now and used after the next tile's products, so that the round trip
+            // of the atomic is not waited for; further ones are placed at once.
+            if (pend_row >= 0 && pend_pos < a.cap) a.cidx[pend_row * a.cap + pend_pos] = pend_col;
+            pend_row = -1;
+            bool first = true;
             while (hits) {
                 const int bit = __ffsll((unsigned long long)hits) - 1;
                 hits &= hits - 1;
@@ -321,10 +329,18 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
                 const int64_t row = m0 + slot_row(i, r);
                 const int col = (int)n0 + wn + 32 * j + (lane & 31);
                 const int pos = atomicAdd(&a.ccnt[row], 1);
-                if (pos < a.cap) a.cidx[row * a.cap + pos] = col;
+                if (first) {
+                    pend_row = row;
+                    pend_col = col;
+                    pend_pos = pos;
+                    first = false;
+                } else if (pos < a.cap) {
+                    a.cidx[row * a.cap + pos] = col;
+                }
             }
         }
     }
+    if (MODE == MODE_EMIT && pend_row >= 0 && pend_pos < a.cap) a.cidx[pend_row * a.cap + pend_pos] = pend_col;
 
     if (MODE == MODE_EMIT) return;
     if (MODE == MODE_MIN) {
