@@ -548,10 +548,21 @@ __global__ __launch_bounds__(256) void k_cells_exact(const float *__restrict__ Q
             const float d = sqdist16(yv, C + (int64_t)i * D, D, l16, vec);
             if (l16 == 0 && c < cnt) ckeys[c] = make_key(d, (uint32_t)i);
         }
-        const int sz = next_pow2_dev(cnt);
-        for (int c = cnt + tid; c < sz; c += 256) ckeys[c] = KEY_MAX;
         __syncthreads();
-        block_bitonic_sort<256>(ckeys, sz, tid);
+        if (cnt <= 256) {
+            // a key per thread: its rank among the (distinct) keys is its place in the output
+            const uint64_t mine = tid < cnt ? ckeys[tid] : KEY_MAX;
+            int rank = 0;
+            for (int c = 0; c < cnt; ++c) rank += ckeys[c] < mine;
+            __syncthreads();
+            if (tid < cnt) ckeys[rank] = mine;
+            __syncthreads();
+        } else {
+            const int sz = next_pow2_dev(cnt);
+            for (int c = cnt + tid; c < sz; c += 256) ckeys[c] = KEY_MAX;
+            __syncthreads();
+            block_bitonic_sort<256>(ckeys, sz, tid);
+        }
     } else {
         // exact ranking over all columns: keys below the current w-th smallest are collected;
         // a full buffer is sorted and cut back to w
