@@ -477,18 +477,30 @@ int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, con
 // A query whose list overflows (masses of coinciding distances) is ranked exactly over all
 // columns instead.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict__ gmin, int G, int want,
+// tau = the want-th smallest of the G group minima of a row, found bit by bit from the top of the
+// ordered bit patterns: a wave per row, every trial value is compared with all minima and the lanes
+// that lie below are counted with ballots (scalar work, no sorting, no barriers).
+__global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict__ gmin, int G, int want, int nq,
                                                         const float *__restrict__ qn, float *__restrict__ thr,
                                                         int32_t *__restrict__ ccnt)
 {
-    extern __shared__ uint64_t tkeys[]; // [next_pow2(G)]
-    const int tid = threadIdx.x, row = blockIdx.x;
-    const int sz = next_pow2_dev(G);
-    for (int i = tid; i < sz; i += 256) tkeys[i] = i < G ? (uint64_t)f2ord(gmin[(int64_t)row * G + i]) : KEY_MAX;
-    __syncthreads();
-    block_bitonic_sort<256>(tkeys, sz, tid);
-    if (tid == 0) {
-        const float tau = ord2f((uint32_t)tkeys[want - 1]);
+    extern __shared__ uint32_t tkeys[]; // [4 waves][G]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= nq) return;
+    uint32_t *mine = tkeys + wave * G;
+    for (int i = lane; i < G; i += 64) mine[i] = f2ord(gmin[(int64_t)row * G + i]);
+    // (the wave reads back only what it wrote itself)
+    uint32_t result = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = result | (1u << bit);
+        int below = 0;
+        for (int i = lane; i < G; i += 64) below += __popcll(__ballot(mine[i] < trial));
+        // G is a multiple of 64, so every lane makes the same number of rounds and `below` is uniform
+        if (below < want) result = trial;
+    }
+    if (lane == 0) {
+        const float tau = ord2f(result);
         const float ra = qn[row];
         const float dt = fmaxf(tau + ra, 0.f);
         // below BF16_NO_KEY, so that columns past the end never qualify
@@ -667,8 +679,8 @@ int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, cons
     a.tile_stride = 1;
     if (rc) return rc;
     const int G = nsplit * 64;
-    hipLaunchKernelGGL(k_cell_threshold, dim3((unsigned)nq), dim3(256), (size_t)next_pow2(G) * 8, st, a.gmin, G, w1,
-                       qn, (float *)(base + ot), a.ccnt);
+    hipLaunchKernelGGL(k_cell_threshold, dim3((unsigned)((nq + 3) / 4)), dim3(256), (size_t)4 * G * 4, st, a.gmin, G,
+                       w1, nq, qn, (float *)(base + ot), a.ccnt);
     return launch_mode<MODE_EMIT>(a, st);
 }
 
