@@ -216,6 +216,13 @@ def main():
             sweep.append({"w1": w, "w2": w22, "queries_per_s": nq * max(2, args.steps // 2) / d2,
                           "points_scanned_per_query": pts / nq, **r2})
         result["config"]["sweep"] = sweep
+        # the cheapest probe whose Recall@10 is within 5 % of the headline operating point's
+        ref = rec["R@10"]
+        ok = [e for e in sweep if e["R@10"] >= 0.95 * ref]
+        if ok:
+            best = max(ok, key=lambda e: e["queries_per_s"])
+            result["config"]["cheapest_within_5pct_of_R@10"] = {"w1": best["w1"], "w2": best["w2"],
+                                                                 "queries_per_s": best["queries_per_s"], "R@10": best["R@10"]}
         # the share alpha of the w1 * n sub-regions that is scanned (Sec. 5, parameter study), at the headline w1
         if not cfg.w2_fixed and cfg.n > 1:
             asw = []
