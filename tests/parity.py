@@ -11,6 +11,11 @@ error that no evaluation order in fp32 avoids, and the bands are widened by it:
   * Eq. 14 is evaluated as a sum of terms (Eq. 16-17) of the size of the
     query's distance to its probed cells, so a returned distance carries up to
     ABS_TERMS roundings of that size;
+  * Eq. 8 gives lambda = (a + c - b) / 2c from three sums: where a and b are far
+    larger than c (few centroids, points far from all of them) the difference
+    cancels, and the grid coordinate of the lambda byte is uncertain by
+    LAM_ROUNDINGS roundings of (a + b + c) / 2c grid steps (never less than the
+    2e-3 of a step that well-conditioned lines need);
   * the residual of Eq. 12 is formed from a vector and an anchor of norm far
     above the spacing of the codewords when a sub-space has one dimension, so
     the distances to two codewords are each uncertain by RES_ROUNDINGS
@@ -25,6 +30,7 @@ DTOL = 1e-4
 EPS32 = 2.0 ** -24
 ABS_TERMS = 32  # m + 4 additions of terms, each term itself a rounded sum, with margin
 RES_ROUNDINGS = 16  # anchor (3 roundings) and subtraction (1), both codeword distances, factor 2 margin
+LAM_ROUNDINGS = 32  # each of a, b, c: difference, square and a short accumulation tree per term, with margin
 
 
 def check_selection(got, val_of, w, scale=None, what=""):
