@@ -131,7 +131,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="billion_sift")
     ap.add_argument("--w1", type=int, default=0, help="probed cells (default: the configuration's operating point)")
     ap.add_argument("--points", type=int, default=0, help="build only the first POINTS vectors (debugging)")
