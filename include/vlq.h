@@ -85,6 +85,20 @@ enum {
 };
 
 /*
+ * Kernel choices that normally follow from the shape, and can be fixed per index with
+ * vlq_index_set_option (the tests use them to reach both sides of each choice; none of them
+ * changes what is computed, only by which kernel).  Values are 0 / 1 unless stated.
+ */
+enum {
+    VLQ_OPT_COARSE_FP32 = 0,      /* 1: cells and nearest centroids from the fp32 contraction, not the bf16 x 3 one */
+    VLQ_OPT_NEIGHBOURS_PER_QUERY, /* 1: distances to the neighbour centroids per query, not cell by cell over the batch */
+    VLQ_OPT_SCAN_PACKED,          /* -1 (default): by mean list length; 0: one list per wave at a time; 1: short lists packed */
+    VLQ_OPT_SCAN_GENERIC,         /* 1: the scan with per-cell / per-sub-region tables (2m lookups, Sec. 3.3.2) for every shape */
+    VLQ_OPT_ENCODE_WAVE,          /* 1: the wave-per-vector encode kernel for every shape */
+    VLQ_OPT_COUNT
+};
+
+/*
  * Create an index from trained codebooks (Sec. 3.1): copies C and the PQ
  * codebooks, computes the centroid norms and the n-NN graph (for every c_i
  * its n nearest other centroids, ascending by (distance, index), and the
@@ -155,10 +169,24 @@ int vlq_index_reserve(vlq_index_t *idx, int64_t total);
  * Build the inverted lists from everything staged so far (Sec. 4: list lengths,
  * ids, codes and lambda bytes; list l = cell * n + edge; ascending id inside a
  * list), and per stored point the query-independent part of its ADC distance
- * (||q2||^2 + 2<q1,q2> + (l^2 - l) c of Eq. 15-17, 4 bytes) that the scan streams
- * with the code.  Synchronises the stream.
+ * (||q2||^2 + 2<q1 - mu,q2> + (l^2 - l) c of Eq. 15-17 with mu the mean of the centroids,
+ * summed in fp64, stored as 4 bytes) that the scan streams with the code.  Synchronises the stream.
  */
 int vlq_index_finalize(vlq_index_t *idx, void *stream);
+
+/* Fix one of the VLQ_OPT_* kernel choices for this index.  Takes effect from the next call on. */
+int vlq_index_set_option(vlq_index_t *idx, int option, int value);
+
+/*
+ * Region traversal (Sec. 3.3.1) with the query's lambda restricted to [lo, hi]: the score of a
+ * sub-region becomes the squared distance from the query to that segment of the line l(c_i, s_ij),
+ * i.e. Eq. 7 evaluated at clamp(lambda of Eq. 8, lo, hi).  The default (-inf, +inf) is the literal
+ * reading of Eq. 7-8, the distance to the whole line; (0, 1) is the segment between the two
+ * centroids (Fig. 1c); the index's own (lambda_lo, lambda_hi) is the part of the line on which
+ * stored points can have their anchors.  lo <= hi required.  Only the choice of the w2 visited
+ * sub-regions changes; the distances returned for their points do not.
+ */
+int vlq_index_set_query_lambda_range(vlq_index_t *idx, float lo, float hi);
 
 /* Number of points added / whether the lists are current. */
 int64_t vlq_index_ntotal(const vlq_index_t *idx);
@@ -172,7 +200,7 @@ int vlq_index_params(const vlq_index_t *idx, vlq_params_t *out);
  *   line l(c_i, s_ij) (Eq. 7 at y's own lambda, Eq. 8), 1 <= w2 <= w1*n;
  *   for every point of those lists the distance of Eq. 14, evaluated as
  *   s_x + a + l (b - a) - sum_p T[p][code_p]: the stored per-point term, the two
- *   coarse distances of the sub-region, and one per-query table of 2 <y^p, codeword>
+ *   coarse distances of the sub-region, and one per-query table of 2 <(y - mu)^p, codeword>
  *   (Eq. 16-17 regrouped; m lookups per point.  Shapes outside m in {8, 16},
  *   K <= 128 use per-cell / per-sub-region tables with 2m lookups);
  *   the K smallest by (distance, id); among points whose fp32 distances are

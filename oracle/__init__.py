@@ -264,7 +264,9 @@ def select_smallest(val, w, key=None):
     return out
 
 
-def subregion_scores(dist, S, E, cells):
+def subregion_scores(dist, S, E, cells, qlam=(-np.inf, np.inf)):
+    """Eq. 7-8 line scores of the w1 * n sub-regions of the probed cells; qlam = (lo, hi) restricts
+    the query's lambda to that range before Eq. 7 is evaluated (default: the whole line)."""
     dist = np.ascontiguousarray(dist, np.float64)
     S = _i32(S)
     E = np.ascontiguousarray(E, np.float64)
@@ -276,7 +278,7 @@ def subregion_scores(dist, S, E, cells):
     label = np.empty((nq, w1 * n), np.int32)
     lib().vlqo_subregion_scores(
         _p(dist, C.c_double), nq, k, n, _p(S, C.c_int32), _p(E, C.c_double), _p(cells, C.c_int32), w1,
-        _p(score, C.c_double), _p(label, C.c_int32),
+        C.c_double(qlam[0]), C.c_double(qlam[1]), _p(score, C.c_double), _p(label, C.c_int32),
     )
     return score, label
 
@@ -312,11 +314,11 @@ class SearchTrace:
     ncand: np.ndarray  # [nq]
 
 
-def search(Cb, S, E, P, lists: Lists, Y, w1, w2, K, lo=LAMBDA_LO, hi=LAMBDA_HI) -> SearchTrace:
+def search(Cb, S, E, P, lists: Lists, Y, w1, w2, K, lo=LAMBDA_LO, hi=LAMBDA_HI, qlam=(-np.inf, np.inf)) -> SearchTrace:
     """Alg. 3 as the composition of its steps."""
     dist = coarse(Cb, Y)
     cells = select_smallest(dist, w1)
-    score, label = subregion_scores(dist, S, E, cells)
+    score, label = subregion_scores(dist, S, E, cells, qlam)
     sub = select_smallest(score, w2, key=label)
     out_d, out_id, ncand = scan(Cb, S, P, lists, Y, sub, K, lo, hi)
     return SearchTrace(dist, cells, score, label, sub, out_d, out_id, ncand)

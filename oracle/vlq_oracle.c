@@ -308,10 +308,14 @@ void vlqo_select_smallest(const double *val, const int32_t *key, int nq, int len
 /* Sec. 3.3.1, second-level traversal: the query is line-quantised against every
  * edge (i, j) of every probed cell: score = Eq. 7 at the query's own lambda
  * (Eq. 8) with a = dist[q][i], b = dist[q][S_i[j]], c = E_ij.
+ * Variant: the query's lambda restricted to [qlo, qhi] before Eq. 7 is evaluated
+ * (the distance to that segment of the line; -inf / +inf is the literal reading,
+ * the whole line).
  * score[q][e*n + j] for the e-th probed cell; label[q][e*n + j] = i*n + j. */
 void vlqo_subregion_scores(const double *dist, int nq, int k, int n,
                            const int32_t *S, const double *E,
-                           const int32_t *cells, int w1, double *score, int32_t *label)
+                           const int32_t *cells, int w1, double qlo, double qhi,
+                           double *score, int32_t *label)
 {
 #pragma omp parallel for schedule(static)
     for (int q = 0; q < nq; ++q)
@@ -322,6 +326,8 @@ void vlqo_subregion_scores(const double *dist, int nq, int k, int n,
                 double b = dist[(size_t)q * k + S[(size_t)i * n + j]];
                 double c = E[(size_t)i * n + j];
                 double lam = vlqo_line_lambda(a, b, c);
+                if (lam < qlo) lam = qlo;
+                if (lam > qhi) lam = qhi;
                 size_t o = ((size_t)q * w1 + e) * n + j;
                 score[o] = vlqo_line_dist2(a, b, c, lam);
                 label[o] = i * n + j;

@@ -18,6 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libvlq.so")
 
 VLQ_OK, VLQ_EINVAL, VLQ_ENOMEM, VLQ_EHIP = 0, -1, -2, -3
 STAGES = ("coarse", "select_cells", "subregions", "scan", "merge")
+(VLQ_OPT_COARSE_FP32, VLQ_OPT_NEIGHBOURS_PER_QUERY, VLQ_OPT_SCAN_PACKED, VLQ_OPT_SCAN_GENERIC,
+ VLQ_OPT_ENCODE_WAVE) = range(5)
 
 
 class VlqError(RuntimeError):
@@ -54,6 +56,8 @@ def lib():
             "vlq_index_finalize": [vp, vp],
             "vlq_index_is_finalized": [vp],
             "vlq_index_params": [vp, C.POINTER(vlq_params_t)],
+            "vlq_index_set_option": [vp, C.c_int, C.c_int],
+            "vlq_index_set_query_lambda_range": [vp, C.c_float, C.c_float],
             "vlq_search": [vp, vp, i32, i32, i32, i32, vp, vp, vp],
             "vlq_search_debug": [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp],
             "vlq_index_get_graph": [vp, vp, vp, vp],
@@ -161,6 +165,14 @@ def vlq_index_params(idx) -> vlq_params_t:
     p = vlq_params_t()
     _chk(lib().vlq_index_params(idx, C.byref(p)))
     return p
+
+
+def vlq_index_set_option(idx, option, value):
+    _chk(lib().vlq_index_set_option(idx, int(option), int(value)))
+
+
+def vlq_index_set_query_lambda_range(idx, lo, hi):
+    _chk(lib().vlq_index_set_query_lambda_range(idx, float(lo), float(hi)))
 
 
 def vlq_search(idx, d_q, nq, w1, w2, K, d_out_dist, d_out_ids, stream=None):

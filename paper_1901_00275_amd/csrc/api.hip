@@ -49,9 +49,20 @@ struct ProfRec {
 struct vlq_index {
     vlq_params_t p;
     float lam_step, lam_zero;
+    double lam_step_d;
     // codebooks and graph
-    float *C = nullptr, *cn = nullptr, *P = nullptr, *E = nullptr;
+    float *C = nullptr, *P = nullptr, *E = nullptr;
     int32_t *S = nullptr;
+    // Distances do not depend on the origin, the rounding error of an inner product does: the
+    // contractions and the scan's tables work relative to the mean of the centroids.
+    //   mu   [D] the mean, for the scan (s_x and the query's table);
+    //   mu_c [D] the mean rounded to integers, for the contractions (integer-valued vectors minus
+    //        an integer vector stay exactly representable in bf16);
+    //   cn   [k] ||c - mu_c||^2;  Cc [k x D] c - mu_c, the operand of the fp32 contraction.
+    float *mu = nullptr, *mu_c = nullptr, *cn = nullptr, *Cc = nullptr;
+    // kernel choices (vlq_index_set_option) and the query-side lambda range
+    int opt[VLQ_OPT_COUNT] = {0, 0, -1, 0, 0};
+    float qlam_lo = -INFINITY, qlam_hi = INFINITY;
     // centroids split into bf16 (hi, lo) for the matrix-core shortlist; null when D does not allow it
     void *Cimg = nullptr;
     int32_t *flags = nullptr;
@@ -131,7 +142,7 @@ extern "C" void vlq_index_free(vlq_index_t *idx)
     (void)hipDeviceSynchronize();
     void *ptrs[] = {idx->C, idx->cn, idx->P, idx->E, idx->S, idx->st_label, idx->st_ids, idx->st_lam,
                     idx->st_codes, idx->off, idx->ids, idx->codes, idx->lam, idx->sx, idx->ws,
-                    idx->Cimg, idx->flags};
+                    idx->Cimg, idx->flags, idx->mu, idx->mu_c, idx->Cc};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (auto &r : idx->recs) {
@@ -144,7 +155,7 @@ extern "C" void vlq_index_free(vlq_index_t *idx)
 // ---------------------------------------------------------------------------
 // build
 // ---------------------------------------------------------------------------
-static int check_params(const vlq_params_t *p, float *step, float *zero)
+static int check_params(const vlq_params_t *p, double *step, float *zero)
 {
     if (!p) return fail(VLQ_EINVAL, "params is NULL");
     if (p->d < 1 || p->d > VLQ_MAX_DIM) return fail(VLQ_EINVAL, "d = %d outside [1, %d]", p->d, VLQ_MAX_DIM);
@@ -162,7 +173,7 @@ static int check_params(const vlq_params_t *p, float *step, float *zero)
     if (!(lo <= 0.0 && hi > 0.0 && hi > lo)) return fail(VLQ_EINVAL, "lambda grid [%g, %g] must contain 0", lo, hi);
     const double s = (hi - lo) / 255.0, z = -lo / s;
     if (fabs(z - rint(z)) > 1e-6) return fail(VLQ_EINVAL, "lambda_lo * 255 / (lambda_hi - lambda_lo) is not an integer");
-    *step = (float)s;
+    *step = s;
     *zero = (float)rint(z);
     return VLQ_OK;
 }
@@ -181,7 +192,7 @@ static int build_graph(vlq_index *idx, hipStream_t st)
     float *dist = b.take<float>((size_t)TR * k);
     for (int64_t r0 = 0; r0 < k; r0 += TR) {
         const int rows = (int)(k - r0 < TR ? k - r0 : TR);
-        launch_coarse_gemm_full(idx->C + r0 * D, rows, idx->C, k, D, idx->cn + r0, idx->cn, dist, k, st);
+        launch_coarse_gemm_full(idx->Cc + r0 * D, rows, idx->Cc, k, D, idx->cn + r0, idx->cn, dist, k, st);
         LAUNCHCHK();
         launch_select_cells(dist, k, rows, k, idx->C + r0 * D, D, idx->cn + r0, idx->C, idx->cn, n, (int)r0,
                             idx->S + r0 * n, idx->E + r0 * n, st);
@@ -194,7 +205,8 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
                                const float *d_base, int64_t N, const int32_t *d_ids, void *stream,
                                vlq_index_t **out)
 {
-    float step, zero;
+    double step;
+    float zero;
     int rc = check_params(params, &step, &zero);
     if (rc) return rc;
     if (!d_centroids || !d_pq || !out) return fail(VLQ_EINVAL, "d_centroids, d_pq and out must not be NULL");
@@ -204,7 +216,8 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
     vlq_index *idx = new (std::nothrow) vlq_index();
     if (!idx) return fail(VLQ_ENOMEM, "host allocation failed");
     idx->p = *params;
-    idx->lam_step = step;
+    idx->lam_step = (float)step;
+    idx->lam_step_d = step;
     idx->lam_zero = zero;
     if (params->lambda_lo == 0.f && params->lambda_hi == 0.f) {
         idx->p.lambda_lo = -0.25f;
@@ -214,6 +227,9 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
     auto body = [&]() -> int {
         HIPCHK(hipMalloc(&idx->C, (size_t)k * D * 4));
         HIPCHK(hipMalloc(&idx->cn, (size_t)k * 4));
+        HIPCHK(hipMalloc(&idx->Cc, (size_t)k * D * 4));
+        HIPCHK(hipMalloc(&idx->mu, (size_t)D * 4));
+        HIPCHK(hipMalloc(&idx->mu_c, (size_t)D * 4));
         HIPCHK(hipMalloc(&idx->P, (size_t)256 * D * 4));
         HIPCHK(hipMalloc(&idx->S, (size_t)k * n * 4));
         HIPCHK(hipMalloc(&idx->E, (size_t)k * n * 4));
@@ -221,12 +237,16 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
         HIPCHK(hipMemcpyAsync(idx->C, d_centroids, (size_t)k * D * 4, hipMemcpyDeviceToDevice, st));
         HIPCHK(hipMemcpyAsync(idx->P, d_pq, (size_t)256 * D * 4, hipMemcpyDeviceToDevice, st));
         HIPCHK(hipMemsetAsync(idx->off, 0, ((size_t)k * n + 1) * 8, st));
-        launch_row_norms(idx->C, k, D, idx->cn, st);
+        launch_col_means(idx->C, k, D, idx->mu, idx->mu_c, st);
+        LAUNCHCHK();
+        launch_center_rows(idx->C, k, D, idx->mu_c, idx->Cc, st);
+        LAUNCHCHK();
+        launch_row_norms(idx->C, k, D, idx->mu_c, idx->cn, st);
         LAUNCHCHK();
         if (coarse_bf16_supported(D)) {
             HIPCHK(hipMalloc(&idx->Cimg, coarse_bf16_image_bytes(k, D)));
             HIPCHK(hipMalloc(&idx->flags, 256));
-            launch_split_bf16(idx->C, k, D, idx->Cimg, idx->flags, st);
+            launch_split_bf16(idx->C, k, D, idx->mu_c, idx->Cimg, idx->flags, st);
             LAUNCHCHK();
         }
         int r = build_graph(idx, st);
@@ -274,17 +294,19 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
     const int k = idx->p.nlist, D = idx->p.d, n = idx->p.n_edges, m = idx->p.m;
     const int64_t chunk = nb < ENC_CHUNK ? nb : ENC_CHUNK;
     const int nsplit = coarse_gemm_nn_splits((int)chunk, k);
-    // shortlist on the bf16 matrix cores unless the dimension rules it out (or the environment asks
-    // for the fp32 product, which the tests use to cover both)
-    const char *env = getenv("VLQ_COARSE_FP32");
-    const bool bf16 = idx->Cimg && !(env && env[0] == '1');
-    float *xn;
+    // shortlist on the bf16 matrix cores unless the dimension rules it out (or the fp32 product is
+    // asked for: VLQ_OPT_COARSE_FP32)
+    const bool bf16 = idx->Cimg && !idx->opt[VLQ_OPT_COARSE_FP32];
+    float *xn, *xc = nullptr;
     uint64_t *cand;
     uint8_t *ximg = nullptr;
     int32_t *tcell, *tedge, *flag;
     auto carve = [&](Bump &b) {
         xn = b.take<float>((size_t)chunk);
-        if (bf16) ximg = b.take<uint8_t>(coarse_bf16_image_bytes(chunk, D));
+        if (bf16)
+            ximg = b.take<uint8_t>(coarse_bf16_image_bytes(chunk, D));
+        else
+            xc = b.take<float>((size_t)chunk * D);
         cand = b.take<uint64_t>((size_t)chunk * nsplit * VLQ_NN_CANDS);
         tcell = b.take<int32_t>((size_t)chunk);
         tedge = b.take<int32_t>((size_t)chunk);
@@ -300,20 +322,25 @@ static int encode_impl(vlq_index *idx, const float *d_x, int64_t nb, int32_t *d_
         const int64_t cnt = nb - s < chunk ? nb - s : chunk;
         const float *x = d_x + s * D;
         // the split count is fixed by the buffer; a short tail only leaves less work per split
-        launch_row_norms(x, cnt, D, xn, st);
+        launch_row_norms(x, cnt, D, idx->mu_c, xn, st);
         LAUNCHCHK();
         EncodeArgs a;
         if (bf16) {
-            launch_split_bf16(x, cnt, D, ximg, flag + 1, st);
+            launch_split_bf16(x, cnt, D, idx->mu_c, ximg, flag + 1, st);
             LAUNCHCHK();
             HIPCHK((hipError_t)launch_coarse_gemm_nn_bf16(ximg, flag + 1, (int)cnt, idx->Cimg, k, D, xn, idx->cn, cand,
                                                           nsplit, &a.band_norm, &a.band_dist, st));
         } else {
-            launch_coarse_gemm_nn(x, (int)cnt, idx->C, k, D, xn, idx->cn, cand, nsplit, st);
+            launch_center_rows(x, cnt, D, idx->mu_c, xc, st);
+            LAUNCHCHK();
+            launch_coarse_gemm_nn(xc, (int)cnt, idx->Cc, k, D, xn, idx->cn, cand, nsplit, st);
             a.band_norm = vlq_fp32_band_norm(D);
             a.band_dist = 0.f;
         }
         LAUNCHCHK();
+        a.mu = idx->mu_c;
+        a.lam_step_d = idx->lam_step_d;
+        a.wave_per_vector = idx->opt[VLQ_OPT_ENCODE_WAVE] != 0;
         a.X = x;
         a.nb = cnt;
         a.D = D;
@@ -398,13 +425,12 @@ extern "C" int vlq_kmeans(const float *d_x, int64_t nt, int32_t d, int32_t k, in
     const int D = d;
     const int64_t chunk = nt < ENC_CHUNK ? nt : ENC_CHUNK;
     const int nsplit = coarse_gemm_nn_splits((int)chunk, k);
-    const char *env = getenv("VLQ_COARSE_FP32");
-    const bool bf16 = coarse_bf16_supported(D) && !(env && env[0] == '1');
+    const bool bf16 = coarse_bf16_supported(D);
     int shift = 62;
     while (shift > 0 && ((int64_t)1 << (62 - shift)) < nt) --shift;
 
     DevBuf buf;
-    float *xn, *cn;
+    float *xn, *cn, *mu, *mu_c, *xc = nullptr, *cc = nullptr;
     uint64_t *cand;
     int32_t *assign, *cnt, *flag;
     long long *sums;
@@ -412,6 +438,8 @@ extern "C" int vlq_kmeans(const float *d_x, int64_t nt, int32_t d, int32_t k, in
     uint8_t *ximg = nullptr, *cimg = nullptr;
     HIPCHK(buf.get(&xn, (size_t)chunk));
     HIPCHK(buf.get(&cn, (size_t)k));
+    HIPCHK(buf.get(&mu, (size_t)D));
+    HIPCHK(buf.get(&mu_c, (size_t)D));
     HIPCHK(buf.get(&cand, (size_t)chunk * nsplit * VLQ_NN_CANDS));
     HIPCHK(buf.get(&assign, (size_t)nt));
     HIPCHK(buf.get(&cnt, (size_t)k));
@@ -421,36 +449,47 @@ extern "C" int vlq_kmeans(const float *d_x, int64_t nt, int32_t d, int32_t k, in
     if (bf16) {
         HIPCHK(buf.get(&ximg, coarse_bf16_image_bytes(chunk, D)));
         HIPCHK(buf.get(&cimg, coarse_bf16_image_bytes(k, D)));
+    } else {
+        HIPCHK(buf.get(&xc, (size_t)chunk * D));
+        HIPCHK(buf.get(&cc, (size_t)k * D));
     }
     HIPCHK(hipMemsetAsync(absmax, 0, 4, st));
     launch_absmax(d_x, nt * D, absmax, st);
     LAUNCHCHK();
 
-    // nearest centroid of every vector (Eq. 2): the encoder's shortlist + exact re-evaluation
+    // nearest centroid of every vector (Eq. 2): the encoder's shortlist + exact re-evaluation; the
+    // product works relative to the (integer-rounded) mean of the current centroids
     auto assign_all = [&]() -> int {
-        launch_row_norms(d_centroids, k, D, cn, st);
+        launch_col_means(d_centroids, k, D, mu, mu_c, st);
+        LAUNCHCHK();
+        launch_row_norms(d_centroids, k, D, mu_c, cn, st);
         LAUNCHCHK();
         if (bf16) {
-            launch_split_bf16(d_centroids, k, D, cimg, flag, st);
-            LAUNCHCHK();
+            launch_split_bf16(d_centroids, k, D, mu_c, cimg, flag, st);
+        } else {
+            launch_center_rows(d_centroids, k, D, mu_c, cc, st);
         }
+        LAUNCHCHK();
         for (int64_t s = 0; s < nt; s += chunk) {
             const int64_t n = nt - s < chunk ? nt - s : chunk;
             const float *x = d_x + s * D;
-            launch_row_norms(x, n, D, xn, st);
+            launch_row_norms(x, n, D, mu_c, xn, st);
             LAUNCHCHK();
             EncodeArgs a = {};
             if (bf16) {
-                launch_split_bf16(x, n, D, ximg, flag + 1, st);
+                launch_split_bf16(x, n, D, mu_c, ximg, flag + 1, st);
                 LAUNCHCHK();
                 HIPCHK((hipError_t)launch_coarse_gemm_nn_bf16(ximg, flag + 1, (int)n, cimg, k, D, xn, cn, cand, nsplit,
                                                               &a.band_norm, &a.band_dist, st));
             } else {
-                launch_coarse_gemm_nn(x, (int)n, d_centroids, k, D, xn, cn, cand, nsplit, st);
+                launch_center_rows(x, n, D, mu_c, xc, st);
+                LAUNCHCHK();
+                launch_coarse_gemm_nn(xc, (int)n, cc, k, D, xn, cn, cand, nsplit, st);
                 a.band_norm = vlq_fp32_band_norm(D);
                 a.band_dist = 0.f;
             }
             LAUNCHCHK();
+            a.mu = mu_c;
             a.X = x;
             a.nb = n;
             a.D = D;
@@ -698,8 +737,8 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
         if (hn <= MAX_LONG) break;
     }
     if (N > 0) {
-        launch_list_static(idx->off, nl, idx->p.n_edges, idx->p.d, m, idx->C, idx->S, idx->E, idx->P, idx->codes,
-                           idx->lam, idx->lam_step, idx->lam_zero, idx->sx, st);
+        launch_list_static(idx->off, nl, idx->p.n_edges, idx->p.d, m, idx->C, idx->S, idx->P, idx->mu, idx->codes,
+                           idx->lam, idx->lam_step_d, idx->lam_zero, idx->sx, st);
         LAUNCHCHK();
     }
     HIPCHK(hipStreamSynchronize(st));
@@ -710,9 +749,13 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
 // ---------------------------------------------------------------------------
 // search
 // ---------------------------------------------------------------------------
+// `fixed` (optional): a caller-provided block of `fixed_bytes` that serves as the scratch memory
+// of this call instead of the index's own (which grows on demand); the call then allocates nothing
+// and fails when the block is too small.
 static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2, int32_t K,
                        float *d_out_dist, int32_t *d_out_ids, int32_t *d_cells, float *d_cell_dist,
-                       int32_t *d_sub, float *d_sub_score, hipStream_t st)
+                       int32_t *d_sub, float *d_sub_score, hipStream_t st, void *fixed = nullptr,
+                       size_t fixed_bytes = 0)
 {
     if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
     const int k = idx->p.nlist, D = idx->p.d, n = idx->p.n_edges, m = idx->p.m;
@@ -728,11 +771,10 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     if (nq == 0) return VLQ_OK;
     if (!d_q || !d_out_dist || !d_out_ids) return fail(VLQ_EINVAL, "d_q, d_out_dist and d_out_ids must not be NULL");
 
-    // cells from two sweeps of the bf16 product where the shape allows it (the environment can ask for
-    // the fp32 distance matrix instead, which the tests use to cover both)
-    const char *env = getenv("VLQ_COARSE_FP32");
+    // cells from two sweeps of the bf16 product where the shape allows it (VLQ_OPT_COARSE_FP32 asks
+    // for the fp32 distance matrix instead)
     int csplit = 0, ccap = 0;
-    const bool bf16 = idx->Cimg && !(env && env[0] == '1') && cells_bf16_plan(nq, k, D, w1, &csplit, &ccap);
+    const bool bf16 = idx->Cimg && !idx->opt[VLQ_OPT_COARSE_FP32] && cells_bf16_plan(nq, k, D, w1, &csplit, &ccap);
     int64_t TQ = ((int64_t)512 << 20) / ((int64_t)4 * k);
     if (TQ < 128) TQ = 128;
     if (TQ > nq) TQ = nq;
@@ -741,8 +783,8 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     uint4 *desc;
     uint8_t *qimg = nullptr, *cws = nullptr, *nws = nullptr;
     int32_t *qflag = nullptr;
-    const char *env2 = getenv("VLQ_NEIGHBOURS_PER_QUERY");
-    const bool by_cell = neighbour_dists_by_cell(nq, k, n, D, w1) && !(env2 && env2[0] == '1');
+    float *qc = nullptr;
+    const bool by_cell = neighbour_dists_by_cell(nq, k, n, D, w1) && !idx->opt[VLQ_OPT_NEIGHBOURS_PER_QUERY];
     size_t o0, o1, o2, o3;
     auto carve = [&](Bump &b, float **qn, float **dist, int32_t **cells, float **cell_dist, int32_t **slab,
                      float **sg, uint64_t **partial) {
@@ -755,6 +797,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
             cws = b.take<uint8_t>(cells_bf16_workspace(nq, csplit, ccap, &o0, &o1, &o2, &o3));
         } else {
             *dist = b.take<float>((size_t)TQ * k);
+            qc = b.take<float>((size_t)TQ * D);
         }
         if (by_cell) nws = b.take<uint8_t>(neighbour_dists_workspace(nq, k, n, w1));
         *cells = b.take<int32_t>((size_t)nq * w1);
@@ -768,12 +811,21 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     uint64_t *partial;
     Bump plan(nullptr);
     carve(plan, &qn, &dist, &cells, &cell_dist, &slab, &sg, &partial);
-    int rc = ws_reserve(idx, plan.off + 256);
-    if (rc) return rc;
-    Bump b(idx->ws);
+    void *wsbase;
+    if (fixed) {
+        if (plan.off + 256 > fixed_bytes)
+            return fail(VLQ_EINVAL, "this search needs %zu bytes of scratch memory, the fixed block holds %zu",
+                        plan.off + 256, fixed_bytes);
+        wsbase = fixed;
+    } else {
+        int rc = ws_reserve(idx, plan.off + 256);
+        if (rc) return rc;
+        wsbase = idx->ws;
+    }
+    Bump b(wsbase);
     carve(b, &qn, &dist, &cells, &cell_dist, &slab, &sg, &partial);
 
-    launch_row_norms(d_q, nq, D, qn, st);
+    launch_row_norms(d_q, nq, D, idx->mu_c, qn, st);
     LAUNCHCHK();
     // with the bf16 cell selection the (query, cell) pairs are counted per cell as the cells are written
     PairWs pw = {};
@@ -786,7 +838,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     if (bf16) {
         {
             StageTimer t(idx, st, VLQ_STAGE_COARSE);
-            launch_split_bf16(d_q, nq, D, qimg, qflag, st);
+            launch_split_bf16(d_q, nq, D, idx->mu_c, qimg, qflag, st);
             LAUNCHCHK();
             HIPCHK((hipError_t)launch_cells_bf16_coarse(qimg, qflag, nq, idx->Cimg, k, D, qn, idx->cn, w1, csplit, ccap,
                                                         cws, st));
@@ -804,7 +856,8 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
             const int rows = (int)(nq - q0 < TQ ? nq - q0 : TQ);
             {
                 StageTimer t(idx, st, VLQ_STAGE_COARSE);
-                launch_coarse_gemm_full(d_q + q0 * D, rows, idx->C, k, D, qn + q0, idx->cn, dist, k, st);
+                launch_center_rows(d_q + q0 * D, rows, D, idx->mu_c, qc, st);
+                launch_coarse_gemm_full(qc, rows, idx->Cc, k, D, qn + q0, idx->cn, dist, k, st);
             }
             LAUNCHCHK();
             {
@@ -833,14 +886,15 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     a.codes = idx->codes;
     a.lam = idx->lam;
     a.sx = idx->sx;
+    a.mu = idx->mu;
     a.desc = desc;
     {
-        // lists of a few tens of points: several of them share a chunk of 64 lanes (the environment can
-        // force either form, which the tests use to cover both)
-        const char *pk = getenv("VLQ_SCAN_PACKED");
+        // lists of a few tens of points: several of them share a chunk of 64 lanes
+        // (VLQ_OPT_SCAN_PACKED forces either form)
         const int64_t nl = (int64_t)k * n;
-        a.packed = pk ? (pk[0] == '1') : (idx->ntotal < 64 * nl);
+        a.packed = idx->opt[VLQ_OPT_SCAN_PACKED] >= 0 ? idx->opt[VLQ_OPT_SCAN_PACKED] : (idx->ntotal < 64 * nl);
     }
+    a.force_generic = idx->opt[VLQ_OPT_SCAN_GENERIC] != 0;
     a.lam_step = idx->lam_step;
     a.lam_zero = idx->lam_zero;
     a.scan_label = slab;
@@ -852,8 +906,9 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
         StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS);
         // the streaming scan takes the visited sub-regions from desc alone, in any order
         const bool stream = scan_will_stream(a);
-        launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, k, cells, cell_dist, w1, w2, d_sub, d_sub_score,
-                          stream ? nullptr : slab, stream ? nullptr : sg, idx->off, desc, nws, pairs_counted, st);
+        launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, k, cells, cell_dist, w1, w2, idx->qlam_lo, idx->qlam_hi,
+                          d_sub, d_sub_score, stream ? nullptr : slab, stream ? nullptr : sg, idx->off, desc, nws,
+                          pairs_counted, st);
     }
     LAUNCHCHK();
     {
@@ -907,6 +962,31 @@ extern "C" int vlq_search_debug(const vlq_index_t *idx, const float *d_q, int32_
 {
     return search_tiled(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, d_cells, d_cell_dist,
                         d_sub, d_sub_score, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------
+// options
+// ---------------------------------------------------------------------------
+extern "C" int vlq_index_set_option(vlq_index_t *idx, int option, int value)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (option < 0 || option >= VLQ_OPT_COUNT) return fail(VLQ_EINVAL, "unknown option %d", option);
+    if (option == VLQ_OPT_SCAN_PACKED) {
+        if (value < -1 || value > 1) return fail(VLQ_EINVAL, "VLQ_OPT_SCAN_PACKED takes -1, 0 or 1");
+    } else if (value != 0 && value != 1) {
+        return fail(VLQ_EINVAL, "option %d takes 0 or 1", option);
+    }
+    idx->opt[option] = value;
+    return VLQ_OK;
+}
+
+extern "C" int vlq_index_set_query_lambda_range(vlq_index_t *idx, float lo, float hi)
+{
+    if (!idx) return fail(VLQ_EINVAL, "idx is NULL");
+    if (!(lo <= hi)) return fail(VLQ_EINVAL, "query lambda range [%g, %g] is empty", (double)lo, (double)hi);
+    idx->qlam_lo = lo;
+    idx->qlam_hi = hi;
+    return VLQ_OK;
 }
 
 // ---------------------------------------------------------------------------

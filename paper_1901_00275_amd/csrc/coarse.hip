@@ -12,22 +12,66 @@
 // row norms
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_row_norms(const float *__restrict__ X, int64_t rows, int D,
-                                                   float *__restrict__ out)
+                                                   const float *__restrict__ mu, float *__restrict__ out)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
     const float *x = X + row * D;
     float s = 0.f;
-    for (int d = lane; d < D; d += 64) s = fmaf(x[d], x[d], s);
+    for (int d = lane; d < D; d += 64) {
+        const float v = mu ? x[d] - mu[d] : x[d];
+        s = fmaf(v, v, s);
+    }
     s = wave_sum(s);
     if (lane == 0) out[row] = s;
 }
 
-void launch_row_norms(const float *X, int64_t rows, int D, float *out, hipStream_t st)
+void launch_row_norms(const float *X, int64_t rows, int D, const float *mu, float *out, hipStream_t st)
 {
     if (rows <= 0) return;
-    hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, X, rows, D, out);
+    hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, X, rows, D, mu, out);
+}
+
+__global__ __launch_bounds__(256) void k_center_rows(const float *__restrict__ X, int64_t count, int D,
+                                                     const float *__restrict__ mu, float *__restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += stride) out[i] = X[i] - mu[i % D];
+}
+
+void launch_center_rows(const float *X, int64_t rows, int D, const float *mu, float *out, hipStream_t st)
+{
+    const int64_t count = rows * D;
+    if (count <= 0) return;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_center_rows, dim3((unsigned)blocks), dim3(256), 0, st, X, count, D, mu, out);
+}
+
+// One workgroup per column: threads stride over the rows with fp64 partial sums, combined in a
+// fixed order (wave butterfly, then the four waves in turn).
+__global__ __launch_bounds__(256) void k_col_means(const float *__restrict__ X, int64_t rows, int D,
+                                                   float *__restrict__ mu, float *__restrict__ mu_int)
+{
+    __shared__ double part[4];
+    const int d = blockIdx.x, tid = threadIdx.x;
+    double s = 0.0;
+    for (int64_t r = tid; r < rows; r += 256) s += (double)X[r * D + d];
+    s = wave_sum_f64(s);
+    if ((tid & 63) == 0) part[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) {
+        const double mean = (part[0] + part[1] + part[2] + part[3]) / (double)rows;
+        mu[d] = (float)mean;
+        mu_int[d] = (float)rint(mean);
+    }
+}
+
+void launch_col_means(const float *X, int64_t rows, int D, float *mu, float *mu_int, hipStream_t st)
+{
+    if (rows <= 0 || D <= 0) return;
+    hipLaunchKernelGGL(k_col_means, dim3((unsigned)D), dim3(256), 0, st, X, rows, D, mu, mu_int);
 }
 
 // ---------------------------------------------------------------------------
@@ -161,6 +205,7 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
     __shared__ unsigned long long rowmin[GT];
     __shared__ int rowcnt[GT];
     __shared__ unsigned long long rowcand[GT][VLQ_NN_CANDS];
+    __shared__ int rowovf[GT];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int64_t m0 = (int64_t)blockIdx.x * GT;
@@ -211,6 +256,7 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
     if (tid < GT) {
         rowmin[tid] = KEY_MAX;
         rowcnt[tid] = 1; // slot 0 is the minimum itself
+        rowovf[tid] = 0;
 #pragma unroll
         for (int s = 0; s < VLQ_NN_CANDS; ++s) rowcand[tid][s] = KEY_MAX;
     }
@@ -234,6 +280,9 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
             // rounding band of the GEMM form: a few ulp of ||a||^2 + ||b||^2 <= 3||a||^2 + 2 d
             const float band = dmin + band_norm * (3.f * ra[i][r] + 2.f * dmin);
             uint64_t ks[2] = {b1[i][r], b2[i][r]};
+            // a lane keeps two keys per row: when its second one lies inside the band a third may
+            // have been dropped, so the row is handed on as incomplete
+            if (ks[1] != KEY_MAX && __uint_as_float((uint32_t)(ks[1] >> 32)) <= band) rowovf[rl] = 1;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 if (ks[s] == KEY_MAX || ks[s] == mn) continue;
@@ -246,7 +295,8 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
     __syncthreads();
     if (tid < GT && m0 + tid < M) {
         uint64_t *dst = cand + ((m0 + tid) * nsplit + split) * VLQ_NN_CANDS;
-        dst[0] = rowmin[tid];
+        const bool ovf = rowovf[tid] != 0 || rowcnt[tid] > VLQ_NN_CANDS;
+        dst[0] = ovf ? VLQ_NN_OVERFLOW : rowmin[tid];
 #pragma unroll
         for (int s = 1; s < VLQ_NN_CANDS; ++s) dst[s] = rowcand[tid][s];
     }

@@ -40,12 +40,12 @@ __device__ __forceinline__ uint32_t bf16_rne(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-// X [rows x D] fp32 -> image [ceil(rows / 128)][D / 16][hi page, lo page]; rows past
+// X [rows x D] fp32 (minus mu [D], if given) -> image [ceil(rows / 128)][D / 16][hi page, lo page]; rows past
 // the end are written as zeros.  *any_lo is raised when some lo is non-zero.
 // One thread per (row, chunk of 8 values).
 __global__ __launch_bounds__(256) void k_split_bf16(const float *__restrict__ X, int64_t rows, int D,
-                                                    int64_t padded_rows, u32x4 *__restrict__ img,
-                                                    int *__restrict__ any_lo)
+                                                    const float *__restrict__ mu, int64_t padded_rows,
+                                                    u32x4 *__restrict__ img, int *__restrict__ any_lo)
 {
     const int cpr = D / 8; // chunks per row
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -55,8 +55,12 @@ __global__ __launch_bounds__(256) void k_split_bf16(const float *__restrict__ X,
         const int ch = (int)(i - row * cpr);
         u32x4 ph = {0, 0, 0, 0}, pl = {0, 0, 0, 0};
         if (row < rows) {
-            const f32x4 v0 = *(const f32x4 *)(X + row * D + ch * 8);
-            const f32x4 v1 = *(const f32x4 *)(X + row * D + ch * 8 + 4);
+            f32x4 v0 = *(const f32x4 *)(X + row * D + ch * 8);
+            f32x4 v1 = *(const f32x4 *)(X + row * D + ch * 8 + 4);
+            if (mu) { // distances do not depend on the origin; the error of the product does
+                v0 -= *(const f32x4 *)(mu + ch * 8);
+                v1 -= *(const f32x4 *)(mu + ch * 8 + 4);
+            }
             uint32_t h[8], l[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -94,13 +98,13 @@ size_t coarse_bf16_image_bytes(int64_t rows, int D)
     return (size_t)blocks * BT * D * 4;
 }
 
-void launch_split_bf16(const float *X, int64_t rows, int D, void *img, int *any_lo, hipStream_t st)
+void launch_split_bf16(const float *X, int64_t rows, int D, const float *mu, void *img, int *any_lo, hipStream_t st)
 {
     hipLaunchKernelGGL(k_zero_flag, dim3(1), dim3(1), 0, st, any_lo);
     const int64_t padded = (rows + BT - 1) / BT * BT;
     const int64_t n = padded * (D / 8);
     if (n <= 0) return;
-    hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, X, rows, D, padded,
+    hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, X, rows, D, mu, padded,
                        (u32x4 *)img, any_lo);
 }
 
@@ -359,10 +363,12 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     __syncthreads(); // the operand pages are dead from here on
     unsigned *rowmin = (unsigned *)lds;                                         // [BT]
     int *rowcnt = (int *)(rowmin + BT);                                         // [BT]
-    unsigned long long *rowcand = (unsigned long long *)(rowcnt + BT);          // [BT][VLQ_NN_CANDS]
+    int *rowovf = rowcnt + BT;                                                  // [BT]
+    unsigned long long *rowcand = (unsigned long long *)(rowovf + BT);          // [BT][VLQ_NN_CANDS]
     if (tid < BT) {
         rowmin[tid] = 0xFFFFFFFFu;
         rowcnt[tid] = 0;
+        rowovf[tid] = 0;
 #pragma unroll
         for (int s = 0; s < VLQ_NN_CANDS; ++s) rowcand[tid * VLQ_NN_CANDS + s] = KEY_MAX;
     }
@@ -385,6 +391,9 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             const float dmin = fmaxf(emin + ra, 0.f);
             const float band = emin + a.band_dist * (ra + dmin) + BF16_BAND_NORM * (3.f * ra + 2.f * dmin);
             const float ks[2] = {b1[i][r], b2[MODE == MODE_NN ? i : 0][r]};
+            // a lane keeps two keys per row: when its second one lies inside the band a third may
+            // have been dropped, so the row is handed on as incomplete
+            if (ks[1] < BF16_NO_KEY && __uint_as_float(__float_as_uint(ks[1]) & keep) <= band) rowovf[rl] = 1;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 if (!(ks[s] < BF16_NO_KEY)) continue;
@@ -404,8 +413,9 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     __syncthreads();
     if (tid < BT && m0 + tid < a.M) {
         uint64_t *dst = a.cand + ((m0 + tid) * a.nsplit + split) * VLQ_NN_CANDS;
+        const bool ovf = rowovf[tid] != 0 || rowcnt[tid] > VLQ_NN_CANDS;
 #pragma unroll
-        for (int s = 0; s < VLQ_NN_CANDS; ++s) dst[s] = rowcand[tid * VLQ_NN_CANDS + s];
+        for (int s = 0; s < VLQ_NN_CANDS; ++s) dst[s] = s == 0 && ovf ? VLQ_NN_OVERFLOW : rowcand[tid * VLQ_NN_CANDS + s];
     }
 }
 

@@ -49,6 +49,14 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// wave-wide fp64 sum (butterfly, fixed order), identical in every lane
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o)
 {
     uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
@@ -142,8 +150,14 @@ static inline int next_pow2(int v)
 // Kernel launchers (one per .hip file).  All pointers are device pointers.
 // ---------------------------------------------------------------------------
 
-// Squared norms of the rows of X [rows x D].
-void launch_row_norms(const float *X, int64_t rows, int D, float *out, hipStream_t st);
+// Squared norms of the rows of X [rows x D]; with mu [D] given, of X - mu.
+void launch_row_norms(const float *X, int64_t rows, int D, const float *mu, float *out, hipStream_t st);
+// out = X - mu row by row (the fp32 contraction is handed centred operands: its rounding error is
+// relative to the norms, and distances do not depend on the origin).
+void launch_center_rows(const float *X, int64_t rows, int D, const float *mu, float *out, hipStream_t st);
+// Column means of X [rows x D] (fp64 sums in row order): mu [D] the mean, mu_int [D] the mean rounded
+// to the nearest integer (subtracting it keeps integer-valued data exactly representable in bf16).
+void launch_col_means(const float *X, int64_t rows, int D, float *mu, float *mu_int, hipStream_t st);
 
 // GEMM-form squared distances between rows of A [M x D] and rows of B [N x D]
 // on the fp32 matrix cores: out[i*ldo + j] = max(an[i] + bn[j] - 2 <A_i, B_j>, 0).
@@ -154,6 +168,10 @@ void launch_coarse_gemm_full(const float *A, int M, const float *B, int N, int D
 // up to VLQ_NN_CANDS keys (distance bits << 32 | column) per column split that lie
 // within the rounding band of the row minimum.  cand [M x nsplit x VLQ_NN_CANDS].
 #define VLQ_NN_CANDS 8
+// Written in place of the first key of a (row, split) whose shortlist may be incomplete (more
+// in-band columns than slots, or a lane that may have dropped a third one): the consumer then
+// ranks that row exactly over all columns.
+#define VLQ_NN_OVERFLOW 0xFFFFFFFFFFFFFFFEull
 // Width of the band around the smallest distance d of a row a:
 // band_norm * (3 ||a||^2 + 2 d) + band_dist * (||a||^2 + d); the fp32 product has band_dist = 0.
 // fp32 product: each value ||a||^2 + ||b||^2 - 2 <a, b> is off by at most
@@ -170,9 +188,10 @@ void launch_coarse_gemm_nn(const float *A, int M, const float *B, int N, int D, 
 // (bf16 hi/lo pairs in the order the product kernel reads them).  Requires
 // coarse_bf16_supported(D).  The band the consumer has to apply is returned in
 // *band_norm / *band_dist; the return value is 0 or a hipError_t.
+// mu (optional, [D]) is subtracted from every row before the split.
 bool coarse_bf16_supported(int D);
 size_t coarse_bf16_image_bytes(int64_t rows, int D);
-void launch_split_bf16(const float *X, int64_t rows, int D, void *img, int *any_lo, hipStream_t st);
+void launch_split_bf16(const float *X, int64_t rows, int D, const float *mu, void *img, int *any_lo, hipStream_t st);
 int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, const void *Bimg, int N, int D,
                                const float *an, const float *bn, uint64_t *cand, int nsplit, float *band_norm,
                                float *band_dist, hipStream_t st);
@@ -198,7 +217,8 @@ void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const f
                          const float *qn, const float *C, const float *cn, int w, int self0,
                          int32_t *cells, float *cell_dist, hipStream_t st);
 
-// Line scores of the w1*n sub-regions of the probed cells and the w2 best of them.
+// Line scores of the w1*n sub-regions of the probed cells and the w2 best of them; the query's
+// lambda is restricted to [lam_min, lam_max] (-inf / +inf: the whole line).
 // desc (optional): per visited sub-region {list begin, list length, a, b - a} for the streaming scan.
 // ws (optional, neighbour_dists_workspace() bytes): the distances to the neighbour centroids are
 // then computed cell by cell over the whole batch first; neighbour_dists_by_cell() says when
@@ -219,8 +239,8 @@ PairWs neighbour_dists_carve(void *ws, int nq, int k, int n, int w1);
 void launch_pair_counts_zero(const PairWs &pw, int k, hipStream_t st);
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
                        int n, int k, const int32_t *cells, const float *cell_dist, int w1, int w2,
-                       int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       const int64_t *off, uint4 *desc, void *ws, bool pairs_counted, hipStream_t st);
+                       float lam_min, float lam_max, int32_t *sub, float *sub_score, int32_t *scan_label,
+                       float *scan_g, const int64_t *off, uint4 *desc, void *ws, bool pairs_counted, hipStream_t st);
 
 struct ScanArgs {
     const float *Q;
@@ -234,9 +254,11 @@ struct ScanArgs {
     const uint8_t *codes;
     const uint8_t *lam;
     const float *sx;   // per point: query-independent part of the distance (streaming scan)
+    const float *mu;   // [D] the vector both s_x and the query's table are taken relative to
     float lam_step, lam_zero;
     const uint4 *desc; // [nq x w2] {begin, length, a, b - a} per visited sub-region (streaming scan)
     int packed;        // streaming scan: short lists, several per chunk of lanes
+    bool force_generic; // the 2m-lookup kernel whatever the shape
     const int32_t *scan_label;
     const float *scan_g;
     uint64_t *partial; // [nq x nsplit x K] when nsplit > 1
@@ -260,6 +282,9 @@ struct EncodeArgs {
     const float *E;
     const float *P;
     float lam_step, lam_zero;
+    double lam_step_d;  // the grid step of the lambda byte in full precision
+    const float *mu;    // what the product subtracted from every operand row (or null)
+    bool wave_per_vector; // the wave-per-vector kernel for every shape
     const uint64_t *cand;
     int nsplit;
     float band_norm, band_dist; // error band of the shortlist's distances
@@ -288,7 +313,7 @@ void launch_list_scatter(const int32_t *label, const int32_t *st_ids, const uint
                          int32_t *ids, uint8_t *codes, uint8_t *lam, hipStream_t st);
 // s_x of every stored point (see scan_stream.hip)
 void launch_list_static(const int64_t *off, int64_t nl, int n, int D, int m, const float *C, const int32_t *S,
-                        const float *E, const float *P, const uint8_t *codes, const uint8_t *lam, float lam_step,
+                        const float *P, const float *mu, const uint8_t *codes, const uint8_t *lam, double lam_step,
                         float lam_zero, float *sx, hipStream_t st);
 void launch_list_sort(const int64_t *off, int64_t nl, int m, int32_t *ids, uint8_t *codes, uint8_t *lam,
                       int32_t *long_lists, int32_t *n_long, int max_long, hipStream_t st);

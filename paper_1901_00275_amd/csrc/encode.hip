@@ -5,6 +5,71 @@
 #define ENC_NT 256
 #define ENC_PB_MAX 32
 
+// Nearest row of C [k x D] to x by direct sums of squared differences, smallest (distance, index):
+// 16 lanes per row, four rows per pass.  Serves the rows whose shortlist came back incomplete.
+__device__ __forceinline__ uint64_t exact_nearest(const float *x, const float *__restrict__ C, int k, int D, int lane)
+{
+    const int sub = lane >> 4, l16 = lane & 15;
+    const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
+    uint64_t best = KEY_MAX;
+    for (int i0 = 0; i0 < k; i0 += 4) {
+        const int i = i0 + sub;
+        const float *row = C + (int64_t)min(i, k - 1) * D;
+        float acc = 0.f;
+        if (vec) {
+            for (int d = l16 * 4; d < D; d += 64) {
+                const f32x4 cv = *(const f32x4 *)(row + d);
+                const float t0 = x[d] - cv.x, t1 = x[d + 1] - cv.y, t2 = x[d + 2] - cv.z, t3 = x[d + 3] - cv.w;
+                acc = fmaf(t0, t0, acc);
+                acc = fmaf(t1, t1, acc);
+                acc = fmaf(t2, t2, acc);
+                acc = fmaf(t3, t3, acc);
+            }
+        } else {
+            for (int d = l16; d < D; d += 16) {
+                const float t = x[d] - row[d];
+                acc = fmaf(t, t, acc);
+            }
+        }
+        acc = row16_sum(acc);
+        if (i < k) {
+            const uint64_t key = make_key(acc, (uint32_t)i);
+            best = key < best ? key : best;
+        }
+    }
+    return wave_min_u64(best);
+}
+
+// The byte of lambda and the residual for the chosen line (Eq. 12-13), in fp64 so that both are
+// known to the rounding of their own size: lambda is taken as the projection
+// <x - c_i, s_ij - c_i> / ||s_ij - c_i||^2, which is Eq. 8 with a, b and c written out (the same
+// value without the cancellation of a + c - b), and the residual as (x - c_i) - l (s_ij - c_i) with
+// l the grid value of the byte.  x (LDS, one wave's vector) is overwritten with the residual.
+__device__ __forceinline__ float line_byte_and_residual(float *x, const float *__restrict__ ci,
+                                                        const float *__restrict__ sj, int D, int lane,
+                                                        double step, float zero, float *__restrict__ res_out)
+{
+    double g = 0.0, cc = 0.0;
+    for (int d = lane; d < D; d += 64) {
+        const double c = (double)ci[d], e = (double)sj[d] - c, z = (double)x[d] - c;
+        g = fma(z, e, g);
+        cc = fma(e, e, cc);
+    }
+    g = wave_sum_f64(g);
+    cc = wave_sum_f64(cc);
+    const double lam = cc > 0.0 ? g / cc : 0.0;
+    double qd = rint(lam / step) + (double)zero;
+    qd = fmin(fmax(qd, 0.0), 255.0);
+    const double lh = (qd - (double)zero) * step;
+    for (int d = lane; d < D; d += 64) {
+        const double c = (double)ci[d];
+        const float r = (float)(((double)x[d] - c) - lh * ((double)sj[d] - c));
+        x[d] = r;
+        if (res_out) res_out[d] = r;
+    }
+    return (float)qd;
+}
+
 // One workgroup encodes PB consecutive vectors.
 //  phase 1 (a wave per vector): the candidates within the rounding band of the
 //    smallest GEMM-form distance are re-evaluated as direct sums of squared
@@ -31,36 +96,45 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
     for (int pt = wave; pt < np; pt += ENC_NT / 64) {
         const int64_t gid = g0 + pt;
         float *x = res + pt * D;
-        float xn = 0.f;
+        float xn = 0.f; // of the vector as the product saw it (centred when mu is given)
         for (int d = lane; d < D; d += 64) {
             const float v = a.X[gid * D + d];
             x[d] = v;
-            xn = fmaf(v, v, xn);
+            const float vc = a.mu ? v - a.mu[d] : v;
+            xn = fmaf(vc, vc, xn);
         }
         xn = wave_sum(xn);
         // candidates of all column splits
         const int nc = a.nsplit * VLQ_NN_CANDS;
         const uint64_t *cd = a.cand + gid * nc;
         uint64_t mn = KEY_MAX;
+        bool ovf = false;
         for (int c = lane; c < nc; c += 64) {
             const uint64_t key = cd[c];
-            mn = key < mn ? key : mn;
+            if (key == VLQ_NN_OVERFLOW)
+                ovf = true;
+            else
+                mn = key < mn ? key : mn;
         }
-        mn = wave_min_u64(mn);
-        const float dmin = __uint_as_float((uint32_t)(mn >> 32));
-        const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
         uint64_t bk = KEY_MAX;
-        for (int c = 0; c < nc; ++c) {
-            const uint64_t key = cd[c]; // same address in all lanes
-            if (key == KEY_MAX || __uint_as_float((uint32_t)(key >> 32)) > band) continue;
-            const uint32_t idx = (uint32_t)key;
-            const float d = wave_sqdist(x, a.C + (int64_t)idx * D, D, lane);
-            const uint64_t ek = make_key(d, idx);
-            bk = ek < bk ? ek : bk;
-        }
-        if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
-            const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
-            bk = make_key(wave_sqdist(x, a.C + (int64_t)idx * D, D, lane), idx);
+        if (__ballot(ovf)) {
+            bk = exact_nearest(x, a.C, a.k, D, lane); // incomplete shortlist: every centroid
+        } else {
+            mn = wave_min_u64(mn);
+            const float dmin = __uint_as_float((uint32_t)(mn >> 32));
+            const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
+            for (int c = 0; c < nc; ++c) {
+                const uint64_t key = cd[c]; // same address in all lanes
+                if (key == KEY_MAX || __uint_as_float((uint32_t)(key >> 32)) > band) continue;
+                const uint32_t idx = (uint32_t)key;
+                const float d = wave_sqdist(x, a.C + (int64_t)idx * D, D, lane);
+                const uint64_t ek = make_key(d, idx);
+                bk = ek < bk ? ek : bk;
+            }
+            if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
+                const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
+                bk = make_key(wave_sqdist(x, a.C + (int64_t)idx * D, D, lane), idx);
+            }
         }
         const int cell = (int)(uint32_t)bk;
         const float av = ord2f((uint32_t)(bk >> 32));
@@ -70,7 +144,7 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
         }
         // line quantisation inside the cell
         int bj = 0;
-        float bl = 0.f, bd2 = INFINITY;
+        float bd2 = INFINITY;
         for (int j = 0; j < n; ++j) {
             const int s = a.S[(int64_t)cell * n + j];
             const float b = wave_sqdist(x, a.C + (int64_t)s * D, D, lane);
@@ -80,20 +154,10 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
             if (d2 < bd2) {
                 bd2 = d2;
                 bj = j;
-                bl = lam;
             }
         }
-        float qf = rintf(bl / a.lam_step) + a.lam_zero;
-        qf = fminf(fmaxf(qf, 0.f), 255.f);
-        const float lh = (qf - a.lam_zero) * a.lam_step;
-        const float *ci = a.C + (int64_t)cell * D;
-        const float *sj = a.C + (int64_t)a.S[(int64_t)cell * n + bj] * D;
-        for (int d = lane; d < D; d += 64) {
-            const float c = ci[d];
-            const float r = x[d] - fmaf(lh, sj[d] - c, c);
-            x[d] = r;
-            if (a.res) a.res[gid * D + d] = r;
-        }
+        const float qf = line_byte_and_residual(x, a.C + (int64_t)cell * D, a.C + (int64_t)a.S[(int64_t)cell * n + bj] * D,
+                                                D, lane, a.lam_step_d, a.lam_zero, a.res ? a.res + gid * D : nullptr);
         if (lane == 0) {
             if (a.cell) a.cell[gid] = cell;
             if (a.edge) a.edge[gid] = bj;
@@ -170,40 +234,49 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
     for (int pt = wave; pt < np; pt += ENC_NT / 64) {
         const int64_t gid = g0 + pt;
         float *x = res + pt * RS;
-        float xn = 0.f;
+        float xn = 0.f; // of the vector as the product saw it (centred when mu is given)
         for (int d = lane; d < D; d += 64) {
             const float v = a.X[gid * D + d];
             x[d] = v;
-            xn = fmaf(v, v, xn);
+            const float vc = a.mu ? v - a.mu[d] : v;
+            xn = fmaf(vc, vc, xn);
         }
         xn = wave_sum(xn);
         const int nc = a.nsplit * VLQ_NN_CANDS;
         const uint64_t *cd = a.cand + gid * nc;
         uint64_t mn = KEY_MAX;
+        bool ovf = false;
         for (int c = lane; c < nc; c += 64) {
             const uint64_t key = cd[c];
-            mn = key < mn ? key : mn;
+            if (key == VLQ_NN_OVERFLOW)
+                ovf = true;
+            else
+                mn = key < mn ? key : mn;
         }
-        mn = wave_min_u64(mn);
-        const float dmin = __uint_as_float((uint32_t)(mn >> 32));
-        const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
         uint64_t bk = KEY_MAX;
-        for (int c0 = 0; c0 < nc; c0 += 64) { // the few candidates inside the band, found 64 keys at a time
-            const uint64_t key = c0 + lane < nc ? cd[c0 + lane] : KEY_MAX;
-            const bool inb = key != KEY_MAX && !(__uint_as_float((uint32_t)(key >> 32)) > band);
-            uint64_t mask = __ballot(inb);
-            while (mask) {
-                const int src = __ffsll((unsigned long long)mask) - 1;
-                mask &= mask - 1;
-                const uint32_t idx = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, src);
-                const float d = wave_sqdist(x, a.C + (int64_t)idx * D, D, lane);
-                const uint64_t ek = make_key(d, idx);
-                bk = ek < bk ? ek : bk;
+        if (__ballot(ovf)) {
+            bk = exact_nearest(x, a.C, a.k, D, lane); // incomplete shortlist: every centroid
+        } else {
+            mn = wave_min_u64(mn);
+            const float dmin = __uint_as_float((uint32_t)(mn >> 32));
+            const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
+            for (int c0 = 0; c0 < nc; c0 += 64) { // the few candidates inside the band, found 64 keys at a time
+                const uint64_t key = c0 + lane < nc ? cd[c0 + lane] : KEY_MAX;
+                const bool inb = key != KEY_MAX && !(__uint_as_float((uint32_t)(key >> 32)) > band);
+                uint64_t mask = __ballot(inb);
+                while (mask) {
+                    const int src = __ffsll((unsigned long long)mask) - 1;
+                    mask &= mask - 1;
+                    const uint32_t idx = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, src);
+                    const float d = wave_sqdist(x, a.C + (int64_t)idx * D, D, lane);
+                    const uint64_t ek = make_key(d, idx);
+                    bk = ek < bk ? ek : bk;
+                }
             }
-        }
-        if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
-            const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
-            bk = make_key(wave_sqdist(x, a.C + (int64_t)idx * D, D, lane), idx);
+            if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
+                const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
+                bk = make_key(wave_sqdist(x, a.C + (int64_t)idx * D, D, lane), idx);
+            }
         }
         const int cell = (int)(uint32_t)bk;
         const float av = ord2f((uint32_t)(bk >> 32));
@@ -212,7 +285,7 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
         f32x4 y0 = zero, y1 = zero;
         if (has0) y0 = *(const f32x4 *)(xg + d0);
         if (has1) y1 = *(const f32x4 *)(xg + d1);
-        float bd2 = INFINITY, bl = 0.f;
+        float bd2 = INFINITY;
         int bj = 0x7FFFFFFF;
         for (int j0 = 0; j0 < n; j0 += 16) { // 16 rows per round: their loads are all under way together
             int sidx[4];
@@ -257,7 +330,6 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
                     if (d2 < bd2) { // rows of a lane group come in ascending j
                         bd2 = d2;
                         bj = j;
-                        bl = lam;
                     }
                 }
             }
@@ -265,29 +337,16 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
         // the four lane groups hold the best of their rows: smallest (distance, j) overall
 #pragma unroll
         for (int o = 16; o <= 32; o <<= 1) {
-            const float od = __shfl_xor(bd2, o, 64), ol = __shfl_xor(bl, o, 64);
+            const float od = __shfl_xor(bd2, o, 64);
             const int oj = __shfl_xor(bj, o, 64);
             if (od < bd2 || (od == bd2 && oj < bj)) {
                 bd2 = od;
                 bj = oj;
-                bl = ol;
             }
         }
-        if (bj == 0x7FFFFFFF) { // every line distance was NaN (non-finite input): keep the index in range
-            bj = 0;
-            bl = 0.f;
-        }
-        float qf = rintf(bl / a.lam_step) + a.lam_zero;
-        qf = fminf(fmaxf(qf, 0.f), 255.f);
-        const float lh = (qf - a.lam_zero) * a.lam_step;
-        const float *ci = a.C + (int64_t)cell * D;
-        const float *sj = a.C + (int64_t)a.S[(int64_t)cell * n + bj] * D;
-        for (int d = lane; d < D; d += 64) {
-            const float c = ci[d];
-            const float r = x[d] - fmaf(lh, sj[d] - c, c);
-            x[d] = r;
-            if (a.res) a.res[gid * D + d] = r;
-        }
+        if (bj == 0x7FFFFFFF) bj = 0; // every line distance was NaN (non-finite input): keep the index in range
+        const float qf = line_byte_and_residual(x, a.C + (int64_t)cell * D, a.C + (int64_t)a.S[(int64_t)cell * n + bj] * D,
+                                                D, lane, a.lam_step_d, a.lam_zero, a.res ? a.res + gid * D : nullptr);
         if (lane == 0) {
             if (a.cell) a.cell[gid] = cell;
             if (a.edge) a.edge[gid] = bj;
@@ -350,9 +409,7 @@ static bool encode_lanes_supported(const EncodeArgs &a)
 void launch_encode_finish(const EncodeArgs &a, hipStream_t st)
 {
     if (a.nb <= 0) return;
-    const char *env = getenv("VLQ_ENCODE_WAVE"); // 1: the wave-per-vector kernel for every shape (testing)
-    const bool wave_per_vector_only = env && atoi(env) != 0;
-    if (!wave_per_vector_only && encode_lanes_supported(a)) {
+    if (!a.wave_per_vector && encode_lanes_supported(a)) {
         const size_t smem2 = (size_t)ENC2_PB * (a.D + 1) * 4 + (size_t)ENC2_PB * a.m;
         const unsigned grid2 = (unsigned)((a.nb + ENC2_PB - 1) / ENC2_PB);
 #define ENC2_LAUNCH(DSV)                                                                                       \

@@ -285,15 +285,19 @@ void launch_long_list_sort_at(int64_t beg, int64_t len, int m, int32_t *ids, uin
 }
 
 // Query-independent part of the ADC distance of every stored point (Eq. 15-17):
-//   s_x = ||q2||^2 + 2 <q1, q2> + (l^2 - l) c,  q1 = c_i + l (s_ij - c_i),  q2 = codewords of x,
-// i.e. term2 + 2 (1-l) term3 + 2 l term4 + (l^2 - l) term7 of Eq. 16-17 summed per point.
-// One 64-thread workgroup per list: lanes stride over the points, every lane walks the D
-// coordinates of its point (centroid rows come from L1/L2, the same for all lanes).
+//   s_x = ||q2||^2 + 2 <q1 - mu, q2> + (l^2 - l) c,  q1 = c_i + l (s_ij - c_i),  q2 = codewords of x,
+// i.e. term2 + 2 (1-l) term3 + 2 l term4 + (l^2 - l) term7 of Eq. 16-17 summed per point, with the
+// inner products taken relative to a fixed vector mu (the scan's table is 2 <y - mu, q2>, so mu drops
+// out of the distance; what it removes is the part of both inner products that grows with the
+// distance of the data from the origin and would cancel between them in fp32).
+// Summed in fp64 and rounded once.  One 64-thread workgroup per list: the edge length c is formed
+// by the whole wave, then lanes stride over the points, every lane walking the D coordinates of its
+// point (centroid rows come from L1/L2, the same for all lanes).
 __global__ __launch_bounds__(64) void k_list_static(const int64_t *__restrict__ off, int n, int D, int m,
                                                     const float *__restrict__ C, const int32_t *__restrict__ S,
-                                                    const float *__restrict__ E, const float *__restrict__ P,
+                                                    const float *__restrict__ P, const float *__restrict__ mu,
                                                     const uint8_t *__restrict__ codes,
-                                                    const uint8_t *__restrict__ lam, float lam_step, float lam_zero,
+                                                    const uint8_t *__restrict__ lam, double lam_step, float lam_zero,
                                                     float *__restrict__ sx)
 {
     const int64_t l = blockIdx.x;
@@ -302,29 +306,34 @@ __global__ __launch_bounds__(64) void k_list_static(const int64_t *__restrict__ 
     const int i = (int)(l / n);
     const float *ci = C + (int64_t)i * D;
     const float *sj = C + (int64_t)S[l] * D;
-    const float c = E[l];
+    double c = 0.0;
+    for (int d = threadIdx.x; d < D; d += 64) {
+        const double e = (double)sj[d] - (double)ci[d];
+        c = fma(e, e, c);
+    }
+    c = wave_sum_f64(c);
     const int ds = D / m;
     for (int64_t t = beg + threadIdx.x; t < end; t += 64) {
-        const float lh = ((float)lam[t] - lam_zero) * lam_step;
-        float q2n = 0.f, q12 = 0.f;
+        const double lh = ((double)lam[t] - (double)lam_zero) * lam_step;
+        double q2n = 0.0, q12 = 0.0;
         for (int p = 0; p < m; ++p) {
             const float *w = P + ((int64_t)p * 256 + codes[t * m + p]) * ds;
             for (int d = 0; d < ds; ++d) {
                 const int g = p * ds + d;
-                const float cv = ci[g];
-                const float q1 = fmaf(lh, sj[g] - cv, cv);
-                q2n = fmaf(w[d], w[d], q2n);
-                q12 = fmaf(q1, w[d], q12);
+                const double cv = (double)ci[g], wv = (double)w[d];
+                const double q1 = (cv - (double)mu[g]) + lh * ((double)sj[g] - cv);
+                q2n = fma(wv, wv, q2n);
+                q12 = fma(q1, wv, q12);
             }
         }
-        sx[t] = q2n + 2.f * q12 + (lh * lh - lh) * c;
+        sx[t] = (float)(q2n + 2.0 * q12 + (lh * lh - lh) * c);
     }
 }
 void launch_list_static(const int64_t *off, int64_t nl, int n, int D, int m, const float *C, const int32_t *S,
-                        const float *E, const float *P, const uint8_t *codes, const uint8_t *lam, float lam_step,
+                        const float *P, const float *mu, const uint8_t *codes, const uint8_t *lam, double lam_step,
                         float lam_zero, float *sx, hipStream_t st)
 {
     if (nl <= 0) return;
-    hipLaunchKernelGGL(k_list_static, dim3((unsigned)nl), dim3(64), 0, st, off, n, D, m, C, S, E, P, codes, lam,
+    hipLaunchKernelGGL(k_list_static, dim3((unsigned)nl), dim3(64), 0, st, off, n, D, m, C, S, P, mu, codes, lam,
                        lam_step, lam_zero, sx);
 }

@@ -5,12 +5,15 @@
 // and Eq. 17 writes the first part with the coarse distances a = ||y - c_i||^2,
 // b = ||y - s_ij||^2 and the edge length c:  (1-l) a + l b + (l^2 - l) c.
 // Everything that does not depend on the query,
-//     s_x = ||q2||^2 + 2 <q1, q2> + (l^2 - l) c          (term2 + term3/4 + the term7 part),
+//     s_x = ||q2||^2 + 2 <q1 - mu, q2> + (l^2 - l) c     (term2 + term3/4 + the term7 part),
 // is summed once per point when the lists are built and streamed with the code,
 // so that a query needs ONE lookup table for the whole scan,
-//     T[p][t] = 2 <y^p, P[p][t]>                           (term5, 256 D multiply-adds),
+//     T[p][t] = 2 <(y - mu)^p, P[p][t]>                    (term5, 256 D multiply-adds),
 // and per point m table reads:
 //     dist = s_x + a + l (b - a) - sum_p T[p][t_p].
+// mu is one vector fixed per index (the mean of the centroids); it cancels between s_x and T and
+// keeps both inner products, and with them the rounding error of the sum, independent of where
+// the data lie relative to the origin.
 // a and b come from the traversal kernels (term6 / term8 are by-products of the
 // region traversal), so the scan itself touches no centroid.
 //
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     volatile lds_u64 *wk = (volatile lds_u64 *)(keys + wave * SS_WSZ);
     int wcnt = 0;
 
-    for (int d = tid; d < D; d += SS_NT) yv[d] = a.Q[(int64_t)q * D + d];
+    for (int d = tid; d < D; d += SS_NT) yv[d] = a.Q[(int64_t)q * D + d] - a.mu[d];
     for (int i = lane; i < SS_WSZ; i += 64) wk[i] = KEY_MAX;
     if (tid == 0) {
         sh_thr = KEY_MAX;
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     }
     if (tid < SS_NW) sh_q[tid] = KEY_MAX;
     __syncthreads();
-    // the query's table: T[p][t] = 2 <y^p, P[p][t]>
+    // the query's table: T[p][t] = 2 <(y - mu)^p, P[p][t]>
     for (int idx = tid; idx < M * 256; idx += SS_NT) {
         const float *w = a.P + (int64_t)idx * ds;
         const float *yp = yv + (idx >> 8) * ds;
@@ -307,7 +310,7 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
 // Shapes served by this kernel; everything else takes the generic kernel.
 bool scan_stream_supported(const ScanArgs &a)
 {
-    return (a.m == 8 || a.m == 16) && a.K <= SS_KP && a.sx != nullptr && a.desc != nullptr &&
+    return (a.m == 8 || a.m == 16) && a.K <= SS_KP && a.sx != nullptr && a.mu != nullptr && a.desc != nullptr &&
            (((uintptr_t)a.codes) % 16 == 0);
 }
 

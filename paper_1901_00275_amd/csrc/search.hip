@@ -1,6 +1,4 @@
 // Second-level traversal, lookup tables, list scan and K-selection (Alg. 3).
-#include <stdlib.h>
-
 #include "common.h"
 #include <type_traits>
 
@@ -9,7 +7,8 @@
 // l(c_i, s_ij) of every probed cell.  With a = ||y-c_i||^2, b = ||y-s_ij||^2 and
 // c = ||s_ij-c_i||^2, Eq. 8 gives the query's own lambda and Eq. 7 evaluated at
 // that lambda collapses to a - c lambda^2.  a and b are direct sums of squared
-// differences.  The w2 smallest by (score, label i*n+j) are kept.
+// differences.  The w2 smallest by (score, label i*n+j) are kept.  On request the
+// query's lambda is restricted to a range (the distance to a segment of the line).
 //
 // Outputs per query: the visited labels in (score, label) order (for callers
 // that want the traversal) and the same set ordered by label, so that the
@@ -32,6 +31,7 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                                                     const float *__restrict__ E, int n,
                                                     const int32_t *__restrict__ cells,
                                                     const float *__restrict__ cell_dist, int w1, int w2,
+                                                    float lam_min, float lam_max,
                                                     int sz, int32_t *__restrict__ sub,
                                                     float *__restrict__ sub_score,
                                                     int32_t *__restrict__ scan_label,
@@ -81,7 +81,11 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
             const float a = cell_dist[(int64_t)q * w1 + e];
             const float c = E[(int64_t)i * n + j];
             const float lam = c > 0.f ? 0.5f * (a + c - b) / c : 0.f;
-            const float score = a - c * lam * lam;
+            float score = a - c * lam * lam;
+            // lambda restricted to [lam_min, lam_max] (the whole line by default): Eq. 7 at the
+            // restricted value is the distance to the line plus c times the squared shift along it
+            const float lc = fminf(fmaxf(lam, lam_min), lam_max);
+            if (lc != lam) score = fmaf(c * (lc - lam), lc - lam, score);
             key = make_key(score, (uint32_t)(i * n + j));
         }
         keys[t] = key;
@@ -637,8 +641,8 @@ void launch_pair_counts_zero(const PairWs &pw, int k, hipStream_t st)
 
 void launch_subregions(const float *Q, int nq, int D, const float *C, const int32_t *S, const float *E,
                        int n, int k, const int32_t *cells, const float *cell_dist, int w1, int w2,
-                       int32_t *sub, float *sub_score, int32_t *scan_label, float *scan_g,
-                       const int64_t *off, uint4 *desc, void *ws, bool pairs_counted, hipStream_t st)
+                       float lam_min, float lam_max, int32_t *sub, float *sub_score, int32_t *scan_label,
+                       float *scan_g, const int64_t *off, uint4 *desc, void *ws, bool pairs_counted, hipStream_t st)
 {
     if (nq <= 0) return;
     const float *bpre = nullptr;
@@ -674,7 +678,7 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
     size_t smem = lean ? (size_t)sz * (8 + 4) : (size_t)sz * (8 + 4 + 2 + 4) + (size_t)D * 4;
     (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
-                       cell_dist, w1, w2, sz, sub, sub_score, scan_label, scan_g, off, desc, bpre);
+                       cell_dist, w1, w2, lam_min, lam_max, sz, sub, sub_score, scan_label, scan_g, off, desc, bpre);
 }
 
 // ---------------------------------------------------------------------------
@@ -864,12 +868,7 @@ int scan_pick_nsplit(int nq, int w2, int K)
     return ns;
 }
 
-bool scan_will_stream(const ScanArgs &a)
-{
-    // VLQ_SCAN_GENERIC=1 forces the generic kernel (used by the tests to cover both paths)
-    static const bool force_generic = getenv("VLQ_SCAN_GENERIC") && atoi(getenv("VLQ_SCAN_GENERIC")) != 0;
-    return !force_generic && scan_stream_supported(a);
-}
+bool scan_will_stream(const ScanArgs &a) { return !a.force_generic && scan_stream_supported(a); }
 
 void launch_scan(const ScanArgs &a, hipStream_t st)
 {

@@ -4,22 +4,26 @@ Integer outputs must be identical wherever the oracle's gap between the chosen
 alternative and the best rejected one exceeds GAP (1e-5, relative to the scale
 stated per decision); inside that band the GPU's choice must be one of the
 near-tied alternatives.  Floating-point outputs must agree to DTOL relative.
+The lambda byte must be equal, or one step apart when the oracle's grid
+coordinate lies within LAM_WINDOW of a half-integer.
 
-Both bands are relative to the result.  Where fp32 arithmetic forms a small
-result from much larger operands, the rounding of the operands is an absolute
-error that no evaluation order in fp32 avoids, and the bands are widened by it:
-  * Eq. 14 is evaluated as a sum of terms (Eq. 16-17) of the size of the
-    query's distance to its probed cells, so a returned distance carries up to
-    ABS_TERMS roundings of that size;
-  * Eq. 8 gives lambda = (a + c - b) / 2c from three sums: where a and b are far
-    larger than c (few centroids, points far from all of them) the difference
-    cancels, and the grid coordinate of the lambda byte is uncertain by
-    LAM_ROUNDINGS roundings of (a + b + c) / 2c grid steps (never less than the
-    2e-3 of a step that well-conditioned lines need);
-  * the residual of Eq. 12 is formed from a vector and an anchor of norm far
-    above the spacing of the codewords when a sub-space has one dimension, so
-    the distances to two codewords are each uncertain by RES_ROUNDINGS
-    roundings of (|x^p| + |anchor^p|).
+Two bands carry a term that is absolute, each with its derivation:
+
+  * Returned distances.  The scan does not rebuild the point: it sums the terms of
+    Eq. 16-17 (the stored per-point term, m table entries, a, lambda (b - a)), each
+    of which can be far larger than the distance.  Every term is rounded once and so
+    is every partial sum: at most abs_terms(m) = m + 4 roundings, each of at most
+    2^-24 of the size of the terms.  `term_scale` bounds that size from the inputs:
+    the largest coarse distance of the probed cells, plus what the inner products
+    with the codewords can reach relative to the mean of the centroids (both the
+    stored term and the table are taken relative to it, so the bound does not move
+    when data, queries and centroids are translated together).
+  * Codes.  The residual of Eq. 12 is formed in fp64 and rounded once to fp32, which
+    moves it by at most 2^-24 of its own norm; the distance to a codeword moves by
+    no more than the residual does.  Two codewords whose distances (not squared)
+    differ by less than RES_ROUNDINGS of those roundings are a tie (both distances,
+    factor 2 margin).  This matters where sub-spaces have one or two dimensions and
+    256 codewords sit closer together than the rounding of the residual.
 """
 from __future__ import annotations
 
@@ -28,9 +32,22 @@ import numpy as np
 GAP = 1e-5
 DTOL = 1e-4
 EPS32 = 2.0 ** -24
-ABS_TERMS = 32  # m + 4 additions of terms, each term itself a rounded sum, with margin
-RES_ROUNDINGS = 16  # anchor (3 roundings) and subtraction (1), both codeword distances, factor 2 margin
-LAM_ROUNDINGS = 32  # each of a, b, c: difference, square and a short accumulation tree per term, with margin
+LAM_WINDOW = 2e-3  # of a grid step, around the half-integers
+RES_ROUNDINGS = 4
+
+
+def abs_terms(m):
+    return m + 4
+
+
+def term_scale(a_max, y, Cb, P):
+    """Bound on the size of the terms a returned distance is summed from (see above), for one
+    query y: a_max + R^2 + 2 R (2 |y - mu| + sqrt(a_max)), R the largest norm a concatenation of
+    codewords can have, mu the mean of the centroids."""
+    mu = np.asarray(Cb, np.float64).mean(0)
+    R = np.sqrt(sum((np.asarray(P[p], np.float64) ** 2).sum(1).max() for p in range(len(P))))
+    ym = np.linalg.norm(np.asarray(y, np.float64) - mu)
+    return a_max + R * R + 2.0 * R * (2.0 * ym + np.sqrt(a_max))
 
 
 def check_selection(got, val_of, w, scale=None, what=""):
@@ -61,12 +78,14 @@ def check_selection(got, val_of, w, scale=None, what=""):
     return set(got) == set(want)
 
 
-def check_topk(g_d, g_i, o_d, o_i, K, what="", scale=0.0):
+STATS = {"max_abs_over_eps_scale": 0.0, "max_rel": 0.0}
+
+
+def check_topk(g_d, g_i, o_d, o_i, K, what="", scale=0.0, m=8):
     """Final results of one query: GPU (g_d, g_i)[K] against the oracle's first
-    K' >= K results (o_d, o_i).  `scale`: the size of the terms the distance is
-    summed from (the query's largest distance to a probed cell).  Returns True
-    when the id sets are identical."""
-    abs_tol = ABS_TERMS * EPS32 * scale
+    K' >= K results (o_d, o_i).  `scale`: term_scale of the query, m the number of
+    code bytes.  Returns True when the id sets are identical."""
+    abs_tol = abs_terms(m) * EPS32 * scale
     o_map = {int(i): float(d) for d, i in zip(o_d, o_i) if i >= 0}
     n_valid = min(K, len(o_map))
     exact = True
@@ -78,6 +97,9 @@ def check_topk(g_d, g_i, o_d, o_i, K, what="", scale=0.0):
         assert gi in o_map, f"{what}: id {gi} at rank {r} is not among the oracle's best {len(o_map)}"
         od = o_map[gi]
         assert abs(gd - od) <= DTOL * max(od, 1e-30) + abs_tol, f"{what}: distance {gd} vs {od} at rank {r}"
+        if scale > 0:
+            STATS["max_abs_over_eps_scale"] = max(STATS["max_abs_over_eps_scale"], abs(gd - od) / (EPS32 * scale))
+        STATS["max_rel"] = max(STATS["max_rel"], abs(gd - od) / max(od, 1e-30))
         if gi != int(o_i[r]):
             exact = False
             ref = float(o_d[r])

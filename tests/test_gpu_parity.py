@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from parity import DTOL, EPS32, GAP, LAM_ROUNDINGS, RES_ROUNDINGS, check_selection, check_topk
+from parity import DTOL, EPS32, GAP, LAM_WINDOW, RES_ROUNDINGS, check_selection, check_topk, term_scale
 from util import Problem, problem
 
 pytestmark = pytest.mark.gpu
@@ -93,19 +93,10 @@ def check_encode(oracle, pr, S, E, X, got, max_soft=0.01, grid=()):
     soft += len(bad)
     # lambda byte: equal, or one step apart when the coordinate sits on a rounding boundary
     bad = np.nonzero(ok & (lamq != enc.lamq))[0]
-    lo_, hi_ = grid if grid else (oracle.LAMBDA_LO, oracle.LAMBDA_HI)
     for t in bad:
         assert abs(int(lamq[t]) - int(enc.lamq[t])) == 1, f"lambda byte of point {t}"
         frac = enc.lam_coord[t] - np.floor(enc.lam_coord[t])
-        # lambda = (a + c - b) / 2c from three fp32 sums: where a and b dwarf c the difference cancels,
-        # and the grid coordinate is uncertain by LAM_ROUNDINGS roundings of (a + b + c) / 2c grid steps
-        i, j = int(enc.cell[t]), int(enc.edge[t])
-        xt = X[t].astype(np.float64)
-        a = ((xt - pr.C[i].astype(np.float64)) ** 2).sum()
-        b = ((xt - pr.C[int(np.asarray(S)[i, j])].astype(np.float64)) ** 2).sum()
-        c = float(np.asarray(E)[i, j])
-        slack = max(2e-3, LAM_ROUNDINGS * EPS32 * (a + b + c) / (2 * c) * 255.0 / (hi_ - lo_))
-        assert abs(frac - 0.5) < slack, f"lambda byte of point {t}: coordinate {enc.lam_coord[t]} (slack {slack})"
+        assert abs(frac - 0.5) < LAM_WINDOW, f"lambda byte of point {t}: coordinate {enc.lam_coord[t]}"
     ok[bad] = False
     soft += len(bad)
     # PQ (Alg. 2): gap relative to the sub-space distance
@@ -115,11 +106,10 @@ def check_encode(oracle, pr, S, E, X, got, max_soft=0.01, grid=()):
         d0, d1 = enc.code_d[t, p]
         if d1 - d0 <= GAP * max(d1, 1e-30) + 1e-12:
             continue
-        # the residual itself is only known to fp32 rounding of the vector and its anchor
-        xp = X[t, p * ds:(p + 1) * ds].astype(np.float64)
+        # the residual itself is only known to its rounding to fp32
         rp = oracle.line_residual(pr.C, S, X[t:t + 1], enc.cell[t:t + 1], enc.edge[t:t + 1], enc.lamq[t:t + 1],
                                   *grid)[0, p * ds:(p + 1) * ds]
-        dr = RES_ROUNDINGS * EPS32 * (np.linalg.norm(xp) + np.linalg.norm(xp - rp))
+        dr = RES_ROUNDINGS * EPS32 * np.linalg.norm(rp)
         assert np.sqrt(d1) - np.sqrt(d0) <= dr, f"code of point {t}, sub-space {p}"
     soft += int(diff.any(1).sum())
     assert soft <= max(2, max_soft * N), f"{soft} of {N} points fell into tie bands"
@@ -151,14 +141,15 @@ def gpu_search(vlq, idx, Y, w1, w2, K):
     return [t.cpu().numpy() for t in (od, oi, cells, cd, sub, ss)]
 
 
-def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15, grid=()):
+def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15, grid=(), qlam=(-np.inf, np.inf)):
     """Stage by stage.  Where the oracle itself sees a tie (mirrored lines
     l(c_i,c_j) / l(c_j,c_i) tie exactly in exact arithmetic) the GPU's choice is
     first checked to lie inside the oracle's tie band, then the next stage is
     compared for that choice."""
     od, oi, cells, cd, sub, ss = got
     extra = 16
-    tr = oracle.search(pr.C, S, E, pr.P, lists, Y, w1, w2, K + extra, *grid)
+    lo_hi = grid if grid else (oracle.LAMBDA_LO, oracle.LAMBDA_HI)
+    tr = oracle.search(pr.C, S, E, pr.P, lists, Y, w1, w2, K + extra, *lo_hi, qlam=qlam)
     nq = len(Y)
     soft = 0
     for q in range(nq):
@@ -167,7 +158,7 @@ def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15, grid
         assert np.allclose(cd[q], tr.dist[q][cells[q]], rtol=DTOL), what
         score, label = tr.score[q], tr.label[q]
         if not same_cells:
-            score, label = (x[0] for x in oracle.subregion_scores(tr.dist[q:q + 1], S, E, cells[q:q + 1]))
+            score, label = (x[0] for x in oracle.subregion_scores(tr.dist[q:q + 1], S, E, cells[q:q + 1], qlam))
         a_max = tr.dist[q][cells[q]].max()
         val = {int(l): float(s) for l, s in zip(label, score)}
         same_sub = check_selection(sub[q], val, w2, scale=a_max, what=what + " sub-regions")
@@ -176,28 +167,55 @@ def check_search(oracle, pr, S, E, lists, Y, w1, w2, K, got, max_soft=0.15, grid
         if not (same_cells and same_sub):
             soft += 1
             o_d, o_i, _ = (x[0] for x in oracle.scan(pr.C, S, pr.P, lists, Y[q:q + 1], sub[q:q + 1], K + extra, *grid))
-        check_topk(od[q], oi[q], o_d, o_i, K, what=what, scale=a_max)
+        check_topk(od[q], oi[q], o_d, o_i, K, what=what, scale=term_scale(a_max, Y[q], pr.C, pr.P), m=pr.m)
     assert soft <= max(3, max_soft * nq), f"{soft} of {nq} queries fell into tie bands"
     return tr, soft
 
 
+def shifted(pr, shift):
+    """The same problem with data, queries and centroids moved by one vector (codewords quantise
+    residuals and stay): every distance is unchanged in exact arithmetic."""
+    if not shift:
+        return pr
+    v = np.float32(shift)
+    return Problem(pr.kind, pr.X + v, pr.Y + v, pr.C + v, pr.P, pr.n)
+
+
 CASES = {
-    # name: (problem kwargs, w1, w2, K)
+    # name: (problem kwargs, w1, w2, K[, shift])
     "small_d32": (dict(N=3000, k=32, n=4, m=8, G=8, nq=40, D=32), 6, 10, 20),
     "sift_ragged": (dict(N=20011, k=100, n=7, m=8, G=16, nq=77), 9, 25, 100),
     "deep_m16": (dict(kind="deep", N=15000, k=96, n=8, m=16, G=32, nq=50), 8, 20, 50),
     "odd_dims": (dict(N=2000, k=20, n=3, m=3, G=5, nq=30, D=6), 4, 7, 10),
     "ds1": (dict(N=1500, k=24, n=5, m=12, G=5, nq=20, D=12), 5, 9, 33),
     "n1": (dict(N=1500, k=24, n=1, m=4, G=5, nq=20, D=16), 5, 5, 10),
+    # the graph degrees of the parameter study of Sec. 5 (n = 64, n = 128) with 16-byte codes
+    "deep_n64": (dict(kind="deep", N=20000, k=200, n=64, m=16, G=32, nq=30), 8, 128, 50),
+    "deep_n128": (dict(kind="deep", N=20000, k=300, n=128, m=16, G=32, nq=30), 6, 192, 50),
+    "sift_n64_m16": (dict(N=20000, k=200, n=64, m=16, G=32, nq=30), 8, 128, 100),
+    # data far from the origin: SIFT-like values + 1 000 per coordinate, DEEP-like + a constant vector
+    "sift_shifted": (dict(N=20011, k=100, n=7, m=8, G=16, nq=77), 9, 25, 100, 1000.0),
+    "deep_shifted": (dict(kind="deep", N=15000, k=96, n=8, m=16, G=32, nq=50), 8, 20, 50, 3.0),
+    "sift_shifted_generic": (dict(N=3000, k=32, n=4, m=4, G=8, nq=40, D=32), 6, 10, 20, 1000.0),
 }
 
 
+@pytest.fixture(params=["stream", "generic"])
+def scan_kind(request):
+    """Every case runs twice: with the scan the shape selects (one table per query and a stored term
+    per point where m is 8 or 16, several lists per wave when they are short), and with the
+    per-cell / per-sub-region tables of Sec. 3.3.2 (2m lookups per point) forced."""
+    return request.param
+
+
 @pytest.mark.parametrize("name", list(CASES))
-def test_build_encode_search_against_oracle(vlq, oracle_mod, name):
-    kw, w1, w2, K = CASES[name]
-    pr = problem(**kw)
+def test_build_encode_search_against_oracle(vlq, oracle_mod, name, scan_kind):
+    kw, w1, w2, K, *rest = CASES[name]
+    pr = shifted(problem(**kw), rest[0] if rest else 0.0)
     idx = make_index(vlq, pr)
     try:
+        if scan_kind == "generic":
+            vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SCAN_GENERIC, 1)
         Sg, Eg = gpu_graph(vlq, idx, pr)
         assert check_graph(oracle_mod, pr, Sg, Eg), "graph differs from the oracle's inside a tie band: pick another seed"
         S, E = oracle_mod.graph(pr.C, pr.n)
@@ -206,9 +224,46 @@ def test_build_encode_search_against_oracle(vlq, oracle_mod, name):
         load_oracle_index(vlq, idx, enc)
         assert vlq.vlq_index_ntotal(idx) == len(pr.X) and vlq.vlq_index_is_finalized(idx)
         lists = oracle_mod.make_lists(pr.k, pr.n, enc.cell, enc.edge, enc.lamq, enc.codes)
-        # tiny codebooks: most graph edges are mutual, so mirrored-line ties at the cut are frequent
-        soft = 0.6 if pr.k < 30 else 0.15
-        check_search(oracle_mod, pr, S, E, lists, pr.Y, w1, w2, K, gpu_search(vlq, idx, pr.Y, w1, w2, K), max_soft=soft)
+        # small codebooks: most graph edges are mutual, so mirrored-line ties at the cut are frequent
+        # (such a query is still compared in full, for the GPU's choice among the tied lines)
+        soft = 0.6 if pr.k < 30 else 0.25
+        _, nsoft = check_search(oracle_mod, pr, S, E, lists, pr.Y, w1, w2, K, gpu_search(vlq, idx, pr.Y, w1, w2, K),
+                                max_soft=soft)
+        print(f"{name}/{scan_kind}: {nsoft} of {len(pr.Y)} queries compared for a tied choice of sub-regions")
+    finally:
+        vlq.vlq_index_free(idx)
+
+
+@pytest.mark.parametrize("qlam", [(0.0, 1.0), "grid"])
+@pytest.mark.parametrize("name", ["sift_ragged", "deep_m16"])
+def test_restricted_query_lambda(vlq, oracle_mod, name, qlam):
+    """Region traversal with the query's lambda restricted to a range (Sec. 3.3.1 variant): the segment
+    between the two centroids, and the part of the line the lambda byte can express.  Same protocol
+    as above; the selection must really differ from the unrestricted one for some queries."""
+    kw, w1, w2, K = CASES[name]
+    pr = problem(**kw)
+    if qlam == "grid":
+        qlam = (oracle_mod.LAMBDA_LO, oracle_mod.LAMBDA_HI)
+    idx = make_index(vlq, pr)
+    try:
+        S, E = oracle_mod.graph(pr.C, pr.n)
+        enc = oracle_mod.encode(pr.C, S, E, pr.P, pr.X)
+        load_oracle_index(vlq, idx, enc)
+        lists = oracle_mod.make_lists(pr.k, pr.n, enc.cell, enc.edge, enc.lamq, enc.codes)
+        free = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        vlq.vlq_index_set_query_lambda_range(idx, *qlam)
+        got = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        # a restricted lambda sits on the end of its range for many lines of a cell, and all lines of a cell
+        # clamped to lambda = 0 score exactly its coarse distance: ties at the cut are common
+        check_search(oracle_mod, pr, S, E, lists, pr.Y, w1, w2, K, got, qlam=qlam, max_soft=0.5)
+        assert (np.sort(free[4], axis=1) != np.sort(got[4], axis=1)).any(1).mean() > 0.2
+        with pytest.raises(vlq.VlqError):
+            vlq.vlq_index_set_query_lambda_range(idx, 1.0, 0.0)
+        # back to the whole line: the first results again
+        vlq.vlq_index_set_query_lambda_range(idx, -np.inf, np.inf)
+        again = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        for x, y in zip(free, again):
+            assert np.array_equal(x, y)
     finally:
         vlq.vlq_index_free(idx)
 
@@ -240,14 +295,13 @@ def test_other_lambda_grids(vlq, oracle_mod, lo, hi, n):
 
 
 @pytest.mark.parametrize("kind,fp32", [("sift", False), ("deep", False), ("sift", True)])
-def test_encode_with_both_coarse_products(vlq, oracle_mod, monkeypatch, kind, fp32):
+def test_encode_with_both_coarse_products(vlq, oracle_mod, kind, fp32):
     """Alg. 1 + 2 with the nearest-centroid shortlist from the split-bf16 product (integer-valued and
     real-valued data: without and with low halves) and from the fp32 product; several ragged tiles."""
-    if fp32:
-        monkeypatch.setenv("VLQ_COARSE_FP32", "1")
     pr = problem(kind=kind, N=6000, k=300, n=6, m=8, G=16, nq=8)
     idx = make_index(vlq, pr)
     try:
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_COARSE_FP32, int(fp32))
         S, E = oracle_mod.graph(pr.C, pr.n)
         check_encode(oracle_mod, pr, S, E, pr.X, gpu_encode(vlq, idx, pr.X, pr.m))
     finally:
@@ -255,13 +309,11 @@ def test_encode_with_both_coarse_products(vlq, oracle_mod, monkeypatch, kind, fp
 
 
 @pytest.mark.parametrize("dup,fp32", [(0, False), (600, False), (0, True)])
-def test_cell_selection_with_many_centroids(vlq, oracle_mod, monkeypatch, dup, fp32):
+def test_cell_selection_with_many_centroids(vlq, oracle_mod, dup, fp32):
     """Alg. 3, first loop, at a codebook size where the cells come from the two sweeps of the bf16
     product (and, for comparison, from the fp32 distance matrix).  With `dup` coinciding centroids
     the candidate lists of the queries near them overflow and the exact ranking over all centroids
     takes over; ties go to the smaller index."""
-    if fp32:
-        monkeypatch.setenv("VLQ_COARSE_FP32", "1")
     pr = problem(N=4000, k=1024, n=4, m=8, G=64, nq=300, D=32, iters=2)
     C = pr.C.copy()
     if dup:
@@ -272,6 +324,7 @@ def test_cell_selection_with_many_centroids(vlq, oracle_mod, monkeypatch, dup, f
         Y[:20] = C[100] + np.arange(20, dtype=np.float32)[:, None]  # queries that see the whole tie
     idx = make_index(vlq, pr2, base=pr.X[:500])
     try:
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_COARSE_FP32, int(fp32))
         for w1 in (1, 7, 32):
             od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y, w1, min(w1 * pr.n, 16), 10)
             dist = oracle_mod.coarse(C, Y)
@@ -293,6 +346,42 @@ def test_cell_selection_with_many_centroids(vlq, oracle_mod, monkeypatch, dup, f
                 assert (cells[q] == oracle_mod.select_smallest(dist[q:q + 1], w1)[0]).all()
                 want = pick[q]  # with a key the oracle returns the keys (labels) of the selection
                 assert sorted(sub[q].tolist()) == sorted(want.tolist()), f"query {q}: sub-regions at an exact tie"
+    finally:
+        vlq.vlq_index_free(idx)
+
+
+@pytest.mark.parametrize("fp32", [False, True])
+def test_encode_with_coinciding_centroids(vlq, oracle_mod, fp32):
+    """Alg. 1 where hundreds of centroids coincide: the nearest-centroid shortlist of the vectors near
+    them holds more columns inside the rounding band than it has room for, is handed on as incomplete
+    and those vectors are ranked exactly over all centroids.  Exactly equal distances go to the
+    smaller index (Eq. 2), all lines of the chosen cell have length zero (edge 0, lambda 0): cell,
+    edge and byte must equal the oracle's, not merely lie in its tie band."""
+    pr = problem(N=4000, k=1024, n=4, m=8, G=64, nq=8, D=32, iters=2)
+    C = pr.C.copy()
+    C[100:700] = C[100]
+    C[900:905] = C[900]  # a handful only: fits the shortlist, still an exact tie
+    rng = np.random.default_rng(4)
+    X = pr.X.copy()
+    X[:300] = C[100] + rng.normal(scale=2.0, size=(300, pr.D)).astype(np.float32)
+    X[300:400] = C[900] + rng.normal(scale=2.0, size=(100, pr.D)).astype(np.float32)
+    pr2 = Problem(pr.kind, X, pr.Y, C, pr.P, pr.n)
+    idx = make_index(vlq, pr2)
+    try:
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_COARSE_FP32, int(fp32))
+        S, E = oracle_mod.graph(C, pr.n)
+        got = gpu_encode(vlq, idx, X, pr.m)
+        enc, _ = check_encode(oracle_mod, pr2, S, E, X, got, max_soft=1.0)
+        near = np.concatenate([np.nonzero(enc.cell == 100)[0], np.nonzero(enc.cell == 900)[0]])
+        assert len(near) >= 380
+        assert (got[0][near] == enc.cell[near]).all() and (got[1][near] == enc.edge[near]).all()
+        assert (got[1][near] == 0).all() and (got[2][near] == 85).all()
+        assert (got[3][near] == enc.codes[near]).mean() > 0.99
+        # the same through the Lloyd assignment (nearest centroid only)
+        a = torch.empty(len(X), dtype=torch.int32, device=DEV)
+        vlq.vlq_kmeans(dev(X), len(X), pr.D, pr.k, 0, dev(C), a, None)
+        torch.cuda.synchronize()
+        assert (a.cpu().numpy()[near] == enc.cell[near]).all()
     finally:
         vlq.vlq_index_free(idx)
 
@@ -327,7 +416,7 @@ def test_cell_selection_with_long_column_splits(vlq, oracle_mod, dup):
         vlq.vlq_index_free(idx)
 
 
-def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
+def test_neighbour_distances_by_cell_and_by_query_agree(vlq):
     """The distances to the neighbour centroids (Alg. 3, second loop) computed cell by cell over the
     batch and computed inside the per-query kernel are the same sums: every output is identical.
     (The parity cases above run the cell-by-cell form; this pins the other one to it.)"""
@@ -336,7 +425,7 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
     idx = make_index(vlq, pr, base=pr.X)
     try:
         a = gpu_search(vlq, idx, pr.Y, w1, w2, K)
-        monkeypatch.setenv("VLQ_NEIGHBOURS_PER_QUERY", "1")
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_NEIGHBOURS_PER_QUERY, 1)
         b = gpu_search(vlq, idx, pr.Y, w1, w2, K)
         for x, y in zip(a, b):
             assert np.array_equal(x, y)
@@ -345,7 +434,7 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq, monkeypatch):
 
 
 @pytest.mark.parametrize("name", ["sift_ragged", "deep_m16", "small_d32"])
-def test_both_encode_kernels_agree(vlq, oracle_mod, monkeypatch, name):
+def test_both_encode_kernels_agree(vlq, oracle_mod, name):
     """Encoding has a kernel for the common shapes (a lane per vector in the product-quantisation step,
     four neighbour rows per pass in the line step) and a general one (a wave per vector).  The parity
     cases above run whichever serves their shape; here both run on the same vectors.  The line
@@ -356,9 +445,9 @@ def test_both_encode_kernels_agree(vlq, oracle_mod, monkeypatch, name):
     idx = make_index(vlq, pr)
     try:
         S, E = oracle_mod.graph(pr.C, pr.n)
-        monkeypatch.setenv("VLQ_ENCODE_WAVE", "0")
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_ENCODE_WAVE, 0)
         a = gpu_encode(vlq, idx, pr.X, pr.m)
-        monkeypatch.setenv("VLQ_ENCODE_WAVE", "1")
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_ENCODE_WAVE, 1)
         b = gpu_encode(vlq, idx, pr.X, pr.m)
         check_encode(oracle_mod, pr, S, E, pr.X, a)
         check_encode(oracle_mod, pr, S, E, pr.X, b)
@@ -371,7 +460,7 @@ def test_both_encode_kernels_agree(vlq, oracle_mod, monkeypatch, name):
 
 
 @pytest.mark.parametrize("name", ["sift_ragged", "deep_m16"])
-def test_packed_and_per_list_scan_agree(vlq, monkeypatch, name):
+def test_packed_and_per_list_scan_agree(vlq, name):
     """The streaming scan in its two forms - several short lists laid end to end over the lanes of a
     wave, or one list at a time - computes the same keys: every output is identical.  (Indexes with
     fewer than 64 points per list take the packed form by default, so the parity cases above run it;
@@ -380,16 +469,16 @@ def test_packed_and_per_list_scan_agree(vlq, monkeypatch, name):
     pr = problem(**kw)
     idx = make_index(vlq, pr, base=pr.X)
     try:
-        monkeypatch.setenv("VLQ_SCAN_PACKED", "1")
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SCAN_PACKED, 1)
         a = gpu_search(vlq, idx, pr.Y, w1, w2, K)
-        monkeypatch.setenv("VLQ_SCAN_PACKED", "0")
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SCAN_PACKED, 0)
         b = gpu_search(vlq, idx, pr.Y, w1, w2, K)
         for x, y in zip(a, b):
             assert np.array_equal(x, y)
         # a single query is split over several workgroups in both forms
-        monkeypatch.setenv("VLQ_SCAN_PACKED", "1")
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SCAN_PACKED, 1)
         a = gpu_search(vlq, idx, pr.Y[:1], w1, w2, K)
-        monkeypatch.setenv("VLQ_SCAN_PACKED", "0")
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SCAN_PACKED, 0)
         b = gpu_search(vlq, idx, pr.Y[:1], w1, w2, K)
         for x, y in zip(a, b):
             assert np.array_equal(x, y)
@@ -509,6 +598,8 @@ def test_tiny_config_end_to_end(vlq, oracle_mod):
         # about 3 % of the queries have a mirrored pair of lines straddling the cut at w2 = 32
         tr, soft = check_search(oracle_mod, pr, S, E, lists, pr.Y, 8, 32, 100, got, max_soft=0.06)
         assert (got[1] == tr.out_id[:, :100]).mean() > 0.95
+        from parity import STATS
+        print("parity stats so far:", STATS)
     finally:
         vlq.vlq_index_free(idx)
 

@@ -30,6 +30,7 @@ def _draw(rng, seed):
 def test_random_shapes(vlq, oracle_mod, seed):
     rng = random.Random(seed)
     done = 0
+    skipped = []
     for ci in range(40):
         kw, N, w1, w2, K = _draw(rng, 1000 * seed + ci)
         case = f"case {ci} of seed {seed}: {kw} N={N} w1={w1} w2={w2} K={K}"
@@ -42,7 +43,8 @@ def test_random_shapes(vlq, oracle_mod, seed):
             T.check_graph(oracle_mod, pr, Sg, Eg)
             S, E = oracle_mod.graph(pr.C, pr.n)
             if not np.array_equal(S, Sg):
-                continue  # neighbours tied within rounding are numbered differently: edges not comparable
+                skipped.append(ci)  # neighbours tied within rounding are numbered differently: edges not comparable
+                continue
             if N > 0:
                 enc, _ = T.check_encode(oracle_mod, pr, S, E, pr.X, T.gpu_encode(vlq, idx, pr.X, pr.m), max_soft=0.05)
                 T.load_oracle_index(vlq, idx, enc)
@@ -58,4 +60,5 @@ def test_random_shapes(vlq, oracle_mod, seed):
             raise AssertionError(f"{case}: {e}") from e
         finally:
             vlq.vlq_index_free(idx)
-    assert done >= 30
+    print(f"seed {seed}: {done} shapes compared, {len(skipped)} skipped for a graph tie: {skipped}")
+    assert done >= 30 and done + len(skipped) == 40

@@ -97,7 +97,11 @@ def test_lambda_grid(oracle_mod):
         assert abs(o.lambda_dequant(q) - lam) <= step / 2 + 1e-12
         assert o.lambda_coord(lam) == pytest.approx(lam * 340 + 85, abs=1e-9)
     # another grid with 0 on it
-    assert o.lambda_quant(0.0, -0.5, 0.5) == 128 or o.lambda_dequant(o.lambda_quant(0.0, -1.0, 0.5), -1.0, 0.5) == 0.0
+    # step 1.5 / 255 = 1 / 170: zero is code 170, 0.5 is code 255, -1 is code 0
+    assert o.lambda_quant(0.0, -1.0, 0.5) == 170 and o.lambda_dequant(170, -1.0, 0.5) == 0.0
+    assert o.lambda_quant(0.5, -1.0, 0.5) == 255 and o.lambda_quant(-1.0, -1.0, 0.5) == 0
+    assert o.lambda_dequant(0, -1.0, 0.5) == pytest.approx(-1.0, abs=1e-15)
+    assert o.lambda_coord(0.25, -1.0, 0.5) == pytest.approx(170 + 42.5, abs=1e-9) and o.lambda_quant(0.25, -1.0, 0.5) == 212
 
 
 # ---- graph -----------------------------------------------------------------
@@ -317,6 +321,46 @@ def test_traversal_steps(oracle_mod):
         assert tr.sub[q].tolist() == [l for _, l in mine]
         # candidates = exactly the points stored in the visited lists
         assert tr.ncand[q] == sum(lists.off[l + 1] - lists.off[l] for l in tr.sub[q])
+
+
+@pytest.mark.parametrize("qlam", [(0.0, 1.0), (-0.25, 0.5), (0.3, 0.3)])
+def test_restricted_query_lambda_is_the_distance_to_the_segment(oracle_mod, qlam):
+    """Sec. 3.3.1 variant: with the query's lambda restricted to [lo, hi] the score of a sub-region is
+    the squared distance from the query to that segment of the line.  Checked against a dense sampling
+    of the segment (no a / b / c formulae), and against the unrestricted scores where the foot of the
+    perpendicular already lies inside the range."""
+    pr = problem(N=1200, k=16, n=4, m=8, G=8, nq=12, D=32)
+    S, E = oracle_mod.graph(pr.C, pr.n)
+    Cb, Y = pr.C.astype(np.float64), pr.Y.astype(np.float64)
+    dist = oracle_mod.coarse(pr.C, pr.Y)
+    cells = oracle_mod.select_smallest(dist, 5)
+    free, label0 = oracle_mod.subregion_scores(dist, S, E, cells)
+    got, label = oracle_mod.subregion_scores(dist, S, E, cells, qlam)
+    assert (label == label0).all() and (got >= free - 1e-9 * np.abs(free)).all()
+    lo, hi = qlam
+    ts = np.linspace(lo, hi, 20001)
+    inside = outside = 0
+    for q in range(len(Y)):
+        o = 0
+        for i in cells[q]:
+            for j in range(pr.n):
+                e = Cb[S[i, j]] - Cb[i]
+                z = Y[q] - Cb[i]
+                # ||z - t e||^2 over the sampled segment
+                sampled = ((z @ z) - 2 * ts * (z @ e) + ts * ts * (e @ e)).min()
+                step_err = (e @ e) * ((hi - lo) / 20000) ** 2  # the sampling misses the minimum by at most half a step
+                assert sampled - step_err - 1e-9 * sampled <= got[q, o] <= sampled + 1e-9 * sampled, (q, i, j)
+                lam = (z @ e) / (e @ e)
+                if lo <= lam <= hi:
+                    assert got[q, o] == pytest.approx(free[q, o], rel=1e-12)
+                    inside += 1
+                else:
+                    end = lo if lam < lo else hi
+                    assert got[q, o] == pytest.approx(((z - end * e) ** 2).sum(), rel=1e-9)
+                    assert got[q, o] > free[q, o]
+                    outside += 1
+                o += 1
+    assert outside > 20 and (inside > 20 or lo == hi)
 
 
 def _ivfadc(pr, cell, codes, Y, w, K):

@@ -7,8 +7,8 @@ from functools import lru_cache
 import numpy as np
 import torch
 
+import cpu_codebooks as codebooks
 import datagen
-from datagen import codebooks
 
 
 @dataclass
