@@ -216,6 +216,21 @@ int vlq_search(const vlq_index_t *idx, const float *d_q, int32_t nq, int32_t w1,
                int32_t K, float *d_out_dist, int32_t *d_out_ids, void *stream);
 
 /*
+ * vlq_search for callers that cannot allocate device memory: code running under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results
+ * as vlq_search, but the scratch memory of the call is a fixed array of VLQ_NOALLOC_SCRATCH_BYTES
+ * that is part of the library's code object (one copy per GPU, held until the process ends) and
+ * the call allocates nothing, on the device or through any library.  A request whose scratch need
+ * exceeds the array is rejected with VLQ_EINVAL and a message stating both sizes (roughly
+ * nq * (16 w2 + 4 w1 (n_edges + 3) + 4 D + ...) bytes: about 20 MB for 1 024 queries at w1 = 64,
+ * w2 = 512, n_edges = 32).  All calls on one GPU share that array, whatever the index: calls that
+ * overlap on one GPU (two streams, two threads) race; order them.  Stage times are not recorded.
+ */
+#define VLQ_NOALLOC_SCRATCH_BYTES (32u << 20)
+int vlq_search_noalloc(const vlq_index_t *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2,
+                       int32_t K, float *d_out_dist, int32_t *d_out_ids, void *stream);
+
+/*
  * vlq_search that also returns the traversal (any extra pointer may be NULL):
  *   d_cells [nq x w1] / d_cell_dist [nq x w1]: probed cells, ascending (distance, index);
  *   d_sub [nq x w2] / d_sub_score [nq x w2]: visited lists (label i*n+j), ascending (score, label).

@@ -59,6 +59,7 @@ def lib():
             "vlq_index_set_option": [vp, C.c_int, C.c_int],
             "vlq_index_set_query_lambda_range": [vp, C.c_float, C.c_float],
             "vlq_search": [vp, vp, i32, i32, i32, i32, vp, vp, vp],
+            "vlq_search_noalloc": [vp, vp, i32, i32, i32, i32, vp, vp, vp],
             "vlq_search_debug": [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp],
             "vlq_index_get_graph": [vp, vp, vp, vp],
             "vlq_index_get_lists": [vp, vp, vp, vp, vp, vp],
@@ -178,6 +179,11 @@ def vlq_index_set_query_lambda_range(idx, lo, hi):
 def vlq_search(idx, d_q, nq, w1, w2, K, d_out_dist, d_out_ids, stream=None):
     _chk(lib().vlq_search(idx, _ptr(d_q, torch.float32), int(nq), int(w1), int(w2), int(K),
                           _ptr(d_out_dist, torch.float32), _ptr(d_out_ids, torch.int32), _stream(stream)))
+
+
+def vlq_search_noalloc(idx, d_q, nq, w1, w2, K, d_out_dist, d_out_ids, stream=None):
+    _chk(lib().vlq_search_noalloc(idx, _ptr(d_q, torch.float32), int(nq), int(w1), int(w2), int(K),
+                                  _ptr(d_out_dist, torch.float32), _ptr(d_out_ids, torch.int32), _stream(stream)))
 
 
 def vlq_search_debug(idx, d_q, nq, w1, w2, K, d_out_dist, d_out_ids, d_cells=None, d_cell_dist=None, d_sub=None,

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -37,6 +38,35 @@ static int fail(int code, const char *fmt, ...)
 
 extern "C" const char *vlq_last_error(void) { return g_err; }
 extern "C" int vlq_version(void) { return VLQ_VERSION; }
+
+// ---------------------------------------------------------------------------
+// static scratch of the entry point that allocates nothing
+// ---------------------------------------------------------------------------
+// The scratch memory of vlq_search_noalloc: one array per GPU, part of the loaded code object and
+// held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address it yields, per device, is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[VLQ_NOALLOC_SCRATCH_BYTES];
+
+#define VLQ_MAX_DEVICES 64
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[VLQ_MAX_DEVICES] = {};
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= VLQ_MAX_DEVICES) return fail(VLQ_EINVAL, "device ordinal %d outside [0, %d)", dev, VLQ_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(VLQ_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return VLQ_OK;
+}
 
 // ---------------------------------------------------------------------------
 // index object
@@ -119,9 +149,9 @@ struct StageTimer {
     hipStream_t st;
     int stage;
     hipEvent_t t0 = nullptr;
-    StageTimer(vlq_index *i, hipStream_t s, int g) : idx(i), st(s), stage(g)
+    StageTimer(vlq_index *i, hipStream_t s, int g, bool on = true) : idx(i), st(s), stage(g)
     {
-        if (idx->prof && hipEventCreate(&t0) == hipSuccess) (void)hipEventRecord(t0, st);
+        if (on && idx->prof && hipEventCreate(&t0) == hipSuccess) (void)hipEventRecord(t0, st);
     }
     ~StageTimer()
     {
@@ -225,6 +255,12 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
     }
     const int k = params->nlist, D = params->d, n = params->n_edges, m = params->m;
     auto body = [&]() -> int {
+        {
+            // set-up: the address of this device's static scratch array (vlq_search_noalloc)
+            void *sp = nullptr;
+            int r0 = static_scratch(&sp);
+            if (r0) return r0;
+        }
         HIPCHK(hipMalloc(&idx->C, (size_t)k * D * 4));
         HIPCHK(hipMalloc(&idx->cn, (size_t)k * 4));
         HIPCHK(hipMalloc(&idx->Cc, (size_t)k * D * 4));
@@ -773,6 +809,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
 
     // cells from two sweeps of the bf16 product where the shape allows it (VLQ_OPT_COARSE_FP32 asks
     // for the fp32 distance matrix instead)
+    const bool timed = !fixed; // (recording stage times creates events)
     int csplit = 0, ccap = 0;
     const bool bf16 = idx->Cimg && !idx->opt[VLQ_OPT_COARSE_FP32] && cells_bf16_plan(nq, k, D, w1, &csplit, &ccap);
     int64_t TQ = ((int64_t)512 << 20) / ((int64_t)4 * k);
@@ -837,7 +874,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     }
     if (bf16) {
         {
-            StageTimer t(idx, st, VLQ_STAGE_COARSE);
+            StageTimer t(idx, st, VLQ_STAGE_COARSE, timed);
             launch_split_bf16(d_q, nq, D, idx->mu_c, qimg, qflag, st);
             LAUNCHCHK();
             HIPCHK((hipError_t)launch_cells_bf16_coarse(qimg, qflag, nq, idx->Cimg, k, D, qn, idx->cn, w1, csplit, ccap,
@@ -845,7 +882,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
         }
         LAUNCHCHK();
         {
-            StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS);
+            StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS, timed);
             launch_cells_bf16_exact(d_q, nq, D, idx->C, k, w1, ccap, cws, csplit, cells, cell_dist,
                                     by_cell ? pw.cnt : nullptr, by_cell ? pw.rank : nullptr, st);
             pairs_counted = by_cell;
@@ -855,13 +892,13 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
         for (int64_t q0 = 0; q0 < nq; q0 += TQ) {
             const int rows = (int)(nq - q0 < TQ ? nq - q0 : TQ);
             {
-                StageTimer t(idx, st, VLQ_STAGE_COARSE);
+                StageTimer t(idx, st, VLQ_STAGE_COARSE, timed);
                 launch_center_rows(d_q + q0 * D, rows, D, idx->mu_c, qc, st);
                 launch_coarse_gemm_full(qc, rows, idx->Cc, k, D, qn + q0, idx->cn, dist, k, st);
             }
             LAUNCHCHK();
             {
-                StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS);
+                StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS, timed);
                 launch_select_cells(dist, k, rows, k, d_q + q0 * D, D, qn + q0, idx->C, idx->cn, w1, -1,
                                     cells + q0 * w1, cell_dist + q0 * w1, st);
             }
@@ -903,7 +940,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     a.out_dist = d_out_dist;
     a.out_ids = d_out_ids;
     {
-        StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS);
+        StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS, timed);
         // the streaming scan takes the visited sub-regions from desc alone, in any order
         const bool stream = scan_will_stream(a);
         launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, k, cells, cell_dist, w1, w2, idx->qlam_lo, idx->qlam_hi,
@@ -912,12 +949,12 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     }
     LAUNCHCHK();
     {
-        StageTimer t(idx, st, VLQ_STAGE_SCAN);
+        StageTimer t(idx, st, VLQ_STAGE_SCAN, timed);
         launch_scan(a, st);
     }
     LAUNCHCHK();
     if (nsplit > 1) {
-        StageTimer t(idx, st, VLQ_STAGE_MERGE);
+        StageTimer t(idx, st, VLQ_STAGE_MERGE, timed);
         launch_merge(partial, nq, nsplit, K, d_out_dist, d_out_ids, st);
     }
     LAUNCHCHK();
@@ -962,6 +999,19 @@ extern "C" int vlq_search_debug(const vlq_index_t *idx, const float *d_q, int32_
 {
     return search_tiled(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, d_cells, d_cell_dist,
                         d_sub, d_sub_score, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------
+// search without allocation
+// ---------------------------------------------------------------------------
+extern "C" int vlq_search_noalloc(const vlq_index_t *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2,
+                                  int32_t K, float *d_out_dist, int32_t *d_out_ids, void *stream)
+{
+    void *ptr = nullptr;
+    int rc = static_scratch(&ptr);
+    if (rc) return rc;
+    return search_impl(const_cast<vlq_index *>(idx), d_q, nq, w1, w2, K, d_out_dist, d_out_ids, nullptr, nullptr,
+                       nullptr, nullptr, (hipStream_t)stream, ptr, (size_t)VLQ_NOALLOC_SCRATCH_BYTES);
 }
 
 // ---------------------------------------------------------------------------
