@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 
 def log(*a):
@@ -28,17 +29,20 @@ def log(*a):
 
 
 def scan_bytes(vlq, wl, w1, w2, torch):
-    """Algorithmic bytes of the list scan for one batch: every point of every
-    visited list once (m code bytes + 1 lambda byte + 4 bytes of the stored
-    query-independent term) plus one 16-byte descriptor per visited list and
-    the K ids looked up for the survivors."""
+    """Algorithmic bytes of the list scan for one batch: every point of every visited list once
+    (m code bytes + 1 lambda byte + 4 bytes of the stored query-independent term) plus the two
+    list offsets (8 bytes) of every visited list.  Also returns the traversal and the results of
+    that search (device tensors) for the parity sample."""
     cfg = wl.cfg
     nq = wl.Y.shape[0]
     dev = wl.Y.device
     od = torch.empty(nq, cfg.K, device=dev)
     oi = torch.empty(nq, cfg.K, dtype=torch.int32, device=dev)
+    cells = torch.empty(nq, w1, dtype=torch.int32, device=dev)
+    cd = torch.empty(nq, w1, device=dev)
     sub = torch.empty(nq, w2, dtype=torch.int32, device=dev)
-    vlq.vlq_search_debug(wl.idx, wl.Y, nq, w1, w2, cfg.K, od, oi, None, None, sub, None)
+    ss = torch.empty(nq, w2, device=dev)
+    vlq.vlq_search_debug(wl.idx, wl.Y, nq, w1, w2, cfg.K, od, oi, cells, cd, sub, ss)
     off = torch.empty(cfg.k * cfg.n + 1, dtype=torch.int64, device=dev)
     vlq.vlq_index_get_lists(wl.idx, off, None, None, None)
     torch.cuda.synchronize()
@@ -46,7 +50,59 @@ def scan_bytes(vlq, wl, w1, w2, torch):
     lens = (off[s + 1] - off[s]) * (sub >= 0)
     points = int(lens.sum())
     visited = int((sub >= 0).sum())
-    return points * (cfg.m + 5) + visited * 16 + nq * cfg.K * 4, points, oi
+    return points * (cfg.m + 5) + visited * 8, points, (od, oi, cells, cd, sub, ss)
+
+
+def parity_on_sample(vlq, wl, w1, w2, dbg, torch, nsample=100):
+    """The tests' protocol on the first queries of the timed batch, at full size: cells, sub-regions
+    and scores against the oracle's traversal, and the whole top-K against the oracle's scan of the
+    lists the GPU visited (copied out of the library).  Returns the summary and the list of
+    violations (empty when the sample is inside the parity bands)."""
+    import numpy as np
+
+    import oracle
+    from datagen import workloads
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import DTOL, check_selection, check_topk, reconciled_graph, term_scale
+
+    cfg = wl.cfg
+    ns = min(nsample, wl.Y.shape[0])
+    od, oi, cells, cd, sub, ss = (t[:ns] for t in dbg)
+    lists = oracle.Lists(*workloads.visited_lists(vlq, wl.idx, cfg, sub))
+    od, oi, cells, cd, sub, ss = (t.cpu().numpy() for t in (od, oi, cells, cd, sub, ss))
+    Cb, P, Y = wl.C.cpu().numpy(), wl.P.cpu().numpy(), wl.Y[:ns].cpu().numpy()
+    dist = oracle.coarse(Cb, Y)
+    ocells = oracle.select_smallest(dist, w1)
+    Sd = torch.empty(cfg.k, cfg.n, dtype=torch.int32, device=wl.Y.device)
+    vlq.vlq_index_get_graph(wl.idx, Sd, None)
+    torch.cuda.synchronize()
+    S, E, _ = reconciled_graph(oracle, Cb, cfg.n, np.concatenate([ocells.ravel(), cells.ravel(), (sub[sub >= 0] // cfg.n).ravel()]),
+                               Sd.cpu().numpy())
+    ids_exact = tie = 0
+    max_rel = 0.0
+    bad = []
+    for q in range(ns):
+        try:
+            same_c = check_selection(cells[q], dict(enumerate(dist[q])), w1, what=f"query {q} cells")
+            assert np.allclose(cd[q], dist[q][cells[q]], rtol=DTOL), f"query {q} cell distances"
+            score, label = (x[0] for x in oracle.subregion_scores(dist[q:q + 1], S, E, cells[q:q + 1]))
+            val = {int(l): float(v) for l, v in zip(label, score)}
+            a_max = dist[q][cells[q]].max()
+            same_s = check_selection(sub[q], val, w2, scale=a_max, what=f"query {q} sub-regions")
+            assert np.allclose(ss[q], [val[int(l)] for l in sub[q]], rtol=0, atol=DTOL * a_max), f"query {q} scores"
+            o_d, o_i, _ = (x[0] for x in oracle.scan(Cb, S, P, lists, Y[q:q + 1], sub[q:q + 1], cfg.K + 16))
+            same_k = check_topk(od[q], oi[q], o_d, o_i, cfg.K, what=f"query {q}", scale=term_scale(a_max, Y[q], Cb, P), m=cfg.m)
+            o_map = {int(i): float(d) for d, i in zip(o_d, o_i)}
+            max_rel = max(max_rel, max(abs(float(g) - o_map[int(i)]) / max(o_map[int(i)], 1e-30) for g, i in zip(od[q], oi[q]) if i >= 0))
+            if same_c and same_s and same_k and (oi[q] == o_i[:cfg.K]).all():
+                ids_exact += 1
+            else:
+                tie += 1
+        except AssertionError as e:
+            bad.append(str(e)[:200])
+    return {"queries": ns, "ids_exact": ids_exact, "in_tie_band": tie, "violations": len(bad),
+            "max_rel_dist_err": max_rel}, bad
 
 
 def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
@@ -116,15 +172,16 @@ def cpu_baseline(vlq, wl, w1, w2, torch, target_s=15.0):
 
 def measured_traffic(workload):
     """HBM bytes per launch of the scan kernel from the committed counter summary of this workload
-    (two rocprofv3 --pmc runs of this script, scaled by the copy yardstick); None if there is none."""
-    path = os.path.join(ROOT, "profiles", f"k_scan_stream_{workload}_hbm_traffic.md")
+    (two rocprofv3 --pmc runs of this script, scaled by the copy yardstick), and the name of that
+    file; (None, None) if there is none.  Not measured in this run: counters need the profiler."""
+    name = f"profiles/k_scan_stream_{workload}_hbm_traffic.md"
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, name)):
             if line.startswith("traffic_bytes_per_launch:"):
-                return int(float(line.split(":", 1)[1]))
+                return int(float(line.split(":", 1)[1])), name
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def main():
@@ -136,7 +193,8 @@ def main():
     ap.add_argument("--w1", type=int, default=0, help="probed cells (default: the configuration's operating point)")
     ap.add_argument("--points", type=int, default=0, help="build only the first POINTS vectors (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sweep", action="store_true", help="also time the other w1 values of the configuration")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also the alpha, batch-size and K sweeps of the configuration (the w1 sweep always runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain streaming kernel of known size (torch.frac over 2^28 floats: 1 GiB read, "
                          "1 GiB written), the yardstick for the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -180,11 +238,15 @@ def main():
 
     w1 = args.w1 or cfg.w1[-1]
     dt, prof, rec, w2 = timed(w1, args.steps, args.warmup)
-    nbytes, points, oi_dbg = scan_bytes(vlq, wl, w1, w2, torch)
+    nbytes, points, dbg = scan_bytes(vlq, wl, w1, w2, torch)
     scan_ms, scan_launches = prof["scan"]
     scan_avg_s = scan_ms / 1e3 / max(scan_launches, 1)
     achieved = nbytes / scan_avg_s / 1e9
     stage_ms = {s: round(v[0] / args.steps, 4) for s, v in prof.items()}
+    traffic, traffic_source = measured_traffic(cfg.name)
+    # coarse distances (Alg. 3, first loop): 2 nq k D flop of the contraction per step, against the bf16 matrix peak
+    coarse_flop = 2.0 * nq * cfg.k * cfg.D
+    coarse_s = prof["coarse"][0] / 1e3 / args.steps
     result = {
         "metric": "queries/sec at Recall@10 (1B pts, 1 GPU); ADC-scan HBM GB/s vs peak",
         "value": nq * args.steps / dt,
@@ -196,33 +258,43 @@ def main():
         "config": {"workload": cfg.name, "N": vlq.vlq_index_ntotal(wl.idx), "D": cfg.D, "centroids": cfg.k,
                    "edges": cfg.n, "code_bytes": cfg.m, "queries": nq, "w1": w1, "w2": w2, "K": K,
                    "recall": rec, "points_scanned_per_query": points / nq,
-                   "stage_ms_per_step": stage_ms, "build_s": wl.timings},
+                   "stage_ms_per_step": stage_ms, "build_s": wl.timings,
+                   "coarse_mfma": {"flop_per_step": coarse_flop, "ms_per_step": coarse_s * 1e3,
+                                   "achieved_tflops": coarse_flop / max(coarse_s, 1e-12) / 1e12,
+                                   "peak_tflops": BF16_PEAK_TFLOPS,
+                                   "frac": coarse_flop / max(coarse_s, 1e-12) / 1e12 / BF16_PEAK_TFLOPS,
+                                   "note": "2 nq k D flop of Alg. 3's first loop over the time of both sweeps of the "
+                                           "split-bf16 product (which issue 2-3 bf16 products per fp32 product)"}},
         "roofline": {"bound": "hbm", "kernel": "k_scan_stream", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": scan_avg_s * 1e3},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": scan_avg_s * 1e3,
+                     "bytes_note": "(m + 5) bytes per scanned point + 8 bytes of list offsets per visited list; the kernel "
+                                   "itself reads a 16-byte descriptor per list (offset, length and the two coarse "
+                                   "distances of Eq. 17), not counted beyond the 8"},
     }
-    result["roofline"]["traffic"] = measured_traffic(cfg.name)
     if args.copy_calibration:
         src = torch.rand(1 << 28, device=dev)
         dst = torch.empty_like(src)
         torch.frac(src, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    # the (w1, queries/s, Recall@10) curve of the configuration; the headline is its last point
+    sweep = []
+    for w in cfg.w1:
+        reps = max(3, args.steps // 2)
+        d2, p2, r2, w22 = timed(w, reps, 1)
+        pts = scan_bytes(vlq, wl, w, w22, torch)[1]
+        sweep.append({"w1": w, "w2": w22, "queries_per_s": nq * reps / d2, "ms_per_step": d2 / reps * 1e3,
+                      "points_scanned_per_query": pts / nq, **r2})
+    result["config"]["sweep"] = sweep
+    # the cheapest probe whose Recall@10 is within 5 % of the headline operating point's
+    ref = rec["R@10"]
+    ok = [e for e in sweep if e["R@10"] >= 0.95 * ref]
+    if ok:
+        best = max(ok, key=lambda e: e["queries_per_s"])
+        result["config"]["cheapest_within_5pct_of_R@10"] = {"w1": best["w1"], "w2": best["w2"],
+                                                             "queries_per_s": best["queries_per_s"], "R@10": best["R@10"]}
     if args.sweep:
-        sweep = []
-        for w in cfg.w1:
-            d2, p2, r2, w22 = timed(w, max(2, args.steps // 2), 1)
-            pts = scan_bytes(vlq, wl, w, w22, torch)[1]
-            sweep.append({"w1": w, "w2": w22, "queries_per_s": nq * max(2, args.steps // 2) / d2,
-                          "points_scanned_per_query": pts / nq, **r2})
-        result["config"]["sweep"] = sweep
-        # the cheapest probe whose Recall@10 is within 5 % of the headline operating point's
-        ref = rec["R@10"]
-        ok = [e for e in sweep if e["R@10"] >= 0.95 * ref]
-        if ok:
-            best = max(ok, key=lambda e: e["queries_per_s"])
-            result["config"]["cheapest_within_5pct_of_R@10"] = {"w1": best["w1"], "w2": best["w2"],
-                                                                 "queries_per_s": best["queries_per_s"], "R@10": best["R@10"]}
         # the share alpha of the w1 * n sub-regions that is scanned (Sec. 5, parameter study), at the headline w1
         if not cfg.w2_fixed and cfg.n > 1:
             asw = []
@@ -251,13 +323,18 @@ def main():
                            f"R@{Kx}": datagen.recall_at(oib, wl.gt[:nb], Kx)})
         if bs:
             result["config"]["batch_sweep"] = bs
+    violations = []
     if not args.no_cpu_baseline:
+        summary, violations = parity_on_sample(vlq, wl, w1, w2, dbg, torch)
+        result["config"]["parity_on_sample"] = summary
         base, o_ids, ns = cpu_baseline(vlq, wl, w1, w2, torch)
         result["cpu_baseline"] = base
-        agree = float((oi_dbg[:ns].cpu().numpy() == o_ids).mean())
-        result["config"]["oracle_id_agreement_on_sample"] = agree
     print(json.dumps(result), flush=True)
     vlq.vlq_index_free(wl.idx)
+    if violations:
+        for v in violations[:10]:
+            log("bench.py: parity violation on the sample:", v)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -80,9 +80,12 @@ def chunks(cfg: Config, n_points: int | None = None):
         c += 1
 
 
-def materialise(vlq, cfg: Config, device="cuda:0", n_points: int | None = None, log=print, iters: int = 10) -> Workload:
+def materialise(vlq, cfg: Config, device="cuda:0", n_points: int | None = None, log=print, iters: int = 10,
+                gt_rows: int | None = None) -> Workload:
     """Train codebooks, build the index chunk by chunk (vectors are generated,
-    encoded, compared against the queries for ground truth, and dropped)."""
+    encoded, compared against the queries for ground truth, and dropped).
+    gt_rows: exact nearest neighbours only for the first gt_rows queries (the rest get -1);
+    the brute force over 10^9 points is the longest part of a build."""
     t0 = time.time()
     mix = Mixture(cfg.kind, cfg.G, seed=MASTER_SEED)
     T = mix.train_sample(cfg.ntrain, device)
@@ -99,9 +102,11 @@ def materialise(vlq, cfg: Config, device="cuda:0", n_points: int | None = None, 
     N = cfg.N if n_points is None else n_points
     vlq.vlq_index_reserve(idx, N)
     t_graph = time.time() - t0
+    ng = cfg.nq if gt_rows is None else min(gt_rows, cfg.nq)
     best_d = torch.full((cfg.nq,), float("inf"), device=device)
     best_i = torch.full((cfg.nq,), -1, dtype=torch.int64, device=device)
-    yn = (Y.double() ** 2).sum(1).float()
+    Yg = Y[:ng]
+    yn = (Yg.double() ** 2).sum(1).float()
     t_add = t_gt = 0.0
     done = 0
     for c, cnt in chunks(cfg, N):
@@ -114,11 +119,11 @@ def materialise(vlq, cfg: Config, device="cuda:0", n_points: int | None = None, 
         t1 = time.time()
         for s in range(0, cnt, 1 << 18):
             xs = X[s: s + (1 << 18)]
-            d = (yn[:, None] + (xs * xs).sum(1)[None, :]) - 2.0 * (Y @ xs.T)
+            d = (yn[:, None] + (xs * xs).sum(1)[None, :]) - 2.0 * (Yg @ xs.T)
             dd, ii = d.min(1)
-            upd = dd < best_d
-            best_d = torch.where(upd, dd, best_d)
-            best_i = torch.where(upd, ii + done + s, best_i)
+            upd = dd < best_d[:ng]
+            best_d[:ng] = torch.where(upd, dd, best_d[:ng])
+            best_i[:ng] = torch.where(upd, ii + done + s, best_i[:ng])
         torch.cuda.synchronize()
         t_gt += time.time() - t1
         done += cnt
@@ -132,3 +137,30 @@ def materialise(vlq, cfg: Config, device="cuda:0", n_points: int | None = None, 
     log(f"[{cfg.name}] index built: {N} vectors, encode {t_add:.1f} s, finalize {t_fin:.1f} s")
     return Workload(cfg, mix, C, P, Y, idx, best_i,
                     dict(train_s=t_train, graph_s=t_graph, encode_s=t_add, ground_truth_s=t_gt, finalize_s=t_fin))
+
+
+def visited_lists(vlq, idx, cfg: Config, sub: torch.Tensor):
+    """The stored lists named in `sub` (any shape, labels i * n + j, -1 ignored), copied out of the
+    library through vlq_index_get_lists and compacted: returns host arrays (off [k n + 1] int64 with
+    zero length for every other list, ids, codes, lambda bytes) laid out like the library's own.
+    Only marshalling: the oracle scans these lists on the host."""
+    dev = sub.device
+    nl = cfg.k * cfg.n
+    N = vlq.vlq_index_ntotal(idx)
+    off = torch.empty(nl + 1, dtype=torch.int64, device=dev)
+    ids = torch.empty(N, dtype=torch.int32, device=dev)
+    codes = torch.empty(N, cfg.m, dtype=torch.uint8, device=dev)
+    lam = torch.empty(N, dtype=torch.uint8, device=dev)
+    vlq.vlq_index_get_lists(idx, off, ids, codes, lam)
+    torch.cuda.synchronize()
+    labels = torch.unique(sub[sub >= 0].long())
+    lens = off[labels + 1] - off[labels]
+    total = int(lens.sum())
+    first = torch.cumsum(lens, 0) - lens  # where each list starts in the compact arrays
+    pos = torch.repeat_interleave(off[labels] - first, lens) + torch.arange(total, device=dev)
+    off_c = torch.zeros(nl + 1, dtype=torch.int64, device=dev)
+    off_c[labels + 1] = lens
+    off_c = torch.cumsum(off_c, 0)
+    out = (off_c.cpu().numpy(), ids[pos].cpu().numpy(), codes[pos].cpu().numpy(), lam[pos].cpu().numpy())
+    del ids, codes, lam
+    return out

@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
     if (tid < GT) {
         rowmin[tid] = KEY_MAX;
         rowcnt[tid] = 1; // slot 0 is the minimum itself
-        rowovf[tid] = 0;
+        rowovf[tid] = -1;
 #pragma unroll
         for (int s = 0; s < VLQ_NN_CANDS; ++s) rowcand[tid][s] = KEY_MAX;
     }
@@ -282,7 +282,11 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
             uint64_t ks[2] = {b1[i][r], b2[i][r]};
             // a lane keeps two keys per row: when its second one lies inside the band a third may
             // have been dropped, so the row is handed on as incomplete
-            if (ks[1] != KEY_MAX && __uint_as_float((uint32_t)(ks[1] >> 32)) <= band) rowovf[rl] = 1;
+            if (ks[1] != KEY_MAX && __uint_as_float((uint32_t)(ks[1] >> 32)) <= band) {
+                const int slot = (wn >> 6) * 32 + (lane & 31);
+                const int old = atomicCAS(&rowovf[rl], -1, slot);
+                if (old != -1 && old != slot) rowovf[rl] = 64; // several slots
+            }
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 if (ks[s] == KEY_MAX || ks[s] == mn) continue;
@@ -295,10 +299,12 @@ __global__ __launch_bounds__(256) void k_coarse_gemm_nn(const float *__restrict_
     __syncthreads();
     if (tid < GT && m0 + tid < M) {
         uint64_t *dst = cand + ((m0 + tid) * nsplit + split) * VLQ_NN_CANDS;
-        const bool ovf = rowovf[tid] != 0 || rowcnt[tid] > VLQ_NN_CANDS;
-        dst[0] = ovf ? VLQ_NN_OVERFLOW : rowmin[tid];
+        const int cnt = rowcnt[tid], sl = rowovf[tid];
+        const bool all = cnt > VLQ_NN_CANDS || sl == 64 || (sl >= 0 && cnt >= VLQ_NN_CANDS);
+        dst[0] = all ? (((uint64_t)VLQ_NN_MARK << 32) | VLQ_NN_ALL) : rowmin[tid];
 #pragma unroll
-        for (int s = 1; s < VLQ_NN_CANDS; ++s) dst[s] = rowcand[tid][s];
+        for (int s = 1; s < VLQ_NN_CANDS; ++s)
+            dst[s] = !all && sl >= 0 && s == cnt ? (((uint64_t)VLQ_NN_MARK << 32) | (uint32_t)sl) : rowcand[tid][s];
     }
 }
 

@@ -29,7 +29,7 @@
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
-#define BT 128          // rows per block
+#define BT 128          // rows per block (= VLQ_NN_TILE columns per tile)
 #define BSTEP 16        // contraction indices per step
 #define PAGE 256        // 16-byte chunks per page
 #define BF16_MAX_D 128  // A block resident in LDS: D / 16 steps x 2 pages x 4 KB
@@ -368,7 +368,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     if (tid < BT) {
         rowmin[tid] = 0xFFFFFFFFu;
         rowcnt[tid] = 0;
-        rowovf[tid] = 0;
+        rowovf[tid] = -1;
 #pragma unroll
         for (int s = 0; s < VLQ_NN_CANDS; ++s) rowcand[tid * VLQ_NN_CANDS + s] = KEY_MAX;
     }
@@ -393,7 +393,11 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             const float ks[2] = {b1[i][r], b2[MODE == MODE_NN ? i : 0][r]};
             // a lane keeps two keys per row: when its second one lies inside the band a third may
             // have been dropped, so the row is handed on as incomplete
-            if (ks[1] < BF16_NO_KEY && __uint_as_float(__float_as_uint(ks[1]) & keep) <= band) rowovf[rl] = 1;
+            if (ks[1] < BF16_NO_KEY && __uint_as_float(__float_as_uint(ks[1]) & keep) <= band) {
+                const int slot = (wn >> 6) * 32 + (lane & 31);
+                const int old = atomicCAS(&rowovf[rl], -1, slot);
+                if (old != -1 && old != slot) rowovf[rl] = 64; // several slots
+            }
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 if (!(ks[s] < BF16_NO_KEY)) continue;
@@ -413,9 +417,15 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     __syncthreads();
     if (tid < BT && m0 + tid < a.M) {
         uint64_t *dst = a.cand + ((m0 + tid) * a.nsplit + split) * VLQ_NN_CANDS;
-        const bool ovf = rowovf[tid] != 0 || rowcnt[tid] > VLQ_NN_CANDS;
+        const int cnt = rowcnt[tid], sl = rowovf[tid];
+        const bool all = cnt > VLQ_NN_CANDS || sl == 64 || (sl >= 0 && cnt >= VLQ_NN_CANDS);
 #pragma unroll
-        for (int s = 0; s < VLQ_NN_CANDS; ++s) dst[s] = s == 0 && ovf ? VLQ_NN_OVERFLOW : rowcand[tid * VLQ_NN_CANDS + s];
+        for (int s = 0; s < VLQ_NN_CANDS; ++s) {
+            uint64_t key = rowcand[tid * VLQ_NN_CANDS + s];
+            if (all && s == 0) key = ((uint64_t)VLQ_NN_MARK << 32) | VLQ_NN_ALL;
+            if (!all && sl >= 0 && s == cnt) key = ((uint64_t)VLQ_NN_MARK << 32) | (uint32_t)sl;
+            dst[s] = key;
+        }
     }
 }
 

@@ -168,10 +168,16 @@ void launch_coarse_gemm_full(const float *A, int M, const float *B, int N, int D
 // up to VLQ_NN_CANDS keys (distance bits << 32 | column) per column split that lie
 // within the rounding band of the row minimum.  cand [M x nsplit x VLQ_NN_CANDS].
 #define VLQ_NN_CANDS 8
-// Written in place of the first key of a (row, split) whose shortlist may be incomplete (more
-// in-band columns than slots, or a lane that may have dropped a third one): the consumer then
-// ranks that row exactly over all columns.
-#define VLQ_NN_OVERFLOW 0xFFFFFFFFFFFFFFFEull
+// A lane of the product kernels keeps the two smallest keys per row among the columns it sees (its
+// "slot": columns (slot >> 5) * 64 + 32 j + (slot & 31), j = 0, 1, of every 128-column tile of the
+// split).  When its second key lies inside the band a third one may have been dropped: the
+// (row, split) then carries, after its kept keys, a marker key whose high word is VLQ_NN_MARK and
+// whose low word names the slot, and the consumer re-evaluates that slot's columns exactly.  A
+// low word of VLQ_NN_ALL (more in-band columns than room, or several such slots) asks for an
+// exact ranking over all columns.
+#define VLQ_NN_MARK 0xFFFFFFFEu
+#define VLQ_NN_ALL 0xFFFFFFFFu
+#define VLQ_NN_TILE 128
 // Width of the band around the smallest distance d of a row a:
 // band_norm * (3 ||a||^2 + 2 d) + band_dist * (||a||^2 + d); the fp32 product has band_dist = 0.
 // fp32 product: each value ||a||^2 + ||b||^2 - 2 <a, b> is off by at most

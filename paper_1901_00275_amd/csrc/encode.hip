@@ -5,39 +5,84 @@
 #define ENC_NT 256
 #define ENC_PB_MAX 32
 
-// Nearest row of C [k x D] to x by direct sums of squared differences, smallest (distance, index):
+// ||x - row||^2 by each group of 16 lanes (l16 = lane % 16): four components per lane and step, then
+// the adder's lane-crossing sum.  Every exact evaluation of a centroid distance in this file goes
+// through it, so that coinciding centroids get bit-identical values and ties fall to the smaller index.
+__device__ __forceinline__ float sqdist16(const float *x, const float *__restrict__ row, int D, int l16, bool vec)
+{
+    float acc = 0.f;
+    if (vec) {
+        for (int d = l16 * 4; d < D; d += 64) {
+            const f32x4 cv = *(const f32x4 *)(row + d);
+            const float t0 = x[d] - cv.x, t1 = x[d + 1] - cv.y, t2 = x[d + 2] - cv.z, t3 = x[d + 3] - cv.w;
+            acc = fmaf(t0, t0, acc);
+            acc = fmaf(t1, t1, acc);
+            acc = fmaf(t2, t2, acc);
+            acc = fmaf(t3, t3, acc);
+        }
+    } else {
+        for (int d = l16; d < D; d += 16) {
+            const float t = x[d] - row[d];
+            acc = fmaf(t, t, acc);
+        }
+    }
+    return row16_sum(acc);
+}
+
+// Nearest row of C [k x D] to x by direct sums of squared differences, smallest (distance, index),
+// over a set of `count` columns given by col_of(c), c = 0 .. count - 1 (columns >= k are skipped):
 // 16 lanes per row, four rows per pass.  Serves the rows whose shortlist came back incomplete.
-__device__ __forceinline__ uint64_t exact_nearest(const float *x, const float *__restrict__ C, int k, int D, int lane)
+template <typename ColOf>
+__device__ __forceinline__ uint64_t exact_nearest_of(const float *x, const float *__restrict__ C, int k, int D, int lane,
+                                                     int count, ColOf col_of)
 {
     const int sub = lane >> 4, l16 = lane & 15;
     const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
     uint64_t best = KEY_MAX;
-    for (int i0 = 0; i0 < k; i0 += 4) {
-        const int i = i0 + sub;
-        const float *row = C + (int64_t)min(i, k - 1) * D;
-        float acc = 0.f;
-        if (vec) {
-            for (int d = l16 * 4; d < D; d += 64) {
-                const f32x4 cv = *(const f32x4 *)(row + d);
-                const float t0 = x[d] - cv.x, t1 = x[d + 1] - cv.y, t2 = x[d + 2] - cv.z, t3 = x[d + 3] - cv.w;
-                acc = fmaf(t0, t0, acc);
-                acc = fmaf(t1, t1, acc);
-                acc = fmaf(t2, t2, acc);
-                acc = fmaf(t3, t3, acc);
-            }
-        } else {
-            for (int d = l16; d < D; d += 16) {
-                const float t = x[d] - row[d];
-                acc = fmaf(t, t, acc);
-            }
-        }
-        acc = row16_sum(acc);
+    for (int c0 = 0; c0 < count; c0 += 4) {
+        const int c = c0 + sub;
+        const int i = c < count ? col_of(c) : k;
+        const float acc = sqdist16(x, C + (int64_t)min(i, k - 1) * D, D, l16, vec);
         if (i < k) {
             const uint64_t key = make_key(acc, (uint32_t)i);
             best = key < best ? key : best;
         }
     }
     return wave_min_u64(best);
+}
+
+// The marker keys of a vector's shortlist (see VLQ_NN_MARK): every marked lane slot is searched
+// exactly, a VLQ_NN_ALL marker asks for all columns.  cd [nc] are the keys of all splits, uniform
+// over the wave.  Returns the best key found (KEY_MAX if there was no marker).
+__device__ __forceinline__ uint64_t resolve_markers(const uint64_t *__restrict__ cd, int nc, int nsplit, const float *x,
+                                                    const float *__restrict__ C, int k, int D, int lane)
+{
+    uint64_t best = KEY_MAX;
+    const int ntiles = (k + VLQ_NN_TILE - 1) / VLQ_NN_TILE;
+    const int per = (ntiles + nsplit - 1) / nsplit;
+    for (int c0 = 0; c0 < nc; c0 += 64) {
+        const uint64_t key = c0 + lane < nc ? cd[c0 + lane] : KEY_MAX;
+        uint64_t mask = __ballot((uint32_t)(key >> 32) == VLQ_NN_MARK);
+        while (mask) {
+            const int src = __ffsll((unsigned long long)mask) - 1;
+            mask &= mask - 1;
+            const uint32_t slot = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, src);
+            uint64_t got;
+            if (slot == VLQ_NN_ALL) {
+                got = exact_nearest_of(x, C, k, D, lane, k, [](int c) { return c; });
+                mask = 0;
+                c0 = nc; // nothing can add to a ranking over all columns
+            } else {
+                const int split = (c0 + src) / VLQ_NN_CANDS;
+                const int t0 = split * per, t1 = min(ntiles, t0 + per);
+                const int base = (int)(slot >> 5) * 64 + (int)(slot & 31);
+                got = exact_nearest_of(x, C, k, D, lane, 2 * (t1 - t0),
+                                       [=](int c) { return (t0 + (c >> 1)) * VLQ_NN_TILE + base + 32 * (c & 1); });
+            }
+            best = got < best ? got : best;
+        }
+    }
+    return best;
 }
 
 // The byte of lambda and the residual for the chosen line (Eq. 12-13), in fp64 so that both are
@@ -74,8 +119,8 @@ __device__ __forceinline__ float line_byte_and_residual(float *x, const float *_
 //  phase 1 (a wave per vector): the candidates within the rounding band of the
 //    smallest GEMM-form distance are re-evaluated as direct sums of squared
 //    differences; the smallest (distance, index) is the cell (Eq. 2).  Then the
-//    n lines of the cell: b_j direct, lambda_j by Eq. 13, squared line distance
-//    a - c lambda^2 (= Eq. 7 at that lambda); smallest (distance, j) is the edge.
+//    n lines of the cell: g_j = <x - c_i, s_ij - c_i>, lambda_j = g_j / c_j (Eq. 13), squared line
+//    distance a - c lambda^2 (= Eq. 7 at that lambda); smallest (distance, j) is the edge.
 //    lambda -> byte -> grid value; residual to the anchor of that grid value (Eq. 12).
 //  phase 2 (thread = codeword): for every sub-space the nearest codeword by direct
 //    squared distance, ties to the smaller codeword (Alg. 2).
@@ -92,6 +137,7 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
     const int np = (int)min((int64_t)PB, a.nb - g0);
 
     for (int i = tid; i < PB * m; i += ENC_NT) best[i] = KEY_MAX;
+    const bool vec16 = (D % 4 == 0) && (((uintptr_t)a.C) % 16 == 0);
 
     for (int pt = wave; pt < np; pt += ENC_NT / 64) {
         const int64_t gid = g0 + pt;
@@ -108,33 +154,33 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
         const int nc = a.nsplit * VLQ_NN_CANDS;
         const uint64_t *cd = a.cand + gid * nc;
         uint64_t mn = KEY_MAX;
-        bool ovf = false;
+        bool marked = false;
         for (int c = lane; c < nc; c += 64) {
             const uint64_t key = cd[c];
-            if (key == VLQ_NN_OVERFLOW)
-                ovf = true;
+            if ((uint32_t)(key >> 32) == VLQ_NN_MARK)
+                marked = true;
             else
                 mn = key < mn ? key : mn;
         }
-        uint64_t bk = KEY_MAX;
-        if (__ballot(ovf)) {
-            bk = exact_nearest(x, a.C, a.k, D, lane); // incomplete shortlist: every centroid
-        } else {
-            mn = wave_min_u64(mn);
+        // incomplete shortlists first: the marked slots (or all columns) exactly
+        uint64_t bk = __ballot(marked) ? resolve_markers(cd, nc, a.nsplit, x, a.C, a.k, D, lane) : KEY_MAX;
+        mn = wave_min_u64(mn);
+        if (mn != KEY_MAX) {
             const float dmin = __uint_as_float((uint32_t)(mn >> 32));
             const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
             for (int c = 0; c < nc; ++c) {
                 const uint64_t key = cd[c]; // same address in all lanes
-                if (key == KEY_MAX || __uint_as_float((uint32_t)(key >> 32)) > band) continue;
+                if (key == KEY_MAX || (uint32_t)(key >> 32) == VLQ_NN_MARK || __uint_as_float((uint32_t)(key >> 32)) > band)
+                    continue;
                 const uint32_t idx = (uint32_t)key;
-                const float d = wave_sqdist(x, a.C + (int64_t)idx * D, D, lane);
+                const float d = sqdist16(x, a.C + (int64_t)idx * D, D, lane & 15, vec16);
                 const uint64_t ek = make_key(d, idx);
                 bk = ek < bk ? ek : bk;
             }
-            if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
-                const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
-                bk = make_key(wave_sqdist(x, a.C + (int64_t)idx * D, D, lane), idx);
-            }
+        }
+        if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
+            const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
+            bk = make_key(sqdist16(x, a.C + (int64_t)idx * D, D, lane & 15, vec16), idx);
         }
         const int cell = (int)(uint32_t)bk;
         const float av = ord2f((uint32_t)(bk >> 32));
@@ -142,15 +188,19 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish(EncodeArgs a, int PB)
             if (lane == 0) a.cell[gid] = cell;
             continue;
         }
-        // line quantisation inside the cell
+        // line quantisation inside the cell: Eq. 8's numerator (a + c - b) / 2 as the inner product
+        // g = <x - c_i, s_ij - c_i> (no cancellation), squared line distance a - g^2 / c
         int bj = 0;
         float bd2 = INFINITY;
+        const float *cc = a.C + (int64_t)cell * D;
         for (int j = 0; j < n; ++j) {
-            const int s = a.S[(int64_t)cell * n + j];
-            const float b = wave_sqdist(x, a.C + (int64_t)s * D, D, lane);
+            const float *sr = a.C + (int64_t)a.S[(int64_t)cell * n + j] * D;
+            float g = 0.f;
+            for (int d = lane; d < D; d += 64) g = fmaf(x[d] - cc[d], sr[d] - cc[d], g);
+            g = wave_sum(g);
             const float c = a.E[(int64_t)cell * n + j];
-            const float lam = c > 0.f ? 0.5f * (av + c - b) / c : 0.f;
-            const float d2 = av - c * lam * lam;
+            const float lam = c > 0.f ? g / c : 0.f;
+            const float d2 = av - g * lam;
             if (d2 < bd2) {
                 bd2 = d2;
                 bj = j;
@@ -230,6 +280,7 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
     const int d0 = l16 * 4, d1 = 64 + l16 * 4;
     const bool has0 = d0 < D, has1 = d1 < D;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const bool vec16 = true; // this kernel serves D % 4 == 0 with aligned centroids only
 
     for (int pt = wave; pt < np; pt += ENC_NT / 64) {
         const int64_t gid = g0 + pt;
@@ -245,46 +296,55 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
         const int nc = a.nsplit * VLQ_NN_CANDS;
         const uint64_t *cd = a.cand + gid * nc;
         uint64_t mn = KEY_MAX;
-        bool ovf = false;
+        bool marked = false;
         for (int c = lane; c < nc; c += 64) {
             const uint64_t key = cd[c];
-            if (key == VLQ_NN_OVERFLOW)
-                ovf = true;
+            if ((uint32_t)(key >> 32) == VLQ_NN_MARK)
+                marked = true;
             else
                 mn = key < mn ? key : mn;
         }
-        uint64_t bk = KEY_MAX;
-        if (__ballot(ovf)) {
-            bk = exact_nearest(x, a.C, a.k, D, lane); // incomplete shortlist: every centroid
-        } else {
-            mn = wave_min_u64(mn);
+        // incomplete shortlists first: the marked slots (or all columns) exactly
+        uint64_t bk = __ballot(marked) ? resolve_markers(cd, nc, a.nsplit, x, a.C, a.k, D, lane) : KEY_MAX;
+        mn = wave_min_u64(mn);
+        if (mn != KEY_MAX) {
             const float dmin = __uint_as_float((uint32_t)(mn >> 32));
             const float band = dmin + a.band_dist * (xn + dmin) + a.band_norm * (3.f * xn + 2.f * dmin);
             for (int c0 = 0; c0 < nc; c0 += 64) { // the few candidates inside the band, found 64 keys at a time
                 const uint64_t key = c0 + lane < nc ? cd[c0 + lane] : KEY_MAX;
-                const bool inb = key != KEY_MAX && !(__uint_as_float((uint32_t)(key >> 32)) > band);
+                const bool inb = key != KEY_MAX && (uint32_t)(key >> 32) != VLQ_NN_MARK &&
+                                 !(__uint_as_float((uint32_t)(key >> 32)) > band);
                 uint64_t mask = __ballot(inb);
                 while (mask) {
                     const int src = __ffsll((unsigned long long)mask) - 1;
                     mask &= mask - 1;
                     const uint32_t idx = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, src);
-                    const float d = wave_sqdist(x, a.C + (int64_t)idx * D, D, lane);
+                    const float d = sqdist16(x, a.C + (int64_t)idx * D, D, lane & 15, vec16);
                     const uint64_t ek = make_key(d, idx);
                     bk = ek < bk ? ek : bk;
                 }
             }
-            if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
-                const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
-                bk = make_key(wave_sqdist(x, a.C + (int64_t)idx * D, D, lane), idx);
-            }
+        }
+        if (bk == KEY_MAX) { // only with non-finite input: keep indices in range
+            const uint32_t idx = mn == KEY_MAX ? 0u : (uint32_t)mn;
+            bk = make_key(sqdist16(x, a.C + (int64_t)idx * D, D, lane & 15, vec16), idx);
         }
         const int cell = (int)(uint32_t)bk;
         const float av = ord2f((uint32_t)(bk >> 32));
         // line quantisation inside the cell, four neighbour rows per pass
+        // (Eq. 8's numerator (a + c - b) / 2 as the inner product g = <x - c_i, s_ij - c_i>: no
+        // cancellation; squared line distance a - g^2 / c)
         const float *xg = a.X + gid * D;
-        f32x4 y0 = zero, y1 = zero;
-        if (has0) y0 = *(const f32x4 *)(xg + d0);
-        if (has1) y1 = *(const f32x4 *)(xg + d1);
+        const float *cg = a.C + (int64_t)cell * D;
+        f32x4 y0 = zero, y1 = zero, ci0 = zero, ci1 = zero; // y = x - c_i
+        if (has0) {
+            ci0 = *(const f32x4 *)(cg + d0);
+            y0 = *(const f32x4 *)(xg + d0) - ci0;
+        }
+        if (has1) {
+            ci1 = *(const f32x4 *)(cg + d1);
+            y1 = *(const f32x4 *)(xg + d1) - ci1;
+        }
         float bd2 = INFINITY;
         int bj = 0x7FFFFFFF;
         for (int j0 = 0; j0 < n; j0 += 16) { // 16 rows per round: their loads are all under way together
@@ -309,24 +369,24 @@ __global__ __launch_bounds__(ENC_NT) void k_encode_finish_lanes(EncodeArgs a)
                 const int j = j0 + 4 * u + sub;
                 float acc = 0.f;
                 {
-                    const float t0 = y0.x - c0[u].x, t1 = y0.y - c0[u].y, t2 = y0.z - c0[u].z, t3 = y0.w - c0[u].w;
-                    acc = fmaf(t0, t0, acc);
-                    acc = fmaf(t1, t1, acc);
-                    acc = fmaf(t2, t2, acc);
-                    acc = fmaf(t3, t3, acc);
+                    const f32x4 e0 = c0[u] - ci0;
+                    acc = fmaf(y0.x, e0.x, acc);
+                    acc = fmaf(y0.y, e0.y, acc);
+                    acc = fmaf(y0.z, e0.z, acc);
+                    acc = fmaf(y0.w, e0.w, acc);
                 }
                 {
-                    const float t0 = y1.x - c1[u].x, t1 = y1.y - c1[u].y, t2 = y1.z - c1[u].z, t3 = y1.w - c1[u].w;
-                    acc = fmaf(t0, t0, acc);
-                    acc = fmaf(t1, t1, acc);
-                    acc = fmaf(t2, t2, acc);
-                    acc = fmaf(t3, t3, acc);
+                    const f32x4 e1 = c1[u] - ci1;
+                    acc = fmaf(y1.x, e1.x, acc);
+                    acc = fmaf(y1.y, e1.y, acc);
+                    acc = fmaf(y1.z, e1.z, acc);
+                    acc = fmaf(y1.w, e1.w, acc);
                 }
                 acc = row16_sum(acc);
                 if (j < n) {
                     const float c = ev[u];
-                    const float lam = c > 0.f ? 0.5f * (av + c - acc) / c : 0.f;
-                    const float d2 = av - c * lam * lam;
+                    const float lam = c > 0.f ? acc / c : 0.f;
+                    const float d2 = av - acc * lam;
                     if (d2 < bd2) { // rows of a lane group come in ascending j
                         bd2 = d2;
                         bj = j;

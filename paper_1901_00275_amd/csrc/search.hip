@@ -6,14 +6,17 @@
 // Sub-region scores (Sec. 3.3.1): the query is line-quantised against every edge
 // l(c_i, s_ij) of every probed cell.  With a = ||y-c_i||^2, b = ||y-s_ij||^2 and
 // c = ||s_ij-c_i||^2, Eq. 8 gives the query's own lambda and Eq. 7 evaluated at
-// that lambda collapses to a - c lambda^2.  a and b are direct sums of squared
-// differences.  The w2 smallest by (score, label i*n+j) are kept.  On request the
+// that lambda collapses to a - c lambda^2.  Eq. 8's numerator (a + c - b) / 2 is the
+// inner product g = <y - c_i, s_ij - c_i>; it is formed as that inner product, which
+// keeps its rounding error proportional to |y - c_i| |s_ij - c_i| instead of a + b (a
+// query far from a short edge would otherwise lose lambda to cancellation), so
+// lambda = g / c, score = a - g lambda, and b - a = c - 2 g for the scan.  a is a
+// direct sum of squared differences.  The w2 smallest by (score, label i*n+j) are kept.  On request the
 // query's lambda is restricted to a range (the distance to a segment of the line).
 //
 // Outputs per query: the visited labels in (score, label) order (for callers
 // that want the traversal) and the same set ordered by label, so that the
-// sub-regions of one cell are adjacent, with g = <y-c_i, s_ij-c_i> = (a+c-b)/2
-// for the scan.
+// sub-regions of one cell are adjacent, with g for the scan.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ int wave_incl_scan(int v, int lane)
 {
@@ -45,7 +48,7 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
     // positions of the selected sub-regions are all that lives in LDS (twice the workgroups per CU).
     const bool lean = bpre && !sub && !sub_score && !scan_label;
     uint64_t *keys = (uint64_t *)smem;          // [sz]
-    float *bval = (float *)(keys + sz);          // [sz]   (not lean)
+    float *bval = (float *)(keys + sz);          // [sz]   (not lean) g of every sub-region
     float *yv = bval + sz;                       // [D]    (not lean)
     uint16_t *pos = (uint16_t *)(yv + D);        // [sz]   (not lean)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -71,17 +74,17 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
         }
     __syncthreads();
 
-    // Line score of sub-region t = (probed cell e, edge j) from b = ||y - s_ij||^2: lambda by
-    // Eq. 13, squared distance to the line a - c lambda^2 (Eq. 7 at that lambda)
-    auto put_score = [&](int t, float b) {
+    // Line score of sub-region t = (probed cell e, edge j) from g = <y - c_i, s_ij - c_i>: lambda by
+    // Eq. 8, squared distance to the line a - c lambda^2 = a - g lambda (Eq. 7 at that lambda)
+    auto put_score = [&](int t, float g) {
         const int e = t / n, j = t - e * n;
         const int i = cells[(int64_t)q * w1 + e];
         uint64_t key = KEY_MAX;
         if (i >= 0) {
             const float a = cell_dist[(int64_t)q * w1 + e];
             const float c = E[(int64_t)i * n + j];
-            const float lam = c > 0.f ? 0.5f * (a + c - b) / c : 0.f;
-            float score = a - c * lam * lam;
+            const float lam = c > 0.f ? g / c : 0.f;
+            float score = a - g * lam;
             // lambda restricted to [lam_min, lam_max] (the whole line by default): Eq. 7 at the
             // restricted value is the distance to the line plus c times the squared shift along it
             const float lc = fminf(fmaxf(lam, lam_min), lam_max);
@@ -90,15 +93,15 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
         }
         keys[t] = key;
         if (!lean) {
-            bval[t] = b;
+            bval[t] = g;
             pos[t] = (uint16_t)t;
         }
     };
     if (bpre) {
-        // the distances were computed cell by cell beforehand (k_neighbour_dists)
+        // the inner products were computed cell by cell beforehand (k_neighbour_dists)
         for (int t = tid; t < total; t += 256) put_score(t, bpre[(int64_t)q * total + t]);
     } else {
-        // b = ||y - s_ij||^2 for all w1*n sub-regions: 16 lanes per centroid row, 4 rows per wave
+        // g = <y - c_i, s_ij - c_i> for all w1*n sub-regions: 16 lanes per centroid row, 4 rows per wave
         // instruction, 16 rows in flight per wave (the rows are scattered over the codebook, so
         // the loop lives on memory-level parallelism).  The order of the additions is fixed.
         const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
@@ -112,20 +115,20 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                 float acc = 0.f;
                 if (s >= 0) {
                     const float *row = C + (int64_t)s * D;
+                    const float *crow = C + (int64_t)cells[(int64_t)q * w1 + t / n] * D;
                     if (vec) {
                         for (int d = l16 * 4; d < D; d += 64) {
                             const f32x4 cv = *(const f32x4 *)(row + d);
-                            const float t0v = yv[d] - cv.x, t1v = yv[d + 1] - cv.y, t2v = yv[d + 2] - cv.z,
-                                        t3v = yv[d + 3] - cv.w;
-                            acc = fmaf(t0v, t0v, acc);
-                            acc = fmaf(t1v, t1v, acc);
-                            acc = fmaf(t2v, t2v, acc);
-                            acc = fmaf(t3v, t3v, acc);
+                            const f32x4 cc = *(const f32x4 *)(crow + d);
+                            acc = fmaf(yv[d] - cc.x, cv.x - cc.x, acc);
+                            acc = fmaf(yv[d + 1] - cc.y, cv.y - cc.y, acc);
+                            acc = fmaf(yv[d + 2] - cc.z, cv.z - cc.z, acc);
+                            acc = fmaf(yv[d + 3] - cc.w, cv.w - cc.w, acc);
                         }
                     } else {
                         for (int d = l16; d < D; d += 16) {
-                            const float tv = yv[d] - row[d];
-                            acc = fmaf(tv, tv, acc);
+                            const float cc = crow[d];
+                            acc = fmaf(yv[d] - cc, row[d] - cc, acc);
                         }
                     }
                 }
@@ -342,8 +345,9 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
                 const int label = (int)(uint32_t)keys[t];
                 const float a = cell_dist[(int64_t)q * w1 + t / n];
                 const int64_t b0 = off[label], b1 = off[label + 1];
-                const float b = lean ? bpre[(int64_t)q * total + t] : bval[t];
-                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(b - a));
+                const float g = lean ? bpre[(int64_t)q * total + t] : bval[t];
+                // b - a = c - 2 g
+                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(fmaf(-2.f, g, E[label])));
             }
             desc[(int64_t)q * w2 + r] = dsc;
         }
@@ -389,12 +393,11 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
             const int p = pos[r];
             const int e = p / n;
             const float a = cell_dist[(int64_t)q * w1 + e];
-            const float c = E[label];
-            const float g = 0.5f * (a + c - bval[p]);
+            const float g = bval[p];
             k2 = ((uint64_t)(uint32_t)label << 32) | __float_as_uint(g);
             if (desc) {
                 const int64_t b0 = off[label], b1 = off[label + 1];
-                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(bval[p] - a));
+                dsc = make_uint4((uint32_t)b0, (uint32_t)(b1 - b0), __float_as_uint(a), __float_as_uint(fmaf(-2.f, g, E[label])));
             }
         }
         if (desc) desc[(int64_t)q * w2 + r] = dsc;
@@ -416,9 +419,10 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
 }
 
 // ---------------------------------------------------------------------------
-// b = ||y - s_ij||^2 cell by cell (Alg. 3, second loop).  A batch of queries probes most cells
-// several times; the (query, probed cell) pairs are grouped by cell, a workgroup brings the n
-// neighbour centroids of its cell into LDS once and serves every pair of the cell from there.
+// g = <y - c_i, s_ij - c_i> cell by cell (Alg. 3, second loop: the numerator of Eq. 8, from which
+// b = a + c - 2 g follows).  A batch of queries probes most cells several times; the (query, probed
+// cell) pairs are grouped by cell, a workgroup brings the centroid of its cell and the n edge vectors
+// s_ij - c_i into LDS once and serves every pair of the cell from there.
 // The sums are formed exactly as in k_subregions (16 lanes per row, fixed order).
 // ---------------------------------------------------------------------------
 __global__ void k_zero_i32(int32_t *p, int64_t n)
@@ -462,8 +466,9 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                                                          const int32_t *__restrict__ pairs,
                                                          float *__restrict__ bq)
 {
-    extern __shared__ float nrows[]; // [n][D]
+    extern __shared__ float nrows[]; // [n][D] edge vectors s_ij - c_i, then [D] the centroid c_i
     __shared__ int sp[ND_PCH], sc[ND_PCH];
+    float *crow = nrows + (size_t)n * D;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane >> 4, l16 = lane & 15;
     const int64_t np = poff[k]; // pairs with a valid cell
@@ -487,17 +492,23 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
         int e = i + 1;
         while (e < cntp && sc[e] == cell) ++e;
         __syncthreads(); // the previous cell's rows are no longer read
+        const float *cg = C + (int64_t)cell * D;
         if (vec) {
             const int d4 = D / 4;
-            for (int t = tid; t < n * d4; t += 256) {
+            for (int t = tid; t < (n + 1) * d4; t += 256) {
                 const int j = t / d4, c = t - j * d4;
-                const int s = S[(int64_t)cell * n + j];
-                ((f32x4 *)nrows)[t] = ((const f32x4 *)(C + (int64_t)s * D))[c];
+                const f32x4 cv = ((const f32x4 *)cg)[c];
+                if (j < n) {
+                    const int s = S[(int64_t)cell * n + j];
+                    ((f32x4 *)nrows)[t] = ((const f32x4 *)(C + (int64_t)s * D))[c] - cv;
+                } else {
+                    ((f32x4 *)nrows)[t] = cv;
+                }
             }
         } else {
-            for (int t = tid; t < n * D; t += 256) {
+            for (int t = tid; t < (n + 1) * D; t += 256) {
                 const int j = t / D, d = t - j * D;
-                nrows[t] = C[(int64_t)S[(int64_t)cell * n + j] * D + d];
+                nrows[t] = j < n ? C[(int64_t)S[(int64_t)cell * n + j] * D + d] - cg[d] : cg[d];
             }
         }
         __syncthreads();
@@ -506,14 +517,16 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
             auto run = [&](auto two_c, int pa, int pb) {
                 constexpr bool TWO = decltype(two_c)::value;
                 const float *ya = Q + (int64_t)(pa / w1) * D, *yb = Q + (int64_t)(pb / w1) * D;
-                f32x4 a0 = zero, a1 = zero, b0 = zero, b1 = zero;
+                f32x4 a0 = zero, a1 = zero, b0 = zero, b1 = zero; // y - c_i
                 if (has0) {
-                    a0 = *(const f32x4 *)(ya + d0);
-                    if (TWO) b0 = *(const f32x4 *)(yb + d0);
+                    const f32x4 cc = *(const f32x4 *)(crow + d0);
+                    a0 = *(const f32x4 *)(ya + d0) - cc;
+                    if (TWO) b0 = *(const f32x4 *)(yb + d0) - cc;
                 }
                 if (has1) {
-                    a1 = *(const f32x4 *)(ya + d1);
-                    if (TWO) b1 = *(const f32x4 *)(yb + d1);
+                    const f32x4 cc = *(const f32x4 *)(crow + d1);
+                    a1 = *(const f32x4 *)(ya + d1) - cc;
+                    if (TWO) b1 = *(const f32x4 *)(yb + d1) - cc;
                 }
                 for (int j0 = 0; j0 < n; j0 += 4) {
                     const int j = j0 + sub;
@@ -521,33 +534,29 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                     if (j < n) {
                         const float *row = nrows + j * D;
                         if (has0) {
-                            const f32x4 cv = *(const f32x4 *)(row + d0);
-                            float t0v = a0.x - cv.x, t1v = a0.y - cv.y, t2v = a0.z - cv.z, t3v = a0.w - cv.w;
-                            acca = fmaf(t0v, t0v, acca);
-                            acca = fmaf(t1v, t1v, acca);
-                            acca = fmaf(t2v, t2v, acca);
-                            acca = fmaf(t3v, t3v, acca);
+                            const f32x4 ev = *(const f32x4 *)(row + d0);
+                            acca = fmaf(a0.x, ev.x, acca);
+                            acca = fmaf(a0.y, ev.y, acca);
+                            acca = fmaf(a0.z, ev.z, acca);
+                            acca = fmaf(a0.w, ev.w, acca);
                             if (TWO) {
-                                t0v = b0.x - cv.x, t1v = b0.y - cv.y, t2v = b0.z - cv.z, t3v = b0.w - cv.w;
-                                accb = fmaf(t0v, t0v, accb);
-                                accb = fmaf(t1v, t1v, accb);
-                                accb = fmaf(t2v, t2v, accb);
-                                accb = fmaf(t3v, t3v, accb);
+                                accb = fmaf(b0.x, ev.x, accb);
+                                accb = fmaf(b0.y, ev.y, accb);
+                                accb = fmaf(b0.z, ev.z, accb);
+                                accb = fmaf(b0.w, ev.w, accb);
                             }
                         }
                         if (has1) {
-                            const f32x4 cv = *(const f32x4 *)(row + d1);
-                            float t0v = a1.x - cv.x, t1v = a1.y - cv.y, t2v = a1.z - cv.z, t3v = a1.w - cv.w;
-                            acca = fmaf(t0v, t0v, acca);
-                            acca = fmaf(t1v, t1v, acca);
-                            acca = fmaf(t2v, t2v, acca);
-                            acca = fmaf(t3v, t3v, acca);
+                            const f32x4 ev = *(const f32x4 *)(row + d1);
+                            acca = fmaf(a1.x, ev.x, acca);
+                            acca = fmaf(a1.y, ev.y, acca);
+                            acca = fmaf(a1.z, ev.z, acca);
+                            acca = fmaf(a1.w, ev.w, acca);
                             if (TWO) {
-                                t0v = b1.x - cv.x, t1v = b1.y - cv.y, t2v = b1.z - cv.z, t3v = b1.w - cv.w;
-                                accb = fmaf(t0v, t0v, accb);
-                                accb = fmaf(t1v, t1v, accb);
-                                accb = fmaf(t2v, t2v, accb);
-                                accb = fmaf(t3v, t3v, accb);
+                                accb = fmaf(b1.x, ev.x, accb);
+                                accb = fmaf(b1.y, ev.y, accb);
+                                accb = fmaf(b1.z, ev.z, accb);
+                                accb = fmaf(b1.w, ev.w, accb);
                             }
                         }
                     }
@@ -576,19 +585,15 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                     const float *row = nrows + j * D;
                     if (vec) {
                         for (int d = l16 * 4; d < D; d += 64) {
-                            const f32x4 cv = *(const f32x4 *)(row + d);
-                            const f32x4 yv = *(const f32x4 *)(y + d);
-                            const float t0v = yv.x - cv.x, t1v = yv.y - cv.y, t2v = yv.z - cv.z, t3v = yv.w - cv.w;
-                            acc = fmaf(t0v, t0v, acc);
-                            acc = fmaf(t1v, t1v, acc);
-                            acc = fmaf(t2v, t2v, acc);
-                            acc = fmaf(t3v, t3v, acc);
+                            const f32x4 ev = *(const f32x4 *)(row + d);
+                            const f32x4 zv = *(const f32x4 *)(y + d) - *(const f32x4 *)(crow + d);
+                            acc = fmaf(zv.x, ev.x, acc);
+                            acc = fmaf(zv.y, ev.y, acc);
+                            acc = fmaf(zv.z, ev.z, acc);
+                            acc = fmaf(zv.w, ev.w, acc);
                         }
                     } else {
-                        for (int d = l16; d < D; d += 16) {
-                            const float tv = y[d] - row[d];
-                            acc = fmaf(tv, tv, acc);
-                        }
+                        for (int d = l16; d < D; d += 16) acc = fmaf(y[d] - crow[d], row[d], acc);
                     }
                 }
                 acc = row16_sum(acc);
@@ -601,9 +606,9 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
 
 bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1)
 {
-    // the neighbour rows of a cell must fit in LDS
+    // the centroid of a cell and its n edge vectors must fit in LDS (two workgroups per compute unit)
     (void)nq; (void)k; (void)w1;
-    return (size_t)n * D * 4 <= 65536;
+    return (size_t)(n + 1) * D * 4 <= 73728;
 }
 
 size_t neighbour_dists_workspace(int nq, int k, int n, int w1)
@@ -660,7 +665,7 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         launch_exclusive_scan(cnt, k, poff, st);
         hipLaunchKernelGGL(k_pair_scatter, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, poff,
                            rank, pairs);
-        const size_t rows_bytes = (size_t)n * D * 4;
+        const size_t rows_bytes = (size_t)(n + 1) * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
         // runs of 32 pairs for large batches; shorter runs (down to one pair per workgroup) keep

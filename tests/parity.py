@@ -78,6 +78,31 @@ def check_selection(got, val_of, w, scale=None, what=""):
     return set(got) == set(want)
 
 
+def reconciled_graph(oracle, Cb, n, rows, S_gpu):
+    """Oracle graph rows (S, E as oracle.sparse_graph gives them) for the given centroids, made
+    consistent with the library's numbering of the edges: two neighbours whose distances from c_i
+    agree to fp32 resolution are ordered by index on the GPU and by their fp64 distances in the
+    oracle, and an edge label i * n + j then names different lines on the two sides.  Such a row
+    must equal the oracle's up to the tie band (checked here); the library's order is then adopted,
+    with the squared edge lengths of that order in fp64, so that everything downstream is compared
+    for the library's (valid) choice.  Returns (S, E, number of rows adopted)."""
+    S, E = oracle.sparse_graph(Cb, n, rows)
+    Cd = None
+    adopted = 0
+    for i in np.unique(np.asarray(rows)):
+        if (S_gpu[i] == S[i]).all():
+            continue
+        if Cd is None:
+            Cd = np.asarray(Cb, np.float64)
+        d = ((Cd - Cd[i]) ** 2).sum(1)
+        val = {int(j): float(d[j]) for j in np.argsort(d)[: 4 * n + 4] if j != i}
+        check_selection(S_gpu[i], val, n, what=f"graph row {i}")
+        S[i] = S_gpu[i]
+        E[i] = d[S_gpu[i]]
+        adopted += 1
+    return S, E, adopted
+
+
 STATS = {"max_abs_over_eps_scale": 0.0, "max_rel": 0.0}
 
 
