@@ -95,6 +95,10 @@ enum {
     VLQ_OPT_SCAN_PACKED,          /* -1 (default): by mean list length; 0: one list per wave at a time; 1: short lists packed */
     VLQ_OPT_SCAN_GENERIC,         /* 1: the scan with per-cell / per-sub-region tables (2m lookups, Sec. 3.3.2) for every shape */
     VLQ_OPT_ENCODE_WAVE,          /* 1: the wave-per-vector encode kernel for every shape */
+    VLQ_OPT_PIPELINE_PARTS,       /* 0 (default): by batch size; 1 .. 8: parts a batch is cut into, the region traversal of
+                                     part p + 1 running on a second stream beside the list scan of part p */
+    VLQ_OPT_SMALL_BATCH,          /* default 32: batches of up to this many queries take the forms with the fewest kernel
+                                     launches (fp32 distance matrix, neighbour distances per query); 0: never */
     VLQ_OPT_COUNT
 };
 

@@ -71,6 +71,8 @@ static int static_scratch(void **out)
 // ---------------------------------------------------------------------------
 // index object
 // ---------------------------------------------------------------------------
+#define VLQ_MAX_PARTS 8
+
 struct ProfRec {
     int stage;
     hipEvent_t t0, t1;
@@ -91,7 +93,10 @@ struct vlq_index {
     //   cn   [k] ||c - mu_c||^2;  Cc [k x D] c - mu_c, the operand of the fp32 contraction.
     float *mu = nullptr, *mu_c = nullptr, *cn = nullptr, *Cc = nullptr;
     // kernel choices (vlq_index_set_option) and the query-side lambda range
-    int opt[VLQ_OPT_COUNT] = {0, 0, -1, 0, 0};
+    int opt[VLQ_OPT_COUNT] = {0, 0, -1, 0, 0, 0, 32};
+    // second stream (default priority) and the events that order it against the caller's stream
+    hipStream_t side = nullptr;
+    hipEvent_t ev_go[VLQ_MAX_PARTS] = {}, ev_done[VLQ_MAX_PARTS] = {};
     float qlam_lo = -INFINITY, qlam_hi = INFINITY;
     // centroids split into bf16 (hi, lo) for the matrix-core shortlist; null when D does not allow it
     void *Cimg = nullptr;
@@ -179,6 +184,11 @@ extern "C" void vlq_index_free(vlq_index_t *idx)
         (void)hipEventDestroy(r.t0);
         (void)hipEventDestroy(r.t1);
     }
+    for (int p = 0; p < VLQ_MAX_PARTS; ++p) {
+        if (idx->ev_go[p]) (void)hipEventDestroy(idx->ev_go[p]);
+        if (idx->ev_done[p]) (void)hipEventDestroy(idx->ev_done[p]);
+    }
+    if (idx->side) (void)hipStreamDestroy(idx->side);
     delete idx;
 }
 
@@ -260,6 +270,11 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
             void *sp = nullptr;
             int r0 = static_scratch(&sp);
             if (r0) return r0;
+        }
+        HIPCHK(hipStreamCreateWithFlags(&idx->side, hipStreamNonBlocking));
+        for (int p = 0; p < VLQ_MAX_PARTS; ++p) {
+            HIPCHK(hipEventCreateWithFlags(&idx->ev_go[p], hipEventDisableTiming));
+            HIPCHK(hipEventCreateWithFlags(&idx->ev_done[p], hipEventDisableTiming));
         }
         HIPCHK(hipMalloc(&idx->C, (size_t)k * D * 4));
         HIPCHK(hipMalloc(&idx->cn, (size_t)k * 4));
@@ -785,9 +800,29 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
 // ---------------------------------------------------------------------------
 // search
 // ---------------------------------------------------------------------------
+// Scratch memory of one part of a batch (a part is a run of consecutive queries that goes through
+// the whole path on its own).
+struct PartBufs {
+    int q0 = 0, nq = 0;
+    bool bf16 = false, by_cell = false;
+    int csplit = 0, ccap = 0, nsplit = 1;
+    int64_t TQ = 0;
+    uint4 *desc = nullptr;
+    uint8_t *qimg = nullptr, *cws = nullptr, *nws = nullptr;
+    int32_t *qflag = nullptr, *cells = nullptr, *slab = nullptr;
+    float *qc = nullptr, *qn = nullptr, *dist = nullptr, *cell_dist = nullptr, *sg = nullptr;
+    uint64_t *partial = nullptr;
+};
+
 // `fixed` (optional): a caller-provided block of `fixed_bytes` that serves as the scratch memory
 // of this call instead of the index's own (which grows on demand); the call then allocates nothing
 // and fails when the block is too small.
+//
+// Large batches are cut into parts.  The region traversal of part p + 1 (coarse distances, cells,
+// sub-regions: matrix cores and latency-bound selections) is queued on the index's second stream
+// beside the list scan of part p (bandwidth-bound), so that only the first part's traversal is
+// exposed; events order the two streams, and the caller's stream has everything behind it when
+// the call returns.
 static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1, int32_t w2, int32_t K,
                        float *d_out_dist, int32_t *d_out_ids, int32_t *d_cells, float *d_cell_dist,
                        int32_t *d_sub, float *d_sub_score, hipStream_t st, void *fixed = nullptr,
@@ -807,47 +842,56 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     if (nq == 0) return VLQ_OK;
     if (!d_q || !d_out_dist || !d_out_ids) return fail(VLQ_EINVAL, "d_q, d_out_dist and d_out_ids must not be NULL");
 
-    // cells from two sweeps of the bf16 product where the shape allows it (VLQ_OPT_COARSE_FP32 asks
-    // for the fp32 distance matrix instead)
     const bool timed = !fixed; // (recording stage times creates events)
-    int csplit = 0, ccap = 0;
-    const bool bf16 = idx->Cimg && !idx->opt[VLQ_OPT_COARSE_FP32] && cells_bf16_plan(nq, k, D, w1, &csplit, &ccap);
-    int64_t TQ = ((int64_t)512 << 20) / ((int64_t)4 * k);
-    if (TQ < 128) TQ = 128;
-    if (TQ > nq) TQ = nq;
-    const int nsplit = scan_pick_nsplit(nq, w2, K);
+    // parts: VLQ_OPT_PIPELINE_PARTS; one by default (measured: the scan's workgroups refill every
+    // compute unit as fast as they leave, the traversal kernels of the next part starve beside them
+    // and the next scan waits for them, so two or more parts take longer than one)
+    int parts = idx->opt[VLQ_OPT_PIPELINE_PARTS];
+    if (parts <= 0) parts = 1;
+    if (parts > VLQ_MAX_PARTS) parts = VLQ_MAX_PARTS;
+    if (parts > nq) parts = nq;
+    if (!idx->side) parts = 1;
 
-    uint4 *desc;
-    uint8_t *qimg = nullptr, *cws = nullptr, *nws = nullptr;
-    int32_t *qflag = nullptr;
-    float *qc = nullptr;
-    const bool by_cell = neighbour_dists_by_cell(nq, k, n, D, w1) && !idx->opt[VLQ_OPT_NEIGHBOURS_PER_QUERY];
-    size_t o0, o1, o2, o3;
-    auto carve = [&](Bump &b, float **qn, float **dist, int32_t **cells, float **cell_dist, int32_t **slab,
-                     float **sg, uint64_t **partial) {
-        desc = b.take<uint4>((size_t)nq * w2);
-        *qn = b.take<float>((size_t)nq);
-        if (bf16) {
-            *dist = nullptr;
-            qimg = b.take<uint8_t>(coarse_bf16_image_bytes(nq, D));
-            qflag = b.take<int32_t>(64);
-            cws = b.take<uint8_t>(cells_bf16_workspace(nq, csplit, ccap, &o0, &o1, &o2, &o3));
-        } else {
-            *dist = b.take<float>((size_t)TQ * k);
-            qc = b.take<float>((size_t)TQ * D);
+    PartBufs pb[VLQ_MAX_PARTS];
+    auto carve = [&](Bump &b) {
+        for (int p = 0; p < parts; ++p) {
+            PartBufs &c = pb[p];
+            c.q0 = (int)((int64_t)nq * p / parts);
+            c.nq = (int)((int64_t)nq * (p + 1) / parts) - c.q0;
+            const int nqp = c.nq;
+            // cells from two sweeps of the bf16 product where the shape allows it (VLQ_OPT_COARSE_FP32
+            // asks for the fp32 distance matrix instead)
+            // (a few queries: the fp32 matrix and one selection kernel per query are three launches
+            // against six of the two-sweep form, and at that size the launches are what counts)
+            c.bf16 = idx->Cimg && !idx->opt[VLQ_OPT_COARSE_FP32] && nqp > idx->opt[VLQ_OPT_SMALL_BATCH] &&
+                     cells_bf16_plan(nqp, k, D, w1, &c.csplit, &c.ccap);
+            c.TQ = ((int64_t)512 << 20) / ((int64_t)4 * k);
+            if (c.TQ < 128) c.TQ = 128;
+            if (c.TQ > nqp) c.TQ = nqp;
+            c.nsplit = scan_pick_nsplit(nqp, w2, K);
+            c.by_cell = neighbour_dists_by_cell(nqp, k, n, D, w1) && !idx->opt[VLQ_OPT_NEIGHBOURS_PER_QUERY];
+            c.desc = b.take<uint4>((size_t)nqp * w2);
+            c.qn = b.take<float>((size_t)nqp);
+            if (c.bf16) {
+                size_t o0, o1, o2, o3;
+                c.dist = nullptr;
+                c.qimg = b.take<uint8_t>(coarse_bf16_image_bytes(nqp, D));
+                c.qflag = b.take<int32_t>(64);
+                c.cws = b.take<uint8_t>(cells_bf16_workspace(nqp, c.csplit, c.ccap, &o0, &o1, &o2, &o3));
+            } else {
+                c.dist = b.take<float>((size_t)c.TQ * k);
+                c.qc = b.take<float>((size_t)c.TQ * D);
+            }
+            if (c.by_cell) c.nws = b.take<uint8_t>(neighbour_dists_workspace(nqp, k, n, w1));
+            c.cells = b.take<int32_t>((size_t)nqp * w1);
+            c.cell_dist = b.take<float>((size_t)nqp * w1);
+            c.slab = b.take<int32_t>((size_t)nqp * w2);
+            c.sg = b.take<float>((size_t)nqp * w2);
+            c.partial = c.nsplit > 1 ? b.take<uint64_t>((size_t)nqp * c.nsplit * K) : nullptr;
         }
-        if (by_cell) nws = b.take<uint8_t>(neighbour_dists_workspace(nq, k, n, w1));
-        *cells = b.take<int32_t>((size_t)nq * w1);
-        *cell_dist = b.take<float>((size_t)nq * w1);
-        *slab = b.take<int32_t>((size_t)nq * w2);
-        *sg = b.take<float>((size_t)nq * w2);
-        *partial = nsplit > 1 ? b.take<uint64_t>((size_t)nq * nsplit * K) : nullptr;
     };
-    float *qn, *dist, *cell_dist, *sg;
-    int32_t *cells, *slab;
-    uint64_t *partial;
     Bump plan(nullptr);
-    carve(plan, &qn, &dist, &cells, &cell_dist, &slab, &sg, &partial);
+    carve(plan);
     void *wsbase;
     if (fixed) {
         if (plan.off + 256 > fixed_bytes)
@@ -860,106 +904,148 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
         wsbase = idx->ws;
     }
     Bump b(wsbase);
-    carve(b, &qn, &dist, &cells, &cell_dist, &slab, &sg, &partial);
+    carve(b);
 
-    launch_row_norms(d_q, nq, D, idx->mu_c, qn, st);
-    LAUNCHCHK();
-    // with the bf16 cell selection the (query, cell) pairs are counted per cell as the cells are written
-    PairWs pw = {};
-    bool pairs_counted = false;
-    if (by_cell) pw = neighbour_dists_carve(nws, nq, k, n, w1);
-    if (bf16 && by_cell) {
-        launch_pair_counts_zero(pw, k, st);
-        LAUNCHCHK();
-    }
-    if (bf16) {
-        {
-            StageTimer t(idx, st, VLQ_STAGE_COARSE, timed);
-            launch_split_bf16(d_q, nq, D, idx->mu_c, qimg, qflag, st);
-            LAUNCHCHK();
-            HIPCHK((hipError_t)launch_cells_bf16_coarse(qimg, qflag, nq, idx->Cimg, k, D, qn, idx->cn, w1, csplit, ccap,
-                                                        cws, st));
-        }
-        LAUNCHCHK();
-        {
-            StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS, timed);
-            launch_cells_bf16_exact(d_q, nq, D, idx->C, k, w1, ccap, cws, csplit, cells, cell_dist,
-                                    by_cell ? pw.cnt : nullptr, by_cell ? pw.rank : nullptr, st);
-            pairs_counted = by_cell;
-        }
-        LAUNCHCHK();
-    } else {
-        for (int64_t q0 = 0; q0 < nq; q0 += TQ) {
-            const int rows = (int)(nq - q0 < TQ ? nq - q0 : TQ);
-            {
-                StageTimer t(idx, st, VLQ_STAGE_COARSE, timed);
-                launch_center_rows(d_q + q0 * D, rows, D, idx->mu_c, qc, st);
-                launch_coarse_gemm_full(qc, rows, idx->Cc, k, D, qn + q0, idx->cn, dist, k, st);
-            }
-            LAUNCHCHK();
-            {
-                StageTimer t(idx, st, VLQ_STAGE_SELECT_CELLS, timed);
-                launch_select_cells(dist, k, rows, k, d_q + q0 * D, D, qn + q0, idx->C, idx->cn, w1, -1,
-                                    cells + q0 * w1, cell_dist + q0 * w1, st);
-            }
-            LAUNCHCHK();
-        }
-    }
-    ScanArgs a;
-    a.Q = d_q;
-    a.nq = nq;
-    a.D = D;
-    a.n = n;
-    a.m = m;
-    a.w2 = w2;
-    a.K = K;
-    a.nsplit = nsplit;
-    a.C = idx->C;
-    a.S = idx->S;
-    a.E = idx->E;
-    a.P = idx->P;
-    a.off = idx->off;
-    a.ids = idx->ids;
-    a.codes = idx->codes;
-    a.lam = idx->lam;
-    a.sx = idx->sx;
-    a.mu = idx->mu;
-    a.desc = desc;
-    {
+    auto scan_args = [&](const PartBufs &c) {
+        ScanArgs a;
+        a.Q = d_q + (int64_t)c.q0 * D;
+        a.nq = c.nq;
+        a.D = D;
+        a.n = n;
+        a.m = m;
+        a.w2 = w2;
+        a.K = K;
+        a.nsplit = c.nsplit;
+        a.C = idx->C;
+        a.S = idx->S;
+        a.E = idx->E;
+        a.P = idx->P;
+        a.off = idx->off;
+        a.ids = idx->ids;
+        a.codes = idx->codes;
+        a.lam = idx->lam;
+        a.sx = idx->sx;
+        a.mu = idx->mu;
+        a.desc = c.desc;
         // lists of a few tens of points: several of them share a chunk of 64 lanes
         // (VLQ_OPT_SCAN_PACKED forces either form)
         const int64_t nl = (int64_t)k * n;
         a.packed = idx->opt[VLQ_OPT_SCAN_PACKED] >= 0 ? idx->opt[VLQ_OPT_SCAN_PACKED] : (idx->ntotal < 64 * nl);
+        a.force_generic = idx->opt[VLQ_OPT_SCAN_GENERIC] != 0;
+        a.lam_step = idx->lam_step;
+        a.lam_zero = idx->lam_zero;
+        a.scan_label = c.slab;
+        a.scan_g = c.sg;
+        a.partial = c.partial;
+        a.out_dist = d_out_dist + (int64_t)c.q0 * K;
+        a.out_ids = d_out_ids + (int64_t)c.q0 * K;
+        return a;
+    };
+
+    // Region traversal of one part (Alg. 3, first loop; Sec. 3.3.1) on stream s
+    auto traverse = [&](const PartBufs &c, hipStream_t s) -> int {
+        const float *q = d_q + (int64_t)c.q0 * D;
+        const int nqp = c.nq;
+        launch_row_norms(q, nqp, D, idx->mu_c, c.qn, s);
+        LAUNCHCHK();
+        // with the bf16 cell selection the (query, cell) pairs are counted per cell as the cells are written
+        PairWs pw = {};
+        bool pairs_counted = false;
+        const bool grouped = c.by_cell && neighbour_dists_grouped(nqp, w1);
+        if (c.by_cell) pw = neighbour_dists_carve(c.nws, nqp, k, n, w1);
+        if (c.bf16 && grouped) {
+            launch_pair_counts_zero(pw, k, s);
+            LAUNCHCHK();
+        }
+        if (c.bf16) {
+            {
+                StageTimer t(idx, s, VLQ_STAGE_COARSE, timed);
+                launch_split_bf16(q, nqp, D, idx->mu_c, c.qimg, c.qflag, s);
+                LAUNCHCHK();
+                HIPCHK((hipError_t)launch_cells_bf16_coarse(c.qimg, c.qflag, nqp, idx->Cimg, k, D, c.qn, idx->cn, w1, c.csplit,
+                                                            c.ccap, c.cws, s));
+            }
+            LAUNCHCHK();
+            {
+                StageTimer t(idx, s, VLQ_STAGE_SELECT_CELLS, timed);
+                launch_cells_bf16_exact(q, nqp, D, idx->C, k, w1, c.ccap, c.cws, c.csplit, c.cells, c.cell_dist,
+                                        grouped ? pw.cnt : nullptr, grouped ? pw.rank : nullptr, s);
+                pairs_counted = grouped;
+            }
+            LAUNCHCHK();
+        } else {
+            for (int64_t r0 = 0; r0 < nqp; r0 += c.TQ) {
+                const int rows = (int)(nqp - r0 < c.TQ ? nqp - r0 : c.TQ);
+                {
+                    StageTimer t(idx, s, VLQ_STAGE_COARSE, timed);
+                    launch_center_rows(q + r0 * D, rows, D, idx->mu_c, c.qc, s);
+                    launch_coarse_gemm_full(c.qc, rows, idx->Cc, k, D, c.qn + r0, idx->cn, c.dist, k, s);
+                }
+                LAUNCHCHK();
+                {
+                    StageTimer t(idx, s, VLQ_STAGE_SELECT_CELLS, timed);
+                    launch_select_cells(c.dist, k, rows, k, q + r0 * D, D, c.qn + r0, idx->C, idx->cn, w1, -1,
+                                        c.cells + r0 * w1, c.cell_dist + r0 * w1, s);
+                }
+                LAUNCHCHK();
+            }
+        }
+        {
+            StageTimer t(idx, s, VLQ_STAGE_SUBREGIONS, timed);
+            // the streaming scan takes the visited sub-regions from desc alone, in any order
+            const bool stream = scan_will_stream(scan_args(c));
+            launch_subregions(q, nqp, D, idx->C, idx->S, idx->E, n, k, c.cells, c.cell_dist, w1, w2, idx->qlam_lo,
+                              idx->qlam_hi, d_sub ? d_sub + (int64_t)c.q0 * w2 : nullptr,
+                              d_sub_score ? d_sub_score + (int64_t)c.q0 * w2 : nullptr, stream ? nullptr : c.slab,
+                              stream ? nullptr : c.sg, idx->off, c.desc, c.nws, pairs_counted, s);
+        }
+        LAUNCHCHK();
+        if (d_cells)
+            HIPCHK(hipMemcpyAsync(d_cells + (int64_t)c.q0 * w1, c.cells, (size_t)nqp * w1 * 4, hipMemcpyDeviceToDevice, s));
+        if (d_cell_dist)
+            HIPCHK(hipMemcpyAsync(d_cell_dist + (int64_t)c.q0 * w1, c.cell_dist, (size_t)nqp * w1 * 4, hipMemcpyDeviceToDevice, s));
+        return VLQ_OK;
+    };
+    // Lookup tables, list scan, K-selection of one part (Sec. 3.3.2 - 3.3.3) on stream s
+    auto scan = [&](const PartBufs &c, hipStream_t s) -> int {
+        const ScanArgs a = scan_args(c);
+        {
+            StageTimer t(idx, s, VLQ_STAGE_SCAN, timed);
+            launch_scan(a, s);
+        }
+        LAUNCHCHK();
+        if (c.nsplit > 1) {
+            StageTimer t(idx, s, VLQ_STAGE_MERGE, timed);
+            launch_merge(c.partial, c.nq, c.nsplit, K, a.out_dist, a.out_ids, s);
+        }
+        LAUNCHCHK();
+        return VLQ_OK;
+    };
+
+    if (parts == 1) {
+        int rc = traverse(pb[0], st);
+        if (rc) return rc;
+        return scan(pb[0], st);
     }
-    a.force_generic = idx->opt[VLQ_OPT_SCAN_GENERIC] != 0;
-    a.lam_step = idx->lam_step;
-    a.lam_zero = idx->lam_zero;
-    a.scan_label = slab;
-    a.scan_g = sg;
-    a.partial = partial;
-    a.out_dist = d_out_dist;
-    a.out_ids = d_out_ids;
-    {
-        StageTimer t(idx, st, VLQ_STAGE_SUBREGIONS, timed);
-        // the streaming scan takes the visited sub-regions from desc alone, in any order
-        const bool stream = scan_will_stream(a);
-        launch_subregions(d_q, nq, D, idx->C, idx->S, idx->E, n, k, cells, cell_dist, w1, w2, idx->qlam_lo, idx->qlam_hi,
-                          d_sub, d_sub_score, stream ? nullptr : slab, stream ? nullptr : sg, idx->off, desc, nws,
-                          pairs_counted, st);
+    // st:    traverse(0) . scan(0) ........ scan(1) ........ scan(2) ...
+    // side:              traverse(1) ....... traverse(2) ....
+    // traverse(p + 1) starts when scan(p) is queued and must have finished before scan(p + 1) starts.
+    int rc = traverse(pb[0], st);
+    if (rc) return rc;
+    for (int p = 0; p < parts; ++p) {
+        if (p + 1 < parts) {
+            HIPCHK(hipEventRecord(idx->ev_go[p], st)); // everything queued on st so far, traverse(p) or scan(p - 1) included
+            HIPCHK(hipStreamWaitEvent(idx->side, idx->ev_go[p], 0));
+        }
+        rc = scan(pb[p], st);
+        if (rc) return rc;
+        if (p + 1 < parts) {
+            rc = traverse(pb[p + 1], idx->side);
+            if (rc) return rc;
+            HIPCHK(hipEventRecord(idx->ev_done[p], idx->side));
+            HIPCHK(hipStreamWaitEvent(st, idx->ev_done[p], 0));
+        }
     }
-    LAUNCHCHK();
-    {
-        StageTimer t(idx, st, VLQ_STAGE_SCAN, timed);
-        launch_scan(a, st);
-    }
-    LAUNCHCHK();
-    if (nsplit > 1) {
-        StageTimer t(idx, st, VLQ_STAGE_MERGE, timed);
-        launch_merge(partial, nq, nsplit, K, d_out_dist, d_out_ids, st);
-    }
-    LAUNCHCHK();
-    if (d_cells) HIPCHK(hipMemcpyAsync(d_cells, cells, (size_t)nq * w1 * 4, hipMemcpyDeviceToDevice, st));
-    if (d_cell_dist) HIPCHK(hipMemcpyAsync(d_cell_dist, cell_dist, (size_t)nq * w1 * 4, hipMemcpyDeviceToDevice, st));
     return VLQ_OK;
 }
 
@@ -1023,6 +1109,10 @@ extern "C" int vlq_index_set_option(vlq_index_t *idx, int option, int value)
     if (option < 0 || option >= VLQ_OPT_COUNT) return fail(VLQ_EINVAL, "unknown option %d", option);
     if (option == VLQ_OPT_SCAN_PACKED) {
         if (value < -1 || value > 1) return fail(VLQ_EINVAL, "VLQ_OPT_SCAN_PACKED takes -1, 0 or 1");
+    } else if (option == VLQ_OPT_SMALL_BATCH) {
+        if (value < 0) return fail(VLQ_EINVAL, "VLQ_OPT_SMALL_BATCH takes a size >= 0");
+    } else if (option == VLQ_OPT_PIPELINE_PARTS) {
+        if (value < 0 || value > VLQ_MAX_PARTS) return fail(VLQ_EINVAL, "VLQ_OPT_PIPELINE_PARTS takes 0 .. %d", VLQ_MAX_PARTS);
     } else if (value != 0 && value != 1) {
         return fail(VLQ_EINVAL, "option %d takes 0 or 1", option);
     }

@@ -584,7 +584,33 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
     block_minmax(mn, mx, tid, shf, &lo, &hi);
     int nsel = 0;      // entries selected so far (all below lo)
     bool ties = false; // the undecided entries are all equal to lo == hi
-    for (int level = 0; level < 8; ++level) {
+    // Short cut: the want-th smallest of the 1 024 per-thread minima bounds the want-th smallest entry
+    // from above (that many entries lie at or below it), and tightly, because the nearest columns
+    // rarely share a thread.  If no more than SEL_CAP entries lie at or below it they are the
+    // selection, and the histogram levels below have nothing left to decide.
+    bool decided = false; // uniform over the workgroup
+    {
+        keys[tid] = ((uint64_t)f2ord(mn) << 32) | (uint32_t)tid;
+        __syncthreads();
+        block_bitonic_sort<SEL2_NT>(keys, SEL2_NT, tid);
+        const float tau = ord2f((uint32_t)(keys[want - 1 < SEL2_NT ? want - 1 : SEL2_NT - 1] >> 32));
+        __syncthreads();
+        int c = 0;
+#pragma unroll
+        for (int e = 0; e < VPT; ++e) c += (undm >> e & 1) && v[e] <= tau;
+        int total;
+        (void)block_incl_scan_int(c, tid, sh16, &total);
+        if (want <= SEL2_NT && total >= want && total <= SEL_CAP) {
+#pragma unroll
+            for (int e = 0; e < VPT; ++e)
+                if ((undm >> e & 1) && v[e] <= tau) selm |= 1ull << e;
+            undm = 0;
+            nsel = total;
+            decided = true;
+        }
+        __syncthreads();
+    }
+    for (int level = 0; level < 8 && !decided; ++level) {
         if (!(hi > lo)) {
             ties = true;
             break;
@@ -642,7 +668,8 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
         sh_taken = 0;
     }
     __syncthreads();
-    if (ties || undm != 0 || nsel < want) {
+    const bool undecided = __syncthreads_or(undm != 0) != 0; // the same answer in every thread: barriers follow
+    if (!decided && (ties || undecided || nsel < want)) {
         // the undecided entries share one value (or the range could not be narrowed further):
         // the missing ones are taken in index order
         const int need = want - nsel;

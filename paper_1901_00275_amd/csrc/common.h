@@ -230,6 +230,7 @@ void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const f
 // then computed cell by cell over the whole batch first; neighbour_dists_by_cell() says when
 // that pays.
 bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1);
+bool neighbour_dists_grouped(int nq, int w1); // false: few pairs, each served on its own (no counting needed)
 size_t neighbour_dists_workspace(int nq, int k, int n, int w1);
 // The parts of that workspace.  A cell selection that can count the (query, cell) pairs per cell as
 // it writes them (and note each pair's rank inside its cell) gets `cnt`, zeroed by

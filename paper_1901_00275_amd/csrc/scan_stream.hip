@@ -279,11 +279,23 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     }
 
     // ---- merge the eight wave lists; resolve ids; order by (distance, id) ----
+    // Every wave's list is sorted and holds at most K keys: its first KP = 2^ceil(log2 K) entries are
+    // gathered (8 KP keys instead of the whole key area) and sorted once.
     merge_wave();
-    for (int i = SS_KP + lane; i < SS_WSZ; i += 64) wk[i] = KEY_MAX;
     __syncthreads();
-    block_bitonic_sort<SS_NT>(keys, SS_NW * SS_WSZ, tid);
     const int KP = next_pow2_dev(K);
+    uint64_t held[SS_KP * SS_NW / SS_NT > 0 ? SS_KP * SS_NW / SS_NT : 1]; // KP <= SS_KP: at most two keys per thread
+    {
+        int c = 0;
+        for (int i = tid; i < SS_NW * KP; i += SS_NT, ++c) held[c] = keys[(i / KP) * SS_WSZ + (i % KP)];
+    }
+    __syncthreads();
+    {
+        int c = 0;
+        for (int i = tid; i < SS_NW * KP; i += SS_NT, ++c) keys[i] = held[c];
+    }
+    __syncthreads();
+    block_bitonic_sort<SS_NT>(keys, SS_NW * KP, tid);
     uint64_t mine = KEY_MAX;
     if (tid < K) {
         const uint64_t key = keys[tid];

@@ -463,24 +463,26 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                                                          const int32_t *__restrict__ S, int n, int k, int w1,
                                                          int pch, const int32_t *__restrict__ cells,
                                                          const int64_t *__restrict__ poff,
-                                                         const int32_t *__restrict__ pairs,
+                                                         const int32_t *__restrict__ pairs, int64_t np_all,
                                                          float *__restrict__ bq)
 {
+    // pairs == nullptr: the pairs are taken in their own order, ungrouped (small batches: np_all of them)
     extern __shared__ float nrows[]; // [n][D] edge vectors s_ij - c_i, then [D] the centroid c_i
     __shared__ int sp[ND_PCH], sc[ND_PCH];
     float *crow = nrows + (size_t)n * D;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane >> 4, l16 = lane & 15;
-    const int64_t np = poff[k]; // pairs with a valid cell
+    const int64_t np = pairs ? poff[k] : np_all; // pairs with a valid cell
     const int64_t pbeg = (int64_t)blockIdx.x * pch;
     if (pbeg >= np) return;
     const int cntp = (int)min((int64_t)pch, np - pbeg);
     if (tid < cntp) {
-        const int p = pairs[pbeg + tid];
+        const int p = pairs ? pairs[pbeg + tid] : (int)(pbeg + tid);
         sp[tid] = p;
         sc[tid] = cells[p];
     }
     __syncthreads();
+    if (!pairs && sc[0] < 0) return; // (ungrouped runs hold one pair; a query with fewer than w1 cells)
     const bool vec = (D % 4 == 0) && ((((uintptr_t)C) | ((uintptr_t)Q)) % 16 == 0);
     const bool fast = vec && D <= 128;
     const int d0 = l16 * 4, d1 = 64 + l16 * 4;
@@ -604,6 +606,10 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
     }
 }
 
+// Few pairs: grouping them by cell (count, prefix sum over all k cells, scatter) costs more than the
+// row loads it saves; every pair is then served on its own.
+bool neighbour_dists_grouped(int nq, int w1) { return (int64_t)nq * w1 > 4096; }
+
 bool neighbour_dists_by_cell(int nq, int k, int n, int D, int w1)
 {
     // the centroid of a cell and its n edge vectors must fit in LDS (two workgroups per compute unit)
@@ -658,13 +664,16 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         int64_t *poff = pw.poff;
         float *bq = pw.bq;
         const int64_t np = (int64_t)nq * w1;
-        if (!pairs_counted) {
-            launch_pair_counts_zero(pw, k, st);
-            hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt, rank);
+        const bool grouped = neighbour_dists_grouped(nq, w1);
+        if (grouped) {
+            if (!pairs_counted) {
+                launch_pair_counts_zero(pw, k, st);
+                hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt, rank);
+            }
+            launch_exclusive_scan(cnt, k, poff, st);
+            hipLaunchKernelGGL(k_pair_scatter, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, poff,
+                               rank, pairs);
         }
-        launch_exclusive_scan(cnt, k, poff, st);
-        hipLaunchKernelGGL(k_pair_scatter, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, poff,
-                           rank, pairs);
         const size_t rows_bytes = (size_t)(n + 1) * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
@@ -672,8 +681,9 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         // all CUs busy when the batch is small
         int pch = (int)(np / 1024);
         pch = pch < 1 ? 1 : (pch > ND_PCH ? ND_PCH : pch);
+        if (!grouped) pch = 1;
         hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)((np + pch - 1) / pch)), dim3(256), rows_bytes, st, Q, D,
-                           C, S, n, k, w1, pch, cells, poff, pairs, bq);
+                           C, S, n, k, w1, pch, cells, poff, grouped ? pairs : nullptr, np, bq);
         bpre = bq;
     }
     int sz = next_pow2(w1 * n);
@@ -866,7 +876,7 @@ int scan_pick_nsplit(int nq, int w2, int K)
     int ns = (1024 + nq - 1) / nq;
     if (ns > w2) ns = w2;
     const int kp = next_pow2(K);
-    const int cap = 8192 / kp; // merge sorts nsplit * KP keys in LDS
+    const int cap = 8192 / kp; // the merge holds nsplit * K keys in LDS
     if (ns > cap) ns = cap;
     if (ns > 16) ns = 16;
     if (ns < 1) ns = 1;
@@ -890,19 +900,44 @@ void launch_scan(const ScanArgs &a, hipStream_t st)
 }
 
 // Merge of the per-split partial results of one query (second pass of the
-// two-pass K-selection of Sec. 4).
-__global__ __launch_bounds__(256) void k_merge(const uint64_t *__restrict__ partial, int nsplit, int K, int sz,
+// two-pass K-selection of Sec. 4).  Every partial list is sorted, so the place of a key in the
+// merged order is its position in its own list plus the number of keys that precede it in every
+// other list (a binary search each): no sorting.  Equal keys (possible only when the caller's ids
+// repeat) are ordered by list, so that every place is taken once.
+__global__ __launch_bounds__(256) void k_merge(const uint64_t *__restrict__ partial, int nsplit, int K,
                                                float *__restrict__ out_dist, int32_t *__restrict__ out_ids)
 {
     extern __shared__ unsigned char smem[];
-    uint64_t *keys = (uint64_t *)smem;
+    uint64_t *keys = (uint64_t *)smem; // [nsplit][K]
+    uint64_t *outk = keys + nsplit * K; // [K]
     const int tid = threadIdx.x, q = blockIdx.x;
     const int total = nsplit * K;
-    for (int i = tid; i < sz; i += 256) keys[i] = i < total ? partial[(int64_t)q * total + i] : KEY_MAX;
+    for (int i = tid; i < total; i += 256) keys[i] = partial[(int64_t)q * total + i];
+    for (int i = tid; i < K; i += 256) outk[i] = KEY_MAX;
     __syncthreads();
-    block_bitonic_sort<256>(keys, sz, tid);
+    for (int e = tid; e < total; e += 256) {
+        const uint64_t x = keys[e];
+        if (x == KEY_MAX) continue;
+        const int s = e / K;
+        int rank = e - s * K;
+        for (int o = 0; o < nsplit && rank < K; ++o) {
+            if (o == s) continue;
+            const uint64_t *l = keys + o * K;
+            int lo = 0, hi = K; // keys of list o that precede x: smaller ones, and equal ones of earlier lists
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (l[mid] < x || (o < s && l[mid] == x))
+                    lo = mid + 1;
+                else
+                    hi = mid;
+            }
+            rank += lo;
+        }
+        if (rank < K) outk[rank] = x;
+    }
+    __syncthreads();
     for (int i = tid; i < K; i += 256) {
-        const uint64_t key = keys[i];
+        const uint64_t key = outk[i];
         const bool ok = key != KEY_MAX;
         out_dist[(int64_t)q * K + i] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
         out_ids[(int64_t)q * K + i] = ok ? (int32_t)(uint32_t)key : -1;
@@ -913,8 +948,7 @@ void launch_merge(const uint64_t *partial, int nq, int nsplit, int K, float *out
                   hipStream_t st)
 {
     if (nq <= 0) return;
-    const int sz = next_pow2(nsplit * K);
-    size_t smem = (size_t)sz * 8;
+    size_t smem = (size_t)(nsplit + 1) * K * 8;
     (void)hipFuncSetAttribute((const void *)k_merge, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    hipLaunchKernelGGL(k_merge, dim3((unsigned)nq), dim3(256), smem, st, partial, nsplit, K, sz, out_dist, out_ids);
+    hipLaunchKernelGGL(k_merge, dim3((unsigned)nq), dim3(256), smem, st, partial, nsplit, K, out_dist, out_ids);
 }
