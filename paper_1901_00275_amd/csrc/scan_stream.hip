@@ -44,25 +44,44 @@ typedef __attribute__((address_space(3))) unsigned long long lds_u64;
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
-// wave-private bitonic sort of SS_WSZ keys in LDS (LDS operations of one wave
-// complete in issue order, so no workgroup barrier is needed)
-__device__ __forceinline__ void wave_sort256(volatile lds_u64 *wk, int lane)
+// Wave-private merge of the candidate buffer wk[SS_KP .. SS_WSZ) (unsorted, padded with KEY_MAX) into
+// the sorted list wk[0 .. SS_KP): the candidates are sorted in descending order, which makes the whole
+// array one bitonic sequence; a single compare-exchange stage against the list leaves the SS_KP
+// smallest keys (still bitonic) in the list's place, and a bitonic merge orders them.  About half
+// the LDS traffic of sorting all SS_WSZ keys.  (LDS operations of one wave complete in issue
+// order, so no workgroup barrier is needed.)
+__device__ __forceinline__ void wave_merge_candidates(volatile lds_u64 *wk, int lane)
 {
-    for (int k = 2; k <= SS_WSZ; k <<= 1)
+    static_assert(SS_KP == 128 && SS_WSZ == 256, "one comparator per lane and stage");
+    volatile lds_u64 *c = wk + SS_KP;
+    for (int k = 2; k <= SS_KP; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
-#pragma unroll
-            for (int h = 0; h < SS_WSZ / 128; ++h) {
-                const int i = lane + 64 * h;
-                const int l = ((i & ~(j - 1)) << 1) | (i & (j - 1));
-                const int r = l | j;
-                const uint64_t x = wk[l], y = wk[r];
-                if ((x > y) == ((l & k) == 0)) {
-                    wk[l] = y;
-                    wk[r] = x;
-                }
+            const int l = ((lane & ~(j - 1)) << 1) | (lane & (j - 1));
+            const int r = l | j;
+            const uint64_t x = c[l], y = c[r];
+            if ((x < y) == ((l & k) == 0)) { // descending
+                c[l] = y;
+                c[r] = x;
             }
             __builtin_amdgcn_wave_barrier();
         }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int i = lane + 64 * h;
+        const uint64_t x = wk[i], y = c[i];
+        if (y < x) wk[i] = y;
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int j = SS_KP >> 1; j > 0; j >>= 1) {
+        const int l = ((lane & ~(j - 1)) << 1) | (lane & (j - 1));
+        const int r = l | j;
+        const uint64_t x = wk[l], y = wk[r];
+        if (x > y) {
+            wk[l] = y;
+            wk[r] = x;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // PACKED: the lists are short (a few tens of points): a wave takes SS_GL lists at a time and lays
@@ -112,7 +131,7 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     auto merge_wave = [&]() {
         for (int i = SS_KP + wcnt + lane; i < SS_WSZ; i += 64) wk[i] = KEY_MAX;
         __builtin_amdgcn_wave_barrier();
-        wave_sort256(wk, lane);
+        wave_merge_candidates(wk, lane);
         for (int i = K + lane; i < SS_KP; i += 64) wk[i] = KEY_MAX;
         __builtin_amdgcn_wave_barrier();
         wcnt = 0;
