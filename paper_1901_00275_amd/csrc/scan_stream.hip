@@ -50,6 +50,21 @@ typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 // smallest keys (still bitonic) in the list's place, and a bitonic merge orders them.  About half
 // the LDS traffic of sorting all SS_WSZ keys.  (LDS operations of one wave complete in issue
 // order, so no workgroup barrier is needed.)
+// bitonic sequence of SS_KP keys -> ascending (one wave, one comparator per lane and stage)
+__device__ __forceinline__ void wave_bitonic_merge(volatile lds_u64 *wk, int lane)
+{
+    for (int j = SS_KP >> 1; j > 0; j >>= 1) {
+        const int l = ((lane & ~(j - 1)) << 1) | (lane & (j - 1));
+        const int r = l | j;
+        const uint64_t x = wk[l], y = wk[r];
+        if (x > y) {
+            wk[l] = y;
+            wk[r] = x;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 __device__ __forceinline__ void wave_merge_candidates(volatile lds_u64 *wk, int lane)
 {
     static_assert(SS_KP == 128 && SS_WSZ == 256, "one comparator per lane and stage");
@@ -72,16 +87,20 @@ __device__ __forceinline__ void wave_merge_candidates(volatile lds_u64 *wk, int 
         if (y < x) wk[i] = y;
     }
     __builtin_amdgcn_wave_barrier();
-    for (int j = SS_KP >> 1; j > 0; j >>= 1) {
-        const int l = ((lane & ~(j - 1)) << 1) | (lane & (j - 1));
-        const int r = l | j;
-        const uint64_t x = wk[l], y = wk[r];
-        if (x > y) {
-            wk[l] = y;
-            wk[r] = x;
-        }
-        __builtin_amdgcn_wave_barrier();
+    wave_bitonic_merge(wk, lane);
+}
+
+// Two sorted lists a, b of SS_KP keys each -> the SS_KP smallest of both, sorted, in a (one wave).
+__device__ __forceinline__ void wave_merge_lists(volatile lds_u64 *a, volatile lds_u64 *b, int lane)
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int i = lane + 64 * h;
+        const uint64_t x = a[i], y = b[SS_KP - 1 - i];
+        if (y < x) a[i] = y;
     }
+    __builtin_amdgcn_wave_barrier();
+    wave_bitonic_merge(a, lane);
 }
 
 // PACKED: the lists are short (a few tens of points): a wave takes SS_GL lists at a time and lays
@@ -298,38 +317,50 @@ __global__ __launch_bounds__(SS_NT, 4) void k_scan_stream(ScanArgs a, const uint
     }
 
     // ---- merge the eight wave lists; resolve ids; order by (distance, id) ----
-    // Every wave's list is sorted and holds at most K keys: its first KP = 2^ceil(log2 K) entries are
-    // gathered (8 KP keys instead of the whole key area) and sorted once.
+    // Every wave's list is sorted: a tree of three rounds merges them pairwise, each merge keeping
+    // the SS_KP smallest keys of its two lists (one wave per merge, no sorting).
     merge_wave();
-    __syncthreads();
     const int KP = next_pow2_dev(K);
-    uint64_t held[SS_KP * SS_NW / SS_NT > 0 ? SS_KP * SS_NW / SS_NT : 1]; // KP <= SS_KP: at most two keys per thread
+#pragma unroll
+    for (int step = SS_NW / 2; step >= 1; step >>= 1) {
+        __syncthreads();
+        if (wave < step) wave_merge_lists(wk, (volatile lds_u64 *)(keys + (wave + step) * SS_WSZ), lane);
+    }
+    __syncthreads();
+    // The first wave resolves the ids of the K survivors and orders them by (distance, id): the list is
+    // in (distance, position) order, so only keys of equal distance can move (a wave-private sort).
+    if (wave != 0) return;
     {
-        int c = 0;
-        for (int i = tid; i < SS_NW * KP; i += SS_NT, ++c) held[c] = keys[(i / KP) * SS_WSZ + (i % KP)];
+        uint64_t mine[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int i = lane + 64 * h;
+            const uint64_t key = i < K ? wk[i] : KEY_MAX;
+            mine[h] = key != KEY_MAX ? ((key & 0xFFFFFFFF00000000ull) | (uint32_t)a.ids[(uint32_t)key]) : KEY_MAX;
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) wk[lane + 64 * h] = mine[h];
+        __builtin_amdgcn_wave_barrier();
+        for (int k = 2; k <= KP; k <<= 1)
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const int l = ((lane & ~(j - 1)) << 1) | (lane & (j - 1));
+                const int r = l | j;
+                if (r < KP) {
+                    const uint64_t x = wk[l], y = wk[r];
+                    if ((x > y) == ((l & k) == 0)) {
+                        wk[l] = y;
+                        wk[r] = x;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
     }
-    __syncthreads();
-    {
-        int c = 0;
-        for (int i = tid; i < SS_NW * KP; i += SS_NT, ++c) keys[i] = held[c];
-    }
-    __syncthreads();
-    block_bitonic_sort<SS_NT>(keys, SS_NW * KP, tid);
-    uint64_t mine = KEY_MAX;
-    if (tid < K) {
-        const uint64_t key = keys[tid];
-        if (key != KEY_MAX) mine = (key & 0xFFFFFFFF00000000ull) | (uint32_t)a.ids[(uint32_t)key];
-    }
-    __syncthreads();
-    if (tid < KP) keys[tid] = mine;
-    __syncthreads();
-    block_bitonic_sort<SS_NT>(keys, KP, tid);
     if (a.nsplit > 1) {
         uint64_t *dst = a.partial + ((int64_t)q * a.nsplit + split) * K;
-        for (int i = tid; i < K; i += SS_NT) dst[i] = keys[i];
+        for (int i = lane; i < K; i += 64) dst[i] = wk[i];
     } else {
-        for (int i = tid; i < K; i += SS_NT) {
-            const uint64_t key = keys[i];
+        for (int i = lane; i < K; i += 64) {
+            const uint64_t key = wk[i];
             const bool ok = key != KEY_MAX;
             a.out_dist[(int64_t)q * K + i] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
             a.out_ids[(int64_t)q * K + i] = ok ? (int32_t)(uint32_t)key : -1;
