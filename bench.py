@@ -53,7 +53,7 @@ def scan_bytes(vlq, wl, w1, w2, torch):
     return points * (cfg.m + 5) + visited * 8, points, (od, oi, cells, cd, sub, ss)
 
 
-def parity_on_sample(vlq, wl, w1, w2, dbg, torch, nsample=100):
+def parity_on_sample(vlq, wl, w1, w2, dbg, torch, nsample=100, qlam=None):
     """The tests' protocol on the first queries of the timed batch, at full size: cells, sub-regions
     and scores against the oracle's traversal, and the whole top-K against the oracle's scan of the
     lists the GPU visited (copied out of the library).  Returns the summary and the list of
@@ -67,6 +67,8 @@ def parity_on_sample(vlq, wl, w1, w2, dbg, torch, nsample=100):
     from parity import DTOL, check_selection, check_topk, reconciled_graph, term_scale
 
     cfg = wl.cfg
+    prm = vlq.vlq_index_params(wl.idx)
+    grid = (float(prm.lambda_lo), float(prm.lambda_hi))  # the lambda byte grid of this index
     ns = min(nsample, wl.Y.shape[0])
     od, oi, cells, cd, sub, ss = (t[:ns] for t in dbg)
     lists = oracle.Lists(*workloads.visited_lists(vlq, wl.idx, cfg, sub))
@@ -86,12 +88,12 @@ def parity_on_sample(vlq, wl, w1, w2, dbg, torch, nsample=100):
         try:
             same_c = check_selection(cells[q], dict(enumerate(dist[q])), w1, what=f"query {q} cells")
             assert np.allclose(cd[q], dist[q][cells[q]], rtol=DTOL), f"query {q} cell distances"
-            score, label = (x[0] for x in oracle.subregion_scores(dist[q:q + 1], S, E, cells[q:q + 1]))
+            score, label = (x[0] for x in oracle.subregion_scores(dist[q:q + 1], S, E, cells[q:q + 1], qlam or (-np.inf, np.inf)))
             val = {int(l): float(v) for l, v in zip(label, score)}
             a_max = dist[q][cells[q]].max()
             same_s = check_selection(sub[q], val, w2, scale=a_max, what=f"query {q} sub-regions")
             assert np.allclose(ss[q], [val[int(l)] for l in sub[q]], rtol=0, atol=DTOL * a_max), f"query {q} scores"
-            o_d, o_i, _ = (x[0] for x in oracle.scan(Cb, S, P, lists, Y[q:q + 1], sub[q:q + 1], cfg.K + 16))
+            o_d, o_i, _ = (x[0] for x in oracle.scan(Cb, S, P, lists, Y[q:q + 1], sub[q:q + 1], cfg.K + 16, *grid))
             same_k = check_topk(od[q], oi[q], o_d, o_i, cfg.K, what=f"query {q}", scale=term_scale(a_max, Y[q], Cb, P), m=cfg.m)
             o_map = {int(i): float(d) for d, i in zip(o_d, o_i)}
             max_rel = max(max_rel, max(abs(float(g) - o_map[int(i)]) / max(o_map[int(i)], 1e-30) for g, i in zip(od[q], oi[q]) if i >= 0))
@@ -195,6 +197,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="also the alpha, batch-size and K sweeps of the configuration (the w1 sweep always runs)")
+    ap.add_argument("--query-lambda", default="",
+                    help="restrict the query's lambda in the region traversal to LO,HI (Sec. 3.3.1 variant; 'grid' = the "
+                         "range of the lambda byte, '0,1' = the segment between the two centroids; default: the whole line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain streaming kernel of known size (torch.frac over 2^28 floats: 1 GiB read, "
                          "1 GiB written), the yardstick for the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -215,6 +220,11 @@ def main():
     wl = workloads.materialise(vlq, cfg, "cuda:0", n_points=args.points or None, log=log)
     nq, K = cfg.nq, cfg.K
     dev = wl.Y.device
+    qlam = None
+    if args.query_lambda:
+        prm = vlq.vlq_index_params(wl.idx)
+        qlam = (prm.lambda_lo, prm.lambda_hi) if args.query_lambda == "grid" else tuple(float(x) for x in args.query_lambda.split(","))
+        vlq.vlq_index_set_query_lambda_range(wl.idx, *qlam)
     od = torch.empty(nq, K, device=dev)
     oi = torch.empty(nq, K, dtype=torch.int32, device=dev)
 
@@ -257,6 +267,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "N": vlq.vlq_index_ntotal(wl.idx), "D": cfg.D, "centroids": cfg.k,
                    "edges": cfg.n, "code_bytes": cfg.m, "queries": nq, "w1": w1, "w2": w2, "K": K,
+                   "query_lambda_range": qlam,
                    "recall": rec, "points_scanned_per_query": points / nq,
                    "stage_ms_per_step": stage_ms, "build_s": wl.timings,
                    "coarse_mfma": {"flop_per_step": coarse_flop, "ms_per_step": coarse_s * 1e3,
@@ -325,7 +336,7 @@ def main():
             result["config"]["batch_sweep"] = bs
     violations = []
     if not args.no_cpu_baseline:
-        summary, violations = parity_on_sample(vlq, wl, w1, w2, dbg, torch)
+        summary, violations = parity_on_sample(vlq, wl, w1, w2, dbg, torch, qlam=qlam)
         result["config"]["parity_on_sample"] = summary
         base, o_ids, ns = cpu_baseline(vlq, wl, w1, w2, torch)
         result["cpu_baseline"] = base
