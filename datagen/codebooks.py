@@ -11,7 +11,7 @@ from . import MASTER_SEED, STREAM_KMEANS, _gen
 
 
 def _seeded_init(X: torch.Tensor, k: int, seed: int, stream: int) -> torch.Tensor:
-    """The initial codebook of `lloyd`: k seeded rows of X (jittered copies if X has fewer rows)."""
+    """An initial codebook for Lloyd iterations: k seeded rows of X (jittered copies if X has fewer rows)."""
     g = _gen("cpu", seed, STREAM_KMEANS, stream)
     nt = X.shape[0]
     if nt >= k:
