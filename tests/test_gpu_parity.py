@@ -433,6 +433,36 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq):
         vlq.vlq_index_free(idx)
 
 
+@pytest.mark.parametrize("name", ["sift_ragged", "deep_m16"])
+def test_batch_parts_and_small_batch_forms_agree(vlq, name):
+    """A batch cut into parts whose region traversal runs on the index's second stream beside the scan of
+    the part before (VLQ_OPT_PIPELINE_PARTS), and the forms a handful of queries take (fp32 distance matrix,
+    ungrouped edge products: VLQ_OPT_SMALL_BATCH) against the ordinary ones: every output identical."""
+    kw, w1, w2, K = CASES[name]
+    pr = problem(**kw)
+    idx = make_index(vlq, pr, base=pr.X)
+    try:
+        ref = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        for parts in (2, 4, 8):
+            vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_PIPELINE_PARTS, parts)
+            for rep in range(2):  # the second call reuses the events of the first
+                got = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+                for x, y in zip(ref, got):
+                    assert np.array_equal(x, y), f"{parts} parts"
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_PIPELINE_PARTS, 0)
+        with pytest.raises(vlq.VlqError):
+            vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_PIPELINE_PARTS, 99)
+        Y = pr.Y[:20]
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SMALL_BATCH, 0)
+        a = gpu_search(vlq, idx, Y, w1, w2, K)
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SMALL_BATCH, 4096)
+        b = gpu_search(vlq, idx, Y, w1, w2, K)
+        assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2]) and np.array_equal(a[4], b[4])
+        assert np.allclose(a[0], b[0], rtol=1e-6) and np.allclose(a[3], b[3], rtol=1e-6)
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 @pytest.mark.parametrize("name", ["sift_ragged", "deep_m16", "small_d32"])
 def test_both_encode_kernels_agree(vlq, oracle_mod, name):
     """Encoding has a kernel for the common shapes (a lane per vector in the product-quantisation step,
