@@ -804,7 +804,7 @@ extern "C" int vlq_index_finalize(vlq_index_t *idx, void *stream)
 // the whole path on its own).
 struct PartBufs {
     int q0 = 0, nq = 0;
-    bool bf16 = false, by_cell = false;
+    bool bf16 = false, by_cell = false, from_matrix = false;
     int csplit = 0, ccap = 0, nsplit = 1;
     int64_t TQ = 0;
     uint4 *desc = nullptr;
@@ -881,6 +881,9 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
             } else {
                 c.dist = b.take<float>((size_t)c.TQ * k);
                 c.qc = b.take<float>((size_t)c.TQ * D);
+                // a handful of queries: exact distances in one pass over the codebook, cells straight from them
+                c.from_matrix = nqp <= idx->opt[VLQ_OPT_SMALL_BATCH] && nqp <= c.TQ && !idx->opt[VLQ_OPT_COARSE_FP32] &&
+                                cells_small_supported(nqp, k, D, w1);
             }
             if (c.by_cell) c.nws = b.take<uint8_t>(neighbour_dists_workspace(nqp, k, n, w1));
             c.cells = b.take<int32_t>((size_t)nqp * w1);
@@ -946,8 +949,10 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
     auto traverse = [&](const PartBufs &c, hipStream_t s) -> int {
         const float *q = d_q + (int64_t)c.q0 * D;
         const int nqp = c.nq;
-        launch_row_norms(q, nqp, D, idx->mu_c, c.qn, s);
-        LAUNCHCHK();
+        if (!c.from_matrix) {
+            launch_row_norms(q, nqp, D, idx->mu_c, c.qn, s);
+            LAUNCHCHK();
+        }
         // with the bf16 cell selection the (query, cell) pairs are counted per cell as the cells are written
         PairWs pw = {};
         bool pairs_counted = false;
@@ -972,6 +977,10 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
                                         grouped ? pw.cnt : nullptr, grouped ? pw.rank : nullptr, s);
                 pairs_counted = grouped;
             }
+            LAUNCHCHK();
+        } else if (c.from_matrix) {
+            StageTimer t(idx, s, VLQ_STAGE_COARSE, timed);
+            launch_cells_small(q, nqp, D, idx->C, k, w1, c.dist, c.cells, c.cell_dist, s);
             LAUNCHCHK();
         } else {
             for (int64_t r0 = 0; r0 < nqp; r0 += c.TQ) {

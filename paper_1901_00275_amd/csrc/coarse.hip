@@ -762,6 +762,173 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
     }
 }
 
+// ---------------------------------------------------------------------------
+// A handful of queries (Alg. 3, first loop, when launches count more than flop): exact distances of
+// all queries to all centroids in one pass over the codebook, then one workgroup per query that
+// takes its w nearest straight from those values.
+//
+// k_small_dists: 16 lanes per centroid row (four components per lane and step, the adder's
+// lane-crossing sum: the summation order of every exact distance in this library), four rows per
+// wave and pass, the queries in LDS; a centroid row is read once for all queries.
+// ---------------------------------------------------------------------------
+#define SMALL_NQ 32   // most queries of the form
+#define SMALL_ROWS 64 // centroid rows per workgroup
+
+__global__ __launch_bounds__(256) void k_small_dists(const float *__restrict__ Q, int nq, int D,
+                                                     const float *__restrict__ C, int k, float *__restrict__ dist)
+{
+    extern __shared__ float yq[]; // [nq][D]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub16 = lane >> 4, l16 = lane & 15;
+    for (int i = tid; i < nq * D; i += 256) yq[i] = Q[i];
+    __syncthreads();
+    const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
+    const int r0 = blockIdx.x * SMALL_ROWS;
+    for (int rr = wave * 4; rr < SMALL_ROWS; rr += 16) {
+        const int i = r0 + rr + sub16;
+        const float *rowp = C + (int64_t)min(i, k - 1) * D;
+        for (int q = 0; q < nq; ++q) {
+            const float *yv = yq + q * D;
+            float acc = 0.f;
+            if (vec) {
+                for (int d = l16 * 4; d < D; d += 64) {
+                    const f32x4 cv = *(const f32x4 *)(rowp + d);
+                    const float t0 = yv[d] - cv.x, t1 = yv[d + 1] - cv.y, t2 = yv[d + 2] - cv.z, t3 = yv[d + 3] - cv.w;
+                    acc = fmaf(t0, t0, acc);
+                    acc = fmaf(t1, t1, acc);
+                    acc = fmaf(t2, t2, acc);
+                    acc = fmaf(t3, t3, acc);
+                }
+            } else {
+                for (int d = l16; d < D; d += 16) {
+                    const float t = yv[d] - rowp[d];
+                    acc = fmaf(t, t, acc);
+                }
+            }
+            acc = row16_sum(acc);
+            if (l16 == 0 && i < k) dist[(int64_t)q * k + i] = acc;
+        }
+    }
+}
+
+// One workgroup per query: the row of exact distances in registers; the w-th smallest of the
+// 1 024 per-thread minima bounds the w-th smallest distance from above (tightly: the nearest
+// columns rarely share a thread); the columns at or below it are ranked by (distance, index) by
+// counting.  A row with more than SMALL_CAP such columns (masses of coinciding distances) is
+// ranked by repeated selection over the whole row instead.
+#define SMALL_CAP 1024
+
+template <int VPT>
+__global__ __launch_bounds__(1024) void k_small_cells(const float *__restrict__ dist, int k, int w,
+                                                      int32_t *__restrict__ cells, float *__restrict__ cell_dist)
+{
+    __shared__ uint32_t mins[1024];
+    __shared__ uint64_t keys[2 * SMALL_CAP];
+    __shared__ uint32_t sh_tau;
+    __shared__ int sh_n;
+    __shared__ unsigned long long sh_cut;
+    const int tid = threadIdx.x, lane = tid & 63, row = blockIdx.x;
+    const float *drow = dist + (int64_t)row * k;
+    float v[VPT];
+#pragma unroll
+    for (int e = 0; e < VPT; ++e) {
+        const int i = tid + 1024 * e;
+        v[e] = i < k ? drow[i] : INFINITY;
+    }
+    float mn = INFINITY;
+#pragma unroll
+    for (int e = 0; e < VPT; ++e) mn = fminf(mn, v[e]);
+    mins[tid] = f2ord(mn);
+    if (tid == 0) sh_n = 0;
+    __syncthreads();
+    if (tid < 64) { // one wave: the w-th smallest of the 1 024 minima, bit by bit from the top (ballot counts)
+        uint32_t u[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) u[e] = mins[lane + 64 * e];
+        uint32_t result = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = result | (1u << bit);
+            int below = 0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) below += __popcll(__ballot(u[e] < trial));
+            if (below < w) result = trial;
+        }
+        if (lane == 0) sh_tau = result;
+    }
+    __syncthreads();
+    const uint32_t tau = sh_tau;
+#pragma unroll
+    for (int e = 0; e < VPT; ++e)
+        if (f2ord(v[e]) <= tau && tid + 1024 * e < k) {
+            const int pos = atomicAdd(&sh_n, 1);
+            if (pos < SMALL_CAP) keys[pos] = make_key(v[e], (uint32_t)(tid + 1024 * e));
+        }
+    __syncthreads();
+    int cnt = sh_n;
+    if (cnt <= SMALL_CAP) {
+        // rank of every key among the (distinct) keys = its place in the output
+        const uint64_t mine = tid < cnt ? keys[tid] : KEY_MAX;
+        int rank = 0;
+        for (int c = 0; c < cnt; ++c) rank += keys[c] < mine;
+        __syncthreads();
+        if (tid < cnt) keys[rank] = mine;
+        __syncthreads();
+    } else {
+        // repeated selection: keys below the current w-th smallest are collected over the whole row; a full
+        // buffer is sorted and cut back to w
+        unsigned long long cut = KEY_MAX;
+        if (tid == 0) sh_n = 0;
+        __syncthreads();
+#pragma unroll 1
+        for (int e = 0; e < VPT; ++e) {
+            const int i = tid + 1024 * e;
+            const uint64_t key = make_key(v[e], (uint32_t)i);
+            if (i < k && key < cut) keys[atomicAdd(&sh_n, 1)] = key; // at most w + 1 024 keys: w from the last cut
+            __syncthreads();
+            const int n = sh_n;
+            __syncthreads();
+            if (n > SMALL_CAP || e == VPT - 1) {
+                const int sz = next_pow2_dev(n);
+                for (int c = n + tid; c < sz; c += 1024) keys[c] = KEY_MAX;
+                __syncthreads();
+                block_bitonic_sort<1024>(keys, sz, tid);
+                if (tid == 0) {
+                    sh_cut = n >= w ? keys[w - 1] : KEY_MAX;
+                    sh_n = min(n, w);
+                }
+                __syncthreads();
+                cut = sh_cut;
+            }
+        }
+        cnt = sh_n;
+    }
+    for (int e = tid; e < w; e += 1024) {
+        const uint64_t key = keys[e];
+        const bool ok = e < cnt && key != KEY_MAX;
+        cells[(int64_t)row * w + e] = ok ? (int32_t)(uint32_t)key : -1;
+        cell_dist[(int64_t)row * w + e] = ok ? ord2f((uint32_t)(key >> 32)) : INFINITY;
+    }
+}
+
+bool cells_small_supported(int nq, int k, int D, int w1)
+{
+    return nq <= SMALL_NQ && k >= 4096 && k <= 65536 && w1 <= 128 && (size_t)nq * D * 4 <= 65536;
+}
+
+void launch_cells_small(const float *Q, int nq, int D, const float *C, int k, int w1, float *dist, int32_t *cells,
+                        float *cell_dist, hipStream_t st)
+{
+    const size_t smem = (size_t)nq * D * 4;
+    (void)hipFuncSetAttribute((const void *)k_small_dists, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(k_small_dists, dim3((unsigned)((k + SMALL_ROWS - 1) / SMALL_ROWS)), dim3(256), smem, st, Q, nq, D, C, k, dist);
+    if (k <= 4 * 1024)
+        hipLaunchKernelGGL(k_small_cells<4>, dim3((unsigned)nq), dim3(1024), 0, st, dist, k, w1, cells, cell_dist);
+    else if (k <= 16 * 1024)
+        hipLaunchKernelGGL(k_small_cells<16>, dim3((unsigned)nq), dim3(1024), 0, st, dist, k, w1, cells, cell_dist);
+    else
+        hipLaunchKernelGGL(k_small_cells<64>, dim3((unsigned)nq), dim3(1024), 0, st, dist, k, w1, cells, cell_dist);
+}
+
 void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const float *Q, int D,
                          const float *qn, const float *C, const float *cn, int w, int self0,
                          int32_t *cells, float *cell_dist, hipStream_t st)

@@ -325,15 +325,17 @@ def test_cell_selection_with_many_centroids(vlq, oracle_mod, dup, fp32):
     idx = make_index(vlq, pr2, base=pr.X[:500])
     try:
         vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_COARSE_FP32, int(fp32))
+        dist = oracle_mod.coarse(C, Y)
         for w1 in (1, 7, 32):
-            od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y, w1, min(w1 * pr.n, 16), 10)
-            dist = oracle_mod.coarse(C, Y)
-            for q in range(len(Y)):
-                check_selection(cells[q], dict(enumerate(dist[q])), w1, what=f"w1 {w1} query {q} cells")
-                assert np.allclose(cd[q], dist[q][cells[q]], rtol=DTOL, atol=1e-3)
-            if dup:
-                ref = oracle_mod.select_smallest(dist[:20], w1)
-                assert (cells[:20] == ref).all()  # exact ties are ordered by index
+            # the whole batch, and a handful of queries (cells from rows of the fp32 distance matrix)
+            for nqs in (len(Y), 24):
+                od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y[:nqs], w1, min(w1 * pr.n, 16), 10)
+                for q in range(nqs):
+                    check_selection(cells[q], dict(enumerate(dist[q])), w1, what=f"w1 {w1} query {q} of {nqs} cells")
+                    assert np.allclose(cd[q], dist[q][cells[q]], rtol=DTOL, atol=1e-3)
+                if dup:
+                    ref = oracle_mod.select_smallest(dist[:20], w1)
+                    assert (cells[:20] == ref).all()  # exact ties are ordered by index
         if dup:
             # hundreds of exactly equal line scores (the probed cells coincide, their edges have length
             # zero, so every score is the cell distance): the cut is taken by label
@@ -386,7 +388,7 @@ def test_encode_with_coinciding_centroids(vlq, oracle_mod, fp32):
         vlq.vlq_index_free(idx)
 
 
-@pytest.mark.parametrize("dup", [0, 600])
+@pytest.mark.parametrize("dup", [0, 600, 1500])
 def test_cell_selection_with_long_column_splits(vlq, oracle_mod, dup):
     """A batch and a codebook large enough that each column split of the first sweep spans eight tiles
     or more: the sweep then bounds the w1-th smallest distance from every other tile only, and the
@@ -412,6 +414,14 @@ def test_cell_selection_with_long_column_splits(vlq, oracle_mod, dup):
                 assert np.allclose(cd[q], dist[r][cells[q]], rtol=DTOL, atol=1e-3)
             if dup:
                 assert (cells[:20] == oracle_mod.select_smallest(dist[:20], w1)).all()
+            # a handful of queries at this codebook size: exact distances to all centroids, cells straight from
+            # them (with 1500 coinciding centroids by repeated selection over the whole row)
+            od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y[:20], w1, 2 * w1, 10)
+            for q in range(20):
+                check_selection(cells[q], dict(enumerate(dist[q])), w1, what=f"w1 {w1} query {q} of 20 cells")
+                assert np.allclose(cd[q], dist[q][cells[q]], rtol=DTOL, atol=1e-3)
+            if dup:
+                assert (cells == oracle_mod.select_smallest(dist[:20], w1)).all()
     finally:
         vlq.vlq_index_free(idx)
 
@@ -436,8 +446,8 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq):
 @pytest.mark.parametrize("name", ["sift_ragged", "deep_m16"])
 def test_batch_parts_and_small_batch_forms_agree(vlq, name):
     """A batch cut into parts whose region traversal runs on the index's second stream beside the scan of
-    the part before (VLQ_OPT_PIPELINE_PARTS), and the forms a handful of queries take (fp32 distance matrix,
-    ungrouped edge products: VLQ_OPT_SMALL_BATCH) against the ordinary ones: every output identical."""
+    the part before (VLQ_OPT_PIPELINE_PARTS), and the forms a handful of queries take (exact or fp32-product
+    distance matrix, ungrouped edge products: VLQ_OPT_SMALL_BATCH) against the ordinary ones: every output identical."""
     kw, w1, w2, K = CASES[name]
     pr = problem(**kw)
     idx = make_index(vlq, pr, base=pr.X)
