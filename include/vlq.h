@@ -99,6 +99,8 @@ enum {
                                      part p + 1 running on a second stream beside the list scan of part p */
     VLQ_OPT_SMALL_BATCH,          /* default 32: batches of up to this many queries take the forms with the fewest kernel
                                      launches (fp32 distance matrix, neighbour distances per query); 0: never */
+    VLQ_OPT_COARSE_SPLIT,         /* 1: the two sweeps of the cell selection multiply split operands (two or three bf16
+                                     products per fp32 product) instead of the hi parts alone; same cells either way */
     VLQ_OPT_COUNT
 };
 

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libvlq.so")
 VLQ_OK, VLQ_EINVAL, VLQ_ENOMEM, VLQ_EHIP = 0, -1, -2, -3
 STAGES = ("coarse", "select_cells", "subregions", "scan", "merge")
 (VLQ_OPT_COARSE_FP32, VLQ_OPT_NEIGHBOURS_PER_QUERY, VLQ_OPT_SCAN_PACKED, VLQ_OPT_SCAN_GENERIC,
- VLQ_OPT_ENCODE_WAVE, VLQ_OPT_PIPELINE_PARTS, VLQ_OPT_SMALL_BATCH) = range(7)
+ VLQ_OPT_ENCODE_WAVE, VLQ_OPT_PIPELINE_PARTS, VLQ_OPT_SMALL_BATCH, VLQ_OPT_COARSE_SPLIT) = range(8)
 
 
 class VlqError(RuntimeError):

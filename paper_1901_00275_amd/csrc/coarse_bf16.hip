@@ -156,9 +156,12 @@ struct Bf16Args {
 
 // SPT = D / 16 steps per tile; PDEPTH page pairs of B in flight in registers (divides SPT, so
 // that every register set and ring half has a fixed role in the unrolled tile body).
-template <int SPT, int MODE>
+// HI: the product of the hi parts alone (search sweeps; the caller's threshold carries the wider error, see
+// k_cell_threshold): lo pages are neither loaded nor multiplied.
+template <int SPT, int MODE, bool HI>
 __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
 {
+    static_assert(!HI || MODE != MODE_NN, "the nearest-centroid mode needs the split product");
     constexpr int PDEPTH = SPT % 4 == 0 ? 4 : (SPT % 3 == 0 ? 3 : 2);
     static_assert(SPT % 2 == 0 && SPT % PDEPTH == 0, "steps per tile");
     // [A pages: SPT x 2][B ring: 2 x 2 pages]; the tail of the kernel reuses the front
@@ -173,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     const int tstride = a.tile_stride;
     const int ntl = t1 > t0 ? (t1 - t0 + tstride - 1) / tstride : 0;
     const int last = ntl * SPT - 1; // last step of the split
-    const bool use_lo = *a.a_any_lo != 0;
+    const bool use_lo = !HI && *a.a_any_lo != 0;
     u32x4 *Apages = lds;
     u32x4 *ring = lds + SPT * 2 * PAGE;
 
@@ -181,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     {
         const u32x4 *src = a.A + (int64_t)blockIdx.x * SPT * 2 * PAGE;
 #pragma unroll
-        for (int p = 0; p < SPT * 2; ++p) Apages[p * PAGE + tid] = src[p * PAGE + tid];
+        for (int p = 0; p < SPT * 2; p += HI ? 2 : 1) Apages[p * PAGE + tid] = src[p * PAGE + tid];
     }
 
     // B pages: step j of this split is step j % SPT of its (j / SPT)-th tile, the page pair at
@@ -193,14 +196,14 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
         const int jt = j / SPT;
         const int64_t pg = (int64_t)(j + jt * (tstride - 1) * SPT) * 2;
         r[0] = bsrc[pg * PAGE];
-        r[1] = bsrc[(pg + 1) * PAGE];
+        if (!HI) r[1] = bsrc[(pg + 1) * PAGE];
     };
     u32x4 rb[PDEPTH][2];
     if (ntl > 0) {
 #pragma unroll
         for (int j = 0; j < PDEPTH; ++j) fetch(rb[j], j);
         ring[tid] = rb[0][0];
-        ring[PAGE + tid] = rb[0][1];
+        if (!HI) ring[PAGE + tid] = rb[0][1];
         fetch(rb[0], PDEPTH);
     }
 
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             {
                 u32x4 *dst = ring + ((u + 1) & 1) * 2 * PAGE;
                 dst[tid] = rb[(u + 1) % PDEPTH][0];
-                dst[PAGE + tid] = rb[(u + 1) % PDEPTH][1];
+                if (!HI) dst[PAGE + tid] = rb[(u + 1) % PDEPTH][1];
                 fetch(rb[(u + 1) % PDEPTH], s + 1 + PDEPTH);
             }
             const u32x4 *ap = Apages + u * 2 * PAGE;
@@ -273,18 +276,20 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             ah[1] = ahr[u][1];
             bh[0] = __builtin_bit_cast(bf16x8, bp[fb0]);
             bh[1] = __builtin_bit_cast(bf16x8, bp[fb1]);
-            bl[0] = __builtin_bit_cast(bf16x8, bp[PAGE + fb0]);
-            bl[1] = __builtin_bit_cast(bf16x8, bp[PAGE + fb1]);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+            if (!HI) {
+                bl[0] = __builtin_bit_cast(bf16x8, bp[PAGE + fb0]);
+                bl[1] = __builtin_bit_cast(bf16x8, bp[PAGE + fb1]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+            }
             if (use_lo) {
                 bf16x8 al[2];
                 al[0] = __builtin_bit_cast(bf16x8, ap[PAGE + fa0]);
@@ -429,7 +434,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     }
 }
 
-template <int MODE>
+template <int MODE, bool HI = false>
 static int launch_mode(Bf16Args &a, hipStream_t st)
 {
     const int ntiles = (a.N + BT - 1) / BT;
@@ -447,10 +452,10 @@ static int launch_mode(Bf16Args &a, hipStream_t st)
         return 0;
     };
     switch (spt) {
-    case 2: return go(k_coarse_bf16<2, MODE>);
-    case 4: return go(k_coarse_bf16<4, MODE>);
-    case 6: return go(k_coarse_bf16<6, MODE>);
-    case 8: return go(k_coarse_bf16<8, MODE>);
+    case 2: return go(k_coarse_bf16<2, MODE, HI>);
+    case 4: return go(k_coarse_bf16<4, MODE, HI>);
+    case 6: return go(k_coarse_bf16<6, MODE, HI>);
+    case 8: return go(k_coarse_bf16<8, MODE, HI>);
     }
     return (int)hipErrorInvalidValue;
 }
@@ -500,9 +505,17 @@ int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, con
 // tau = the want-th smallest of the G group minima of a row, found bit by bit from the top of the
 // ordered bit patterns: a wave per row, every trial value is compared with all minima and the lanes
 // that lie below are counted with ballots (scalar work, no sorting, no barriers).
+//
+// Band of the hi-only product (hi_bn_max > 0: the largest squared column norm).  An operand's hi part differs from
+// it by at most 2^-9 of each component, so <a, b> - <a_h, b_h> = <a - a_h, b> + <a_h, b - b_h> is at most
+// 2^-8 |a||b| (1 + 2^-9) in size, half of that when the rows are their own hi parts (integer-valued queries); e
+// takes twice the product's error, and the fp32 accumulation of D <= 128 products adds 2 D 2^-24 |a||b|, inside the
+// 2 % the constant is rounded up by.  With B = c |a| max|b| every group minimum is at most B below its true value
+// and every column whose true value is at most tau + B shows at most tau + 2 B.
 __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict__ gmin, int G, int want, int nq,
                                                         const float *__restrict__ qn, float *__restrict__ thr,
-                                                        int32_t *__restrict__ ccnt)
+                                                        int32_t *__restrict__ ccnt, float hi_bn_max,
+                                                        const int *__restrict__ a_any_lo)
 {
     extern __shared__ uint32_t tkeys[]; // [4 waves][G]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -523,8 +536,10 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
         const float tau = ord2f(result);
         const float ra = qn[row];
         const float dt = fmaxf(tau + ra, 0.f);
+        float band = BF16_BAND_NORM * (3.f * ra + 2.f * dt);
+        if (hi_bn_max > 0.f) band = 2.f * (*a_any_lo ? 0x1p-7f : 0x1p-8f) * 1.02f * sqrtf(ra * hi_bn_max);
         // below BF16_NO_KEY, so that columns past the end never qualify
-        thr[row] = fminf(tau + BF16_BAND_NORM * (3.f * ra + 2.f * dt), BF16_NO_KEY);
+        thr[row] = fminf(tau + band, BF16_NO_KEY);
         ccnt[row] = 0;
     }
 }
@@ -632,7 +647,7 @@ __global__ __launch_bounds__(256) void k_cells_exact(const float *__restrict__ Q
     }
 }
 
-bool cells_bf16_plan(int nq, int k, int D, int w1, int *nsplit, int *cap)
+bool cells_bf16_plan(int nq, int k, int D, int w1, bool hi_only, int *nsplit, int *cap)
 {
     if (!coarse_bf16_supported(D)) return false;
     const int ntiles = (k + BT - 1) / BT;
@@ -647,7 +662,9 @@ bool cells_bf16_plan(int nq, int k, int D, int w1, int *nsplit, int *cap)
     ns = (ntiles + per - 1) / per; // no empty split
     if (ns < need) return false;
     *nsplit = ns;
-    *cap = next_pow2(4 * w1 > 256 ? 4 * w1 : 256);
+    // the hi-only sweeps list more columns (wider band): room for eight times the cells wanted
+    const int room = (hi_only ? 8 : 4) * w1;
+    *cap = next_pow2(room > (hi_only ? 512 : 256) ? room : (hi_only ? 512 : 256));
     return true;
 }
 
@@ -669,7 +686,8 @@ size_t cells_bf16_workspace(int nq, int nsplit, int cap, size_t *gmin_off, size_
 }
 
 int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, const void *Cimg, int k, int D,
-                             const float *qn, const float *cn, int w1, int nsplit, int cap, void *ws, hipStream_t st)
+                             const float *qn, const float *cn, float cn_max, bool hi_only, int w1, int nsplit, int cap,
+                             void *ws, hipStream_t st)
 {
     size_t og, ot, oc, oi;
     cells_bf16_workspace(nq, nsplit, cap, &og, &ot, &oc, &oi);
@@ -695,13 +713,13 @@ int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, cons
     // re-evaluated exactly, still well inside the candidate lists).
     const int ntiles = (k + BT - 1) / BT;
     a.tile_stride = (ntiles + nsplit - 1) / nsplit >= 8 ? 2 : 1;
-    int rc = launch_mode<MODE_MIN>(a, st);
+    int rc = hi_only ? launch_mode<MODE_MIN, true>(a, st) : launch_mode<MODE_MIN>(a, st);
     a.tile_stride = 1;
     if (rc) return rc;
     const int G = nsplit * 64;
     hipLaunchKernelGGL(k_cell_threshold, dim3((unsigned)((nq + 3) / 4)), dim3(256), (size_t)4 * G * 4, st, a.gmin, G,
-                       w1, nq, qn, (float *)(base + ot), a.ccnt);
-    return launch_mode<MODE_EMIT>(a, st);
+                       w1, nq, qn, (float *)(base + ot), a.ccnt, hi_only ? cn_max : 0.f, q_any_lo);
+    return hi_only ? launch_mode<MODE_EMIT, true>(a, st) : launch_mode<MODE_EMIT>(a, st);
 }
 
 void launch_cells_bf16_exact(const float *Q, int nq, int D, const float *C, int k, int w1, int cap, const void *ws,

@@ -447,7 +447,9 @@ def test_neighbour_distances_by_cell_and_by_query_agree(vlq):
 def test_batch_parts_and_small_batch_forms_agree(vlq, name):
     """A batch cut into parts whose region traversal runs on the index's second stream beside the scan of
     the part before (VLQ_OPT_PIPELINE_PARTS), and the forms a handful of queries take (exact or fp32-product
-    distance matrix, ungrouped edge products: VLQ_OPT_SMALL_BATCH) against the ordinary ones: every output identical."""
+    distance matrix, ungrouped edge products: VLQ_OPT_SMALL_BATCH) against the ordinary ones, and the
+    cell selection's sweeps over split operands (VLQ_OPT_COARSE_SPLIT) against the hi parts alone: every output
+    identical."""
     kw, w1, w2, K = CASES[name]
     pr = problem(**kw)
     idx = make_index(vlq, pr, base=pr.X)
@@ -469,6 +471,13 @@ def test_batch_parts_and_small_batch_forms_agree(vlq, name):
         b = gpu_search(vlq, idx, Y, w1, w2, K)
         assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2]) and np.array_equal(a[4], b[4])
         assert np.allclose(a[0], b[0], rtol=1e-6) and np.allclose(a[3], b[3], rtol=1e-6)
+        # the two sweeps of the cell selection with split operands instead of the hi parts alone: the candidate
+        # lists differ, the exact ranking of them does not
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SMALL_BATCH, 32)
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_COARSE_SPLIT, 1)
+        got = gpu_search(vlq, idx, pr.Y, w1, w2, K)
+        for x, y in zip(ref, got):
+            assert np.array_equal(x, y), "split operands"
     finally:
         vlq.vlq_index_free(idx)
 
