@@ -94,7 +94,6 @@ struct vlq_index {
     float *mu = nullptr, *mu_c = nullptr, *cn = nullptr, *Cc = nullptr;
     // kernel choices (vlq_index_set_option) and the query-side lambda range
     int opt[VLQ_OPT_COUNT] = {0, 0, -1, 0, 0, 0, 32, 0};
-    float cn_max = 0.f; // largest squared norm of a centred centroid (band of the hi-only sweeps)
     // second stream (default priority) and the events that order it against the caller's stream
     hipStream_t side = nullptr;
     hipEvent_t ev_go[VLQ_MAX_PARTS] = {}, ev_done[VLQ_MAX_PARTS] = {};
@@ -311,11 +310,6 @@ extern "C" int vlq_build_index(const vlq_params_t *params, const float *d_centro
             if (r) return r;
         }
         HIPCHK(hipStreamSynchronize(st));
-        {
-            std::vector<float> h((size_t)k);
-            HIPCHK(hipMemcpy(h.data(), idx->cn, (size_t)k * 4, hipMemcpyDeviceToHost));
-            for (float v : h) idx->cn_max = v > idx->cn_max ? v : idx->cn_max;
-        }
         return VLQ_OK;
     };
     (void)m;
@@ -973,7 +967,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
                 StageTimer t(idx, s, VLQ_STAGE_COARSE, timed);
                 launch_split_bf16(q, nqp, D, idx->mu_c, c.qimg, c.qflag, s);
                 LAUNCHCHK();
-                HIPCHK((hipError_t)launch_cells_bf16_coarse(c.qimg, c.qflag, nqp, idx->Cimg, k, D, c.qn, idx->cn, idx->cn_max,
+                HIPCHK((hipError_t)launch_cells_bf16_coarse(c.qimg, c.qflag, nqp, idx->Cimg, k, D, c.qn, idx->cn,
                                                             !idx->opt[VLQ_OPT_COARSE_SPLIT], w1, c.csplit, c.ccap, c.cws, s));
             }
             LAUNCHCHK();

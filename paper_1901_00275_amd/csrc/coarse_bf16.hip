@@ -156,8 +156,14 @@ struct Bf16Args {
 
 // SPT = D / 16 steps per tile; PDEPTH page pairs of B in flight in registers (divides SPT, so
 // that every register set and ring half has a fixed role in the unrolled tile body).
-// HI: the product of the hi parts alone (search sweeps; the caller's threshold carries the wider error, see
-// k_cell_threshold): lo pages are neither loaded nor multiplied.
+// HI: the product of the hi parts alone (search sweeps): lo pages are neither loaded nor multiplied.
+// An operand's hi part differs from it by at most 2^-9 of each component, so <a, b> - <a_h, b_h> =
+// <a - a_h, b> + <a_h, b - b_h> is at most 2^-8 |a||b| (1 + 2^-9) in size, half of that when the rows are their
+// own hi parts (integer-valued queries); e takes twice the product's error, and the fp32 accumulation of D <= 128
+// products adds 2 D 2^-24 |a||b|, inside the 2 % the constant is rounded up by.  With |a| taken as the largest
+// of the workgroup's 128 rows the error bound t of a column depends on the column alone and joins its norm:
+// MODE_MIN works on e + t (an upper bound of the true value, so the threshold drawn from the minima still has
+// enough columns at or below it), MODE_EMIT on e - t (a lower bound: no column at or below the threshold is missed).
 template <int SPT, int MODE, bool HI>
 __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
 {
@@ -177,6 +183,16 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     const int ntl = t1 > t0 ? (t1 - t0 + tstride - 1) / tstride : 0;
     const int last = ntl * SPT - 1; // last step of the split
     const bool use_lo = !HI && *a.a_any_lo != 0;
+    // (kept in a lo page of the ring, which the hi-only form never fills: the operand pages take the
+    // whole 80 KB that let two workgroups share a compute unit)
+    float *strip_max = (float *)(lds + (SPT * 2 + 1) * PAGE);
+    if (HI) {
+        const int64_t row = m0 + (tid & (BT - 1));
+        float v = row < a.M ? a.an[row] : 0.f;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+        if (lane == 0) strip_max[wave] = v;
+    }
     u32x4 *Apages = lds;
     u32x4 *ring = lds + SPT * 2 * PAGE;
 
@@ -240,6 +256,10 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     __syncthreads();
+    float hi_band = 0.f; // error bound of e per unit of |b|
+    if (HI)
+        hi_band = sqrtf(fmaxf(fmaxf(strip_max[0], strip_max[1]), fmaxf(strip_max[2], strip_max[3]))) *
+                  (*a.a_any_lo ? 0x1p-7f : 0x1p-8f) * 1.02f * (MODE == MODE_MIN ? 1.f : -1.f);
     // the hi fragments of the wave's 64 rows for all steps: the same for every tile, kept in registers
     bf16x8 ahr[SPT][2];
 #pragma unroll
@@ -257,6 +277,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
         for (int j = 0; j < 2; ++j) {
             const int64_t col = n0 + wn + 32 * j + (lane & 31);
             cb[j] = a.bn[min(col, (int64_t)a.N - 1)];
+            if (HI) cb[j] = fmaf(hi_band, sqrtf(fmaxf(cb[j], 0.f)), cb[j]);
             cb[j] = col < a.N ? cb[j] : BF16_NO_COLUMN;
         }
 #pragma unroll
@@ -505,17 +526,11 @@ int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, con
 // tau = the want-th smallest of the G group minima of a row, found bit by bit from the top of the
 // ordered bit patterns: a wave per row, every trial value is compared with all minima and the lanes
 // that lie below are counted with ballots (scalar work, no sorting, no barriers).
-//
-// Band of the hi-only product (hi_bn_max > 0: the largest squared column norm).  An operand's hi part differs from
-// it by at most 2^-9 of each component, so <a, b> - <a_h, b_h> = <a - a_h, b> + <a_h, b - b_h> is at most
-// 2^-8 |a||b| (1 + 2^-9) in size, half of that when the rows are their own hi parts (integer-valued queries); e
-// takes twice the product's error, and the fp32 accumulation of D <= 128 products adds 2 D 2^-24 |a||b|, inside the
-// 2 % the constant is rounded up by.  With B = c |a| max|b| every group minimum is at most B below its true value
-// and every column whose true value is at most tau + B shows at most tau + 2 B.
+// (The hi-only sweeps carry their own, wider error inside the values they compare; the band added here is that
+// of the fp32 arithmetic and of the split product, which the hi-only bound exceeds by far.)
 __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict__ gmin, int G, int want, int nq,
                                                         const float *__restrict__ qn, float *__restrict__ thr,
-                                                        int32_t *__restrict__ ccnt, float hi_bn_max,
-                                                        const int *__restrict__ a_any_lo)
+                                                        int32_t *__restrict__ ccnt)
 {
     extern __shared__ uint32_t tkeys[]; // [4 waves][G]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -536,10 +551,8 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
         const float tau = ord2f(result);
         const float ra = qn[row];
         const float dt = fmaxf(tau + ra, 0.f);
-        float band = BF16_BAND_NORM * (3.f * ra + 2.f * dt);
-        if (hi_bn_max > 0.f) band = 2.f * (*a_any_lo ? 0x1p-7f : 0x1p-8f) * 1.02f * sqrtf(ra * hi_bn_max);
         // below BF16_NO_KEY, so that columns past the end never qualify
-        thr[row] = fminf(tau + band, BF16_NO_KEY);
+        thr[row] = fminf(tau + BF16_BAND_NORM * (3.f * ra + 2.f * dt), BF16_NO_KEY);
         ccnt[row] = 0;
     }
 }
@@ -686,8 +699,8 @@ size_t cells_bf16_workspace(int nq, int nsplit, int cap, size_t *gmin_off, size_
 }
 
 int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, const void *Cimg, int k, int D,
-                             const float *qn, const float *cn, float cn_max, bool hi_only, int w1, int nsplit, int cap,
-                             void *ws, hipStream_t st)
+                             const float *qn, const float *cn, bool hi_only, int w1, int nsplit, int cap, void *ws,
+                             hipStream_t st)
 {
     size_t og, ot, oc, oi;
     cells_bf16_workspace(nq, nsplit, cap, &og, &ot, &oc, &oi);
@@ -718,7 +731,7 @@ int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, cons
     if (rc) return rc;
     const int G = nsplit * 64;
     hipLaunchKernelGGL(k_cell_threshold, dim3((unsigned)((nq + 3) / 4)), dim3(256), (size_t)4 * G * 4, st, a.gmin, G,
-                       w1, nq, qn, (float *)(base + ot), a.ccnt, hi_only ? cn_max : 0.f, q_any_lo);
+                       w1, nq, qn, (float *)(base + ot), a.ccnt);
     return hi_only ? launch_mode<MODE_EMIT, true>(a, st) : launch_mode<MODE_EMIT>(a, st);
 }
 

@@ -207,14 +207,14 @@ int launch_coarse_gemm_nn_bf16(const void *Aimg, const int *a_any_lo, int M, con
 // split count and the candidate capacity per query; the workspace holds group minima,
 // thresholds, candidate counts and candidate lists.  launch_cells_bf16_coarse runs both sweeps
 // (return value 0 or a hipError_t), launch_cells_bf16_exact ranks the candidates exactly.
-// hi_only: both sweeps multiply the hi parts alone (a third to a half of the products; cn_max, the largest
-// squared column norm, sizes the wider band of the second sweep).
+// hi_only: both sweeps multiply the hi parts alone (a third to a half of the products) and carry that product's
+// error bound inside the values they compare.
 bool cells_bf16_plan(int nq, int k, int D, int w1, bool hi_only, int *nsplit, int *cap);
 size_t cells_bf16_workspace(int nq, int nsplit, int cap, size_t *gmin_off, size_t *thr_off, size_t *ccnt_off,
                             size_t *cidx_off);
 int launch_cells_bf16_coarse(const void *Qimg, const int *q_any_lo, int nq, const void *Cimg, int k, int D,
-                             const float *qn, const float *cn, float cn_max, bool hi_only, int w1, int nsplit, int cap,
-                             void *ws, hipStream_t st);
+                             const float *qn, const float *cn, bool hi_only, int w1, int nsplit, int cap, void *ws,
+                             hipStream_t st);
 void launch_cells_bf16_exact(const float *Q, int nq, int D, const float *C, int k, int w1, int cap, const void *ws,
                              int nsplit, int32_t *cells, float *cell_dist, int32_t *pair_cnt, int32_t *pair_rank,
                              hipStream_t st);
