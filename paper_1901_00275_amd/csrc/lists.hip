@@ -51,21 +51,36 @@ void launch_list_histogram(const int32_t *label, int64_t N, int32_t *cnt, hipStr
     hipLaunchKernelGGL(k_list_histogram, dim3((unsigned)blocks), dim3(256), 0, st, label, N, cnt);
 }
 
-// off[i] = sum of cnt[0..i), off[nl] = total; one workgroup walks the array in tiles of 4096
-// (four consecutive counts per thread, so loads and stores are coalesced), carrying the sum.
+// off[i] = sum of cnt[0..i), off[nl] = total; one workgroup walks the array in tiles of 16 384
+// (sixteen consecutive counts per thread: few rounds, each with two barriers), carrying the sum.
+#define XS_PER 16
 __global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restrict__ cnt, int64_t nl,
                                                          int64_t *__restrict__ off)
 {
     __shared__ int64_t wsum[16];
     __shared__ int64_t carry_sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool vec = ((uintptr_t)cnt) % 16 == 0;
     int64_t carry = 0;
-    for (int64_t t0 = 0; t0 < nl; t0 += 4096) {
-        const int64_t i0 = t0 + 4 * tid;
-        int32_t c[4];
+    for (int64_t t0 = 0; t0 < nl; t0 += 1024 * XS_PER) {
+        const int64_t i0 = t0 + XS_PER * tid;
+        int32_t c[XS_PER];
+        if (vec && i0 + XS_PER <= nl) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) c[e] = i0 + e < nl ? cnt[i0 + e] : 0;
-        const int64_t mine = (int64_t)c[0] + c[1] + c[2] + c[3];
+            for (int e = 0; e < XS_PER; e += 4) {
+                const int4 v = *(const int4 *)(cnt + i0 + e);
+                c[e] = v.x;
+                c[e + 1] = v.y;
+                c[e + 2] = v.z;
+                c[e + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < XS_PER; ++e) c[e] = i0 + e < nl ? cnt[i0 + e] : 0;
+        }
+        int64_t mine = 0;
+#pragma unroll
+        for (int e = 0; e < XS_PER; ++e) mine += c[e];
         int64_t inc = mine; // inclusive scan over the wave
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -78,7 +93,7 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restri
         for (int w = 0; w < wave; ++w) before += wsum[w];
         int64_t run = before + inc - mine;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < XS_PER; ++e) {
             if (i0 + e < nl) off[i0 + e] = run;
             run += c[e];
         }

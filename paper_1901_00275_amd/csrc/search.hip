@@ -453,47 +453,44 @@ __global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, co
     }
 }
 
-#define ND_PCH 32 // most pairs per workgroup
+#define ND_PCH 32 // pairs taken up at a time
 
-// The pairs, ordered by cell, are cut into runs of ND_PCH; a workgroup walks its run cell by
-// cell (a popular cell spreads over many workgroups, a run of rarely probed cells costs one
-// reload of the rows per cell).  A wave per pair, four rows per pass.
+// Grouped (pairs != nullptr): a workgroup per cell brings the cell's rows into LDS once and walks the
+// cell's pairs in chunks of ND_PCH (cells nobody probes leave at once).  Ungrouped (small batches): a
+// workgroup per pair, in the pairs' own order, np_all of them.  A wave per pair, four rows per pass.
 __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict__ Q, int D,
                                                          const float *__restrict__ C,
                                                          const int32_t *__restrict__ S, int n, int k, int w1,
-                                                         int pch, const int32_t *__restrict__ cells,
+                                                         const int32_t *__restrict__ cells,
                                                          const int64_t *__restrict__ poff,
                                                          const int32_t *__restrict__ pairs, int64_t np_all,
                                                          float *__restrict__ bq)
 {
-    // pairs == nullptr: the pairs are taken in their own order, ungrouped (small batches: np_all of them)
     extern __shared__ float nrows[]; // [n][D] edge vectors s_ij - c_i, then [D] the centroid c_i
-    __shared__ int sp[ND_PCH], sc[ND_PCH];
+    __shared__ int sp[ND_PCH];
     float *crow = nrows + (size_t)n * D;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane >> 4, l16 = lane & 15;
-    const int64_t np = pairs ? poff[k] : np_all; // pairs with a valid cell
-    const int64_t pbeg = (int64_t)blockIdx.x * pch;
-    if (pbeg >= np) return;
-    const int cntp = (int)min((int64_t)pch, np - pbeg);
-    if (tid < cntp) {
-        const int p = pairs ? pairs[pbeg + tid] : (int)(pbeg + tid);
-        sp[tid] = p;
-        sc[tid] = cells[p];
+    int64_t pbeg, pend;
+    int cell;
+    if (pairs) {
+        cell = blockIdx.x;
+        pbeg = poff[cell];
+        pend = poff[cell + 1];
+        if (pbeg >= pend) return;
+    } else {
+        pbeg = blockIdx.x;
+        pend = pbeg + 1;
+        if (pbeg >= np_all) return;
+        cell = cells[pbeg];
+        if (cell < 0) return; // a query with fewer than w1 cells
     }
-    __syncthreads();
-    if (!pairs && sc[0] < 0) return; // (ungrouped runs hold one pair; a query with fewer than w1 cells)
     const bool vec = (D % 4 == 0) && ((((uintptr_t)C) | ((uintptr_t)Q)) % 16 == 0);
     const bool fast = vec && D <= 128;
     const int d0 = l16 * 4, d1 = 64 + l16 * 4;
     const bool has0 = fast && d0 < D, has1 = fast && d1 < D;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    int i = 0;
-    while (i < cntp) {
-        const int cell = sc[i];
-        int e = i + 1;
-        while (e < cntp && sc[e] == cell) ++e;
-        __syncthreads(); // the previous cell's rows are no longer read
+    {
         const float *cg = C + (int64_t)cell * D;
         if (vec) {
             const int d4 = D / 4;
@@ -513,6 +510,11 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                 nrows[t] = j < n ? C[(int64_t)S[(int64_t)cell * n + j] * D + d] - cg[d] : cg[d];
             }
         }
+    }
+    for (int64_t ch = pbeg; ch < pend; ch += ND_PCH) {
+        const int i = 0, e = (int)min((int64_t)ND_PCH, pend - ch);
+        __syncthreads(); // rows staged; the previous chunk's pair list no longer read
+        if (tid < e) sp[tid] = pairs ? pairs[ch + tid] : (int)(ch + tid);
         __syncthreads();
         if (fast) {
             // two pairs of the cell per wave where there are that many: a row read from LDS serves both
@@ -602,7 +604,6 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                 if (l16 == 0 && j < n) bq[(int64_t)p * n + j] = acc;
             }
         }
-        i = e;
     }
 }
 
@@ -677,13 +678,8 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         const size_t rows_bytes = (size_t)(n + 1) * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
-        // runs of 32 pairs for large batches; shorter runs (down to one pair per workgroup) keep
-        // all CUs busy when the batch is small
-        int pch = (int)(np / 1024);
-        pch = pch < 1 ? 1 : (pch > ND_PCH ? ND_PCH : pch);
-        if (!grouped) pch = 1;
-        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)((np + pch - 1) / pch)), dim3(256), rows_bytes, st, Q, D,
-                           C, S, n, k, w1, pch, cells, poff, grouped ? pairs : nullptr, np, bq);
+        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)(grouped ? (int64_t)k : np)), dim3(256), rows_bytes, st, Q,
+                           D, C, S, n, k, w1, cells, poff, grouped ? pairs : nullptr, np, bq);
         bpre = bq;
     }
     int sz = next_pow2(w1 * n);
