@@ -103,9 +103,60 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restri
     }
     if (tid == 0) off[nl] = carry;
 }
+// The same for short arrays (the per-cell pair counts of a search) without the serial walk: a workgroup per
+// 4 096 counts first adds up everything before its tile (read again by every later workgroup: a few
+// hundred KB from L2 at most), then scans its own tile.
+#define XB_TILE 4096
+__global__ __launch_bounds__(256) void k_exclusive_scan_tiles(const int32_t *__restrict__ cnt, int64_t nl,
+                                                              int64_t *__restrict__ off)
+{
+    __shared__ int64_t wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t t0 = (int64_t)blockIdx.x * XB_TILE;
+    int64_t before = 0;
+    for (int64_t i = 4 * tid; i < t0; i += XB_TILE) { // t0 is a multiple of the tile: four loads in flight
+        int4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *(const int4 *)(cnt + i + 1024 * u);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) before += (int64_t)v[u].x + v[u].y + v[u].z + v[u].w;
+    }
+    const int64_t i0 = t0 + XS_PER * tid;
+    int32_t c[XS_PER];
+#pragma unroll
+    for (int e = 0; e < XS_PER; ++e) c[e] = i0 + e < nl ? cnt[i0 + e] : 0;
+    int64_t mine = 0;
+#pragma unroll
+    for (int e = 0; e < XS_PER; ++e) mine += c[e];
+    // the sum of `before` over the workgroup, and the scan of `mine`
+    int64_t inc = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int64_t v = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += v;
+        before += __shfl_xor(before, o, 64);
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __shared__ int64_t bsum[4];
+    if (lane == 0) bsum[wave] = before;
+    __syncthreads();
+    int64_t run = bsum[0] + bsum[1] + bsum[2] + bsum[3] + inc - mine;
+    for (int w = 0; w < wave; ++w) run += wsum[w];
+#pragma unroll
+    for (int e = 0; e < XS_PER; ++e) {
+        if (i0 + e < nl) off[i0 + e] = run;
+        run += c[e];
+    }
+    if (i0 <= nl - 1 && nl - 1 < i0 + XS_PER) off[nl] = run; // the thread that holds the last count
+}
+
 void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, cnt, nl, off);
+    if (nl > 0 && nl <= ((int64_t)1 << 18) && ((uintptr_t)cnt) % 16 == 0)
+        hipLaunchKernelGGL(k_exclusive_scan_tiles, dim3((unsigned)((nl + XB_TILE - 1) / XB_TILE)), dim3(256), 0, st, cnt,
+                           nl, off);
+    else
+        hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, cnt, nl, off);
 }
 
 __global__ void k_list_scatter(const int32_t *__restrict__ label, const int32_t *__restrict__ st_ids,
