@@ -579,6 +579,38 @@ __device__ __forceinline__ float sqdist16(const float *yv, const float *__restri
     return row16_sum(acc);
 }
 
+// the same sums for four rows at once (their loads in flight together)
+__device__ __forceinline__ void sqdist16x4(const float *yv, const float *const (&rowp)[4], int D, int l16, bool vec,
+                                           float (&out)[4])
+{
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (vec) {
+        for (int d = l16 * 4; d < D; d += 64) {
+            f32x4 cv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cv[u] = *(const f32x4 *)(rowp[u] + d);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float t0 = yv[d] - cv[u].x, t1 = yv[d + 1] - cv[u].y, t2 = yv[d + 2] - cv[u].z, t3 = yv[d + 3] - cv[u].w;
+                acc[u] = fmaf(t0, t0, acc[u]);
+                acc[u] = fmaf(t1, t1, acc[u]);
+                acc[u] = fmaf(t2, t2, acc[u]);
+                acc[u] = fmaf(t3, t3, acc[u]);
+            }
+        }
+    } else {
+        for (int d = l16; d < D; d += 16) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float t = yv[d] - rowp[u][d];
+                acc[u] = fmaf(t, t, acc[u]);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) out[u] = row16_sum(acc[u]);
+}
+
 #define CELLS_FB 2048 // buffer of the exact ranking over all columns
 
 __global__ __launch_bounds__(256) void k_cells_exact(const float *__restrict__ Q, int D,
@@ -602,11 +634,22 @@ __global__ __launch_bounds__(256) void k_cells_exact(const float *__restrict__ Q
     __syncthreads();
     if (listed <= cap) {
         cnt = listed;
-        for (int c0 = wave * 4; c0 < cnt; c0 += 16) {
-            const int c = c0 + sub16;
-            const int i = c < cnt ? cidx[(int64_t)row * cap + c] : 0;
-            const float d = sqdist16(yv, C + (int64_t)i * D, D, l16, vec);
-            if (l16 == 0 && c < cnt) ckeys[c] = make_key(d, (uint32_t)i);
+        for (int c0 = wave * 4; c0 < cnt; c0 += 64) { // four candidates per 16 lanes and round
+            int ii[4];
+            const float *rp[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 16 * u + sub16;
+                ii[u] = c < cnt ? cidx[(int64_t)row * cap + c] : 0;
+                rp[u] = C + (int64_t)ii[u] * D;
+            }
+            float dd[4];
+            sqdist16x4(yv, rp, D, l16, vec, dd);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 16 * u + sub16;
+                if (l16 == 0 && c < cnt) ckeys[c] = make_key(dd[u], (uint32_t)ii[u]);
+            }
         }
         __syncthreads();
         if (cnt <= 256) {

@@ -419,6 +419,157 @@ __global__ __launch_bounds__(256) void k_subregions(const float *__restrict__ Q,
 }
 
 // ---------------------------------------------------------------------------
+// The same selection when only the scan's descriptors are asked for and the products g are there
+// already (large batches): the w1*n keys of a query stay in registers, KPT consecutive ones per
+// thread.  The cut, i.e. the w2-th smallest (score, label), is found bit by bit from the top of the
+// ordered score pattern: every trial value is compared with all keys, the keys below it are
+// counted with ballots and the four wave counts meet in LDS (one barrier per bit); scores equal to
+// the cut's are then separated by label the same way.  The selected sub-regions keep the order of
+// their positions (nearer cells first, which tightens the scan's bound early).
+// ---------------------------------------------------------------------------
+template <int KPT>
+__global__ __launch_bounds__(256) void k_subregions_lean(const float *__restrict__ E, int n,
+                                                         const int32_t *__restrict__ cells,
+                                                         const float *__restrict__ cell_dist, int w1, int w2,
+                                                         float lam_min, float lam_max,
+                                                         const int64_t *__restrict__ off,
+                                                         uint4 *__restrict__ desc,
+                                                         const float *__restrict__ bpre)
+{
+    extern __shared__ uint32_t picked[]; // [w2] {label, b - a, probed cell} of the selected sub-regions
+    __shared__ int slot[2][4];
+    __shared__ int sh4[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = blockIdx.x;
+    const int total = w1 * n;
+    uint32_t o[KPT];     // ordered score bits; 0xFFFFFFFF = no sub-region
+    uint32_t label[KPT];
+    float bma[KPT];      // b - a = c - 2 g for the scan
+    const int tb = tid * KPT;
+    {
+        // all loads without branches (indices clamped), so that they are in flight together
+        int ci[KPT];
+        float gv[KPT], av[KPT], cv[KPT];
+#pragma unroll
+        for (int e = 0; e < KPT; ++e) {
+            const int t = min(tb + e, total - 1);
+            ci[e] = cells[(int64_t)q * w1 + t / n];
+            av[e] = cell_dist[(int64_t)q * w1 + t / n];
+            gv[e] = bpre[(int64_t)q * total + t];
+        }
+#pragma unroll
+        for (int e = 0; e < KPT; ++e) {
+            const int t = min(tb + e, total - 1);
+            cv[e] = E[(int64_t)max(ci[e], 0) * n + (t - (t / n) * n)];
+        }
+#pragma unroll
+        for (int e = 0; e < KPT; ++e) {
+            const int t = tb + e;
+            const bool ok = t < total && ci[e] >= 0;
+            const float c = cv[e];
+            const float lam = c > 0.f ? gv[e] / c : 0.f;
+            float score = av[e] - gv[e] * lam;
+            const float lc = fminf(fmaxf(lam, lam_min), lam_max);
+            if (lc != lam) score = fmaf(c * (lc - lam), lc - lam, score);
+            label[e] = ok ? (uint32_t)(ci[e] * n + (t - (t / n) * n)) : 0xFFFFFFFFu;
+            // (a score whose pattern is all ones would count as absent below: one step down keeps it present)
+            o[e] = ok ? min(f2ord(score), 0xFFFFFFFEu) : 0xFFFFFFFFu;
+            bma[e] = fmaf(-2.f, gv[e], c);
+        }
+    }
+    // sum of a wave-uniform count over the four waves; `round` alternates the LDS slots, so one
+    // barrier per call is enough
+    int round = 0;
+    auto block_sum = [&](int v) {
+        if (lane == 0) slot[round & 1][wave] = v;
+        __syncthreads();
+        const int r = slot[round & 1][0] + slot[round & 1][1] + slot[round & 1][2] + slot[round & 1][3];
+        ++round;
+        return r;
+    };
+    int nv = 0;
+#pragma unroll
+    for (int e = 0; e < KPT; ++e) nv += __popcll(__ballot(o[e] != 0xFFFFFFFFu));
+    const int nvalid = block_sum(nv);
+    const int w2eff = min(w2, nvalid);
+    uint32_t vcut = 0, lcut = 0xFFFFFFFFu;
+    if (w2eff > 0) {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = vcut | (1u << bit);
+            int below = 0;
+#pragma unroll
+            for (int e = 0; e < KPT; ++e) below += __popcll(__ballot(o[e] < trial)); // absent keys are below nothing
+            if (block_sum(below) < w2eff) vcut = trial;
+        }
+        int less = 0, equal = 0;
+#pragma unroll
+        for (int e = 0; e < KPT; ++e) {
+            less += __popcll(__ballot(o[e] < vcut));
+            equal += __popcll(__ballot(o[e] == vcut));
+        }
+        less = block_sum(less);
+        equal = block_sum(equal);
+        const int need = w2eff - less; // of the keys with the cut's score, the smallest labels
+        if (equal > need) {
+            lcut = 0;
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = lcut | (1u << bit);
+                int below = 0;
+#pragma unroll
+                for (int e = 0; e < KPT; ++e)
+                    below += __popcll(__ballot(o[e] == vcut && label[e] < trial));
+                if (block_sum(below) < need) lcut = trial;
+            }
+        }
+    }
+    // the selected keys, in position order, into LDS
+    int mysel = 0;
+#pragma unroll
+    for (int e = 0; e < KPT; ++e) {
+        const bool sel = w2eff > 0 && (o[e] < vcut || (o[e] == vcut && label[e] <= lcut));
+        mysel += sel;
+    }
+    int base = wave_incl_scan(mysel, lane);
+    if (lane == 63) sh4[wave] = base;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) base += sh4[w];
+    base -= mysel;
+#pragma unroll
+    for (int e = 0; e < KPT; ++e) {
+        const bool sel = w2eff > 0 && (o[e] < vcut || (o[e] == vcut && label[e] <= lcut));
+        if (sel && base < w2) { // (exactly w2eff keys are selected; the bound is a safeguard)
+            picked[3 * base] = label[e];
+            picked[3 * base + 1] = __float_as_uint(bma[e]);
+            picked[3 * base + 2] = (uint32_t)((tb + e) / n);
+            ++base;
+        }
+    }
+    __syncthreads();
+    // descriptors: a thread per selected sub-region, four at a time (their offset loads in flight together)
+    for (int r0 = tid; r0 < w2; r0 += 1024) {
+        uint32_t lb[4];
+        int64_t b0[4], b1[4];
+        float a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = r0 + 256 * u;
+            lb[u] = r < w2eff ? picked[3 * r] : 0u;
+            b0[u] = off[lb[u]];
+            b1[u] = off[lb[u] + 1];
+            a[u] = cell_dist[(int64_t)q * w1 + (r < w2eff ? picked[3 * r + 2] : 0u)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = r0 + 256 * u;
+            if (r < w2)
+                desc[(int64_t)q * w2 + r] = r < w2eff ? make_uint4((uint32_t)b0[u], (uint32_t)(b1[u] - b0[u]),
+                                                                  __float_as_uint(a[u]), picked[3 * r + 1])
+                                                      : make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // g = <y - c_i, s_ij - c_i> cell by cell (Alg. 3, second loop: the numerator of Eq. 8, from which
 // b = a + c - 2 g follows).  A batch of queries probes most cells several times; the (query, probed
 // cell) pairs are grouped by cell, a workgroup brings the centroid of its cell and the n edge vectors
@@ -686,6 +837,21 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
     if (sz < next_pow2(w2)) sz = next_pow2(w2);
     if (sz < 2) sz = 2;
     const bool lean = bpre && !sub && !sub_score && !scan_label;
+    if (lean && desc && w1 * n <= 4096) {
+        // keys in registers: 4, 8 or 16 per thread
+        const int total = w1 * n;
+        const size_t pk = (size_t)w2 * 12;
+        if (total <= 1024)
+            hipLaunchKernelGGL(k_subregions_lean<4>, dim3((unsigned)nq), dim3(256), pk, st, E, n, cells, cell_dist, w1, w2,
+                               lam_min, lam_max, off, desc, bpre);
+        else if (total <= 2048)
+            hipLaunchKernelGGL(k_subregions_lean<8>, dim3((unsigned)nq), dim3(256), pk, st, E, n, cells, cell_dist, w1, w2,
+                               lam_min, lam_max, off, desc, bpre);
+        else
+            hipLaunchKernelGGL(k_subregions_lean<16>, dim3((unsigned)nq), dim3(256), pk, st, E, n, cells, cell_dist, w1, w2,
+                               lam_min, lam_max, off, desc, bpre);
+        return;
+    }
     size_t smem = lean ? (size_t)sz * (8 + 4) : (size_t)sz * (8 + 4 + 2 + 4) + (size_t)D * 4;
     (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
