@@ -247,13 +247,9 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
         }
     const uint32_t keep = MODE == MODE_NN ? ~((1u << a.idx_bits) - 1u) : 0xFFFFFFFFu;
 
+    // (the first product of a tile starts from a constant zero, so the accumulators are never cleared)
     f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     __syncthreads();
     float hi_band = 0.f; // error bound of e per unit of |b|
@@ -301,7 +297,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], u == 0 ? zero16 : acc[i][j], 0, 0, 0);
             if (!HI) {
                 bl[0] = __builtin_bit_cast(bf16x8, bp[PAGE + fb0]);
                 bl[1] = __builtin_bit_cast(bf16x8, bp[PAGE + fb1]);
@@ -324,7 +320,9 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             __syncthreads();
         }
         // ---- tile finished ----
-        uint64_t hits = 0; // MODE_EMIT: bit (2 j + i) * 16 + r
+        // MODE_EMIT: a column qualifies when thr - e = (thr - ||b||^2) + 2 <a, b> is not negative; the sign bits
+        // are shifted into one word per column half, element (i, r) ending at bit 31 - (16 i + r)
+        uint32_t miss[2] = {0u, 0u};
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t tj = (uint32_t)(tl * 2 + j);
@@ -332,17 +330,19 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float e = fmaf(-2.f, acc[i][j][r], cb[j]);
-                    if (MODE == MODE_NN) {
-                        const float key = __uint_as_float((__float_as_uint(e) & keep) | tj);
-                        b2[i][r] = __builtin_amdgcn_fmed3f(b1[i][r], b2[i][r], key);
-                        b1[i][r] = fminf(b1[i][r], key);
-                    } else if (MODE == MODE_MIN) {
-                        b1[i][r] = fminf(b1[i][r], e);
+                    if (MODE == MODE_EMIT) {
+                        const float t = fmaf(2.f, acc[i][j][r], b1[i][r] - cb[j]);
+                        miss[j] = __builtin_amdgcn_alignbit(miss[j], __float_as_uint(t), 31);
                     } else {
-                        hits |= e <= b1[i][r] ? 1ull << ((2 * j + i) * 16 + r) : 0ull;
+                        const float e = fmaf(-2.f, acc[i][j][r], cb[j]);
+                        if (MODE == MODE_NN) {
+                            const float key = __uint_as_float((__float_as_uint(e) & keep) | tj);
+                            b2[i][r] = __builtin_amdgcn_fmed3f(b1[i][r], b2[i][r], key);
+                            b1[i][r] = fminf(b1[i][r], key);
+                        } else {
+                            b1[i][r] = fminf(b1[i][r], e);
+                        }
                     }
-                    acc[i][j][r] = 0.f;
                 }
         }
         if (MODE == MODE_EMIT) {
@@ -352,10 +352,11 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
             if (pend_row >= 0 && pend_pos < a.cap) a.cidx[pend_row * a.cap + pend_pos] = pend_col;
             pend_row = -1;
             bool first = true;
+            uint64_t hits = ((uint64_t)~miss[1] << 32) | (uint32_t)~miss[0];
             while (hits) {
                 const int bit = __ffsll((unsigned long long)hits) - 1;
                 hits &= hits - 1;
-                const int j = bit >> 5, i = (bit >> 4) & 1, r = bit & 15;
+                const int j = bit >> 5, el = 31 - (bit & 31), i = el >> 4, r = el & 15;
                 const int64_t row = m0 + slot_row(i, r);
                 const int col = (int)n0 + wn + 32 * j + (lane & 31);
                 const int pos = atomicAdd(&a.ccnt[row], 1);
