@@ -641,18 +641,39 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
     const int d0 = l16 * 4, d1 = 64 + l16 * 4;
     const bool has0 = fast && d0 < D, has1 = fast && d1 < D;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    // the first chunk's pairs are asked for now, beside the rows
+    int first_p = 0;
+    if (tid < min((int64_t)ND_PCH, pend - pbeg)) first_p = pairs ? pairs[pbeg + tid] : (int)(pbeg + tid);
     {
         const float *cg = C + (int64_t)cell * D;
         if (vec) {
-            const int d4 = D / 4;
-            for (int t = tid; t < (n + 1) * d4; t += 256) {
-                const int j = t / d4, c = t - j * d4;
-                const f32x4 cv = ((const f32x4 *)cg)[c];
-                if (j < n) {
-                    const int s = S[(int64_t)cell * n + j];
-                    ((f32x4 *)nrows)[t] = ((const f32x4 *)(C + (int64_t)s * D))[c] - cv;
-                } else {
-                    ((f32x4 *)nrows)[t] = cv;
+            // eight items per thread and pass, all index loads first, then all row loads, so that a pass
+            // costs two round trips
+            const int d4 = D / 4, items = (n + 1) * d4;
+            for (int t0 = tid; t0 < items; t0 += 256 * 8) {
+                int jj[8], cc[8], ss[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t0 + 256 * u;
+                    jj[u] = t / d4;
+                    cc[u] = t - jj[u] * d4;
+                    ss[u] = cell;
+                    if (t < items && jj[u] < n) ss[u] = S[(int64_t)cell * n + jj[u]];
+                }
+                f32x4 rv[8], cv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    rv[u] = zero;
+                    cv[u] = zero;
+                    if (t0 + 256 * u < items) {
+                        rv[u] = ((const f32x4 *)(C + (int64_t)ss[u] * D))[cc[u]];
+                        cv[u] = ((const f32x4 *)cg)[cc[u]];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t0 + 256 * u;
+                    if (t < items) ((f32x4 *)nrows)[t] = jj[u] < n ? rv[u] - cv[u] : cv[u];
                 }
             }
         } else {
@@ -665,7 +686,7 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
     for (int64_t ch = pbeg; ch < pend; ch += ND_PCH) {
         const int i = 0, e = (int)min((int64_t)ND_PCH, pend - ch);
         __syncthreads(); // rows staged; the previous chunk's pair list no longer read
-        if (tid < e) sp[tid] = pairs ? pairs[ch + tid] : (int)(ch + tid);
+        if (tid < e) sp[tid] = ch == pbeg ? first_p : (pairs ? pairs[ch + tid] : (int)(ch + tid));
         __syncthreads();
         if (fast) {
             // two pairs of the cell per wave where there are that many: a row read from LDS serves both
