@@ -275,7 +275,7 @@ def main():
                                    "peak_tflops": BF16_PEAK_TFLOPS,
                                    "frac": coarse_flop / max(coarse_s, 1e-12) / 1e12 / BF16_PEAK_TFLOPS,
                                    "note": "2 nq k D flop of Alg. 3's first loop over the time of both sweeps of the "
-                                           "split-bf16 product (which issue 2-3 bf16 products per fp32 product)"}},
+                                           "bf16 product (hi parts of the split operands; the first sweep visits every other tile)"}},
         "roofline": {"bound": "hbm", "kernel": "k_scan_stream", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": scan_avg_s * 1e3,

@@ -7,7 +7,9 @@
 // together stay below 3 * 2^-18 |x| |c|.  The result only shortlists centroids: every
 // column whose approximate distance lies within the error band of the row minimum
 // is handed on and re-evaluated there as a direct fp32 sum of squared differences,
-// so the decision itself is taken in fp32 exactly as by the fp32 path.
+// so the decision itself is taken in fp32 exactly as by the fp32 path.  The two sweeps of the search's
+// cell selection multiply the hi parts alone and carry the (much wider, still rigorous) error bound of
+// that product per column inside the values they compare; see the kernel's HI parameter.
 //
 // Operand images.  Both operands are first rewritten (k_split_bf16) into the exact
 // byte image the product kernel wants in LDS: rows in blocks of 128, the contraction

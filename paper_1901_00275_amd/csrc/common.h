@@ -249,6 +249,8 @@ struct PairWs {
     int64_t *poff;  // [k + 1]
     int32_t *rank;  // [nq x w1]
     int32_t *pairs; // [nq x w1]
+    int64_t *woff;  // [k + 1] work items (a cell's pairs in chunks) before each cell
+    int2 *work;     // [nq x w1 / chunk + k] {cell, chunk}
     float *bq;      // [nq x w1 x n]
 };
 PairWs neighbour_dists_carve(void *ws, int nq, int k, int n, int w1);
@@ -324,6 +326,8 @@ void launch_pack_labels(const int32_t *cell, const int32_t *edge, int n, int k, 
                         int32_t *bad, hipStream_t st);
 void launch_list_histogram(const int32_t *label, int64_t N, int32_t *cnt, hipStream_t st);
 void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStream_t st);
+// the same, and beside it the exclusive scan of ceil(cnt / chunk) into off2 (nl <= 2^18, cnt 16-byte aligned)
+void launch_exclusive_scan_chunks(const int32_t *cnt, int64_t nl, int64_t *off, int chunk, int64_t *off2, hipStream_t st);
 void launch_list_scatter(const int32_t *label, const int32_t *st_ids, const uint8_t *st_codes,
                          const uint8_t *st_lam, int64_t N, int m, const int64_t *off, int32_t *cursor,
                          int32_t *ids, uint8_t *codes, uint8_t *lam, hipStream_t st);

@@ -107,19 +107,24 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restri
 // 4 096 counts first adds up everything before its tile (read again by every later workgroup: a few
 // hundred KB from L2 at most), then scans its own tile.
 #define XB_TILE 4096
+// With chunk > 0 the scan of ceil(cnt / chunk) goes to off2 beside it (both are summed in one word, the counts
+// in the low 32 bits, the chunk counts above them: for counts that add up to less than 2^31).
 __global__ __launch_bounds__(256) void k_exclusive_scan_tiles(const int32_t *__restrict__ cnt, int64_t nl,
-                                                              int64_t *__restrict__ off)
+                                                              int64_t *__restrict__ off, int chunk,
+                                                              int64_t *__restrict__ off2)
 {
     __shared__ int64_t wsum[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t t0 = (int64_t)blockIdx.x * XB_TILE;
+    auto both = [&](int32_t c) { return (int64_t)c + (chunk > 0 ? (int64_t)((c + chunk - 1) / chunk) << 32 : 0); };
+    const int64_t low = chunk > 0 ? (((int64_t)1 << 32) - 1) : ~(int64_t)0;
     int64_t before = 0;
     for (int64_t i = 4 * tid; i < t0; i += XB_TILE) { // t0 is a multiple of the tile: four loads in flight
         int4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = *(const int4 *)(cnt + i + 1024 * u);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) before += (int64_t)v[u].x + v[u].y + v[u].z + v[u].w;
+        for (int u = 0; u < 4; ++u) before += both(v[u].x) + both(v[u].y) + both(v[u].z) + both(v[u].w);
     }
     const int64_t i0 = t0 + XS_PER * tid;
     int32_t c[XS_PER];
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(256) void k_exclusive_scan_tiles(const int32_t *__r
     for (int e = 0; e < XS_PER; ++e) c[e] = i0 + e < nl ? cnt[i0 + e] : 0;
     int64_t mine = 0;
 #pragma unroll
-    for (int e = 0; e < XS_PER; ++e) mine += c[e];
+    for (int e = 0; e < XS_PER; ++e) mine += both(c[e]);
     // the sum of `before` over the workgroup, and the scan of `mine`
     int64_t inc = mine;
 #pragma unroll
@@ -144,19 +149,31 @@ __global__ __launch_bounds__(256) void k_exclusive_scan_tiles(const int32_t *__r
     for (int w = 0; w < wave; ++w) run += wsum[w];
 #pragma unroll
     for (int e = 0; e < XS_PER; ++e) {
-        if (i0 + e < nl) off[i0 + e] = run;
-        run += c[e];
+        if (i0 + e < nl) {
+            off[i0 + e] = run & low;
+            if (chunk > 0) off2[i0 + e] = run >> 32;
+        }
+        run += both(c[e]);
     }
-    if (i0 <= nl - 1 && nl - 1 < i0 + XS_PER) off[nl] = run; // the thread that holds the last count
+    if (i0 <= nl - 1 && nl - 1 < i0 + XS_PER) { // the thread that holds the last count
+        off[nl] = run & low;
+        if (chunk > 0) off2[nl] = run >> 32;
+    }
 }
 
 void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStream_t st)
 {
     if (nl > 0 && nl <= ((int64_t)1 << 18) && ((uintptr_t)cnt) % 16 == 0)
         hipLaunchKernelGGL(k_exclusive_scan_tiles, dim3((unsigned)((nl + XB_TILE - 1) / XB_TILE)), dim3(256), 0, st, cnt,
-                           nl, off);
+                           nl, off, 0, (int64_t *)nullptr);
     else
         hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, cnt, nl, off);
+}
+
+void launch_exclusive_scan_chunks(const int32_t *cnt, int64_t nl, int64_t *off, int chunk, int64_t *off2, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_exclusive_scan_tiles, dim3((unsigned)((nl + XB_TILE - 1) / XB_TILE)), dim3(256), 0, st, cnt, nl,
+                       off, chunk, off2);
 }
 
 __global__ void k_list_scatter(const int32_t *__restrict__ label, const int32_t *__restrict__ st_ids,

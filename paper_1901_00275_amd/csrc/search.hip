@@ -595,27 +595,36 @@ __global__ void k_pair_count(const int32_t *__restrict__ cells, int64_t np, int3
 }
 
 __global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, const int64_t *__restrict__ poff,
-                               const int32_t *__restrict__ rank, int32_t *__restrict__ pairs)
+                               const int32_t *__restrict__ rank, int32_t *__restrict__ pairs,
+                               const int64_t *__restrict__ woff, int2 *__restrict__ work, int chunk)
 {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p < np) {
         const int c = cells[p];
-        if (c >= 0) pairs[poff[c] + rank[p]] = (int32_t)p;
+        if (c >= 0) {
+            const int r = rank[p];
+            pairs[poff[c] + r] = (int32_t)p;
+            // the first pair of every chunk of its cell enters the chunk in the work list
+            if (r % chunk == 0) work[woff[c] + r / chunk] = make_int2(c, r / chunk);
+        }
     }
 }
 
 #define ND_PCH 32 // pairs taken up at a time
 
-// Grouped (pairs != nullptr): a workgroup per cell brings the cell's rows into LDS once and walks the
-// cell's pairs in chunks of ND_PCH (cells nobody probes leave at once).  Ungrouped (small batches): a
-// workgroup per pair, in the pairs' own order, np_all of them.  A wave per pair, four rows per pass.
+// Grouped (pairs != nullptr): the pairs of a cell are cut into chunks of ND_PCH; a workgroup takes one
+// chunk from the work list (woff[k] entries; the grid is an upper bound of that), brings the cell's rows
+// into LDS and serves the chunk's pairs (a popular cell spreads over many workgroups).  Ungrouped (small
+// batches): a workgroup per pair, in the pairs' own order, np_all of them.  Two pairs per wave, four
+// rows per pass.
 __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict__ Q, int D,
                                                          const float *__restrict__ C,
                                                          const int32_t *__restrict__ S, int n, int k, int w1,
                                                          const int32_t *__restrict__ cells,
                                                          const int64_t *__restrict__ poff,
                                                          const int32_t *__restrict__ pairs, int64_t np_all,
-                                                         float *__restrict__ bq)
+                                                         const int64_t *__restrict__ woff,
+                                                         const int2 *__restrict__ work, float *__restrict__ bq)
 {
     extern __shared__ float nrows[]; // [n][D] edge vectors s_ij - c_i, then [D] the centroid c_i
     __shared__ int sp[ND_PCH];
@@ -625,10 +634,11 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
     int64_t pbeg, pend;
     int cell;
     if (pairs) {
-        cell = blockIdx.x;
-        pbeg = poff[cell];
-        pend = poff[cell + 1];
-        if (pbeg >= pend) return;
+        if ((int64_t)blockIdx.x >= woff[k]) return;
+        const int2 wi = work[blockIdx.x];
+        cell = wi.x;
+        pbeg = poff[cell] + (int64_t)wi.y * ND_PCH;
+        pend = min(poff[cell + 1], pbeg + ND_PCH);
     } else {
         pbeg = blockIdx.x;
         pend = pbeg + 1;
@@ -797,6 +807,8 @@ size_t neighbour_dists_workspace(int nq, int k, int n, int w1)
     b += (((size_t)(k + 1) * 8) + 255) & ~(size_t)255;             // offsets
     b += (((size_t)nq * w1 * 4) + 255) & ~(size_t)255;             // ranks
     b += (((size_t)nq * w1 * 4) + 255) & ~(size_t)255;             // pairs
+    b += (((size_t)(k + 1) * 8) + 255) & ~(size_t)255;             // work offsets
+    b += ((((size_t)nq * w1 / ND_PCH + k + 1) * 8) + 255) & ~(size_t)255; // work list
     b += (((size_t)nq * w1 * n * 4) + 255) & ~(size_t)255;         // distances
     return b;
 }
@@ -814,6 +826,8 @@ PairWs neighbour_dists_carve(void *ws, int nq, int k, int n, int w1)
     pw.poff = (int64_t *)take((size_t)(k + 1) * 8);
     pw.rank = (int32_t *)take((size_t)nq * w1 * 4);
     pw.pairs = (int32_t *)take((size_t)nq * w1 * 4);
+    pw.woff = (int64_t *)take((size_t)(k + 1) * 8);
+    pw.work = (int2 *)take(((size_t)nq * w1 / ND_PCH + k + 1) * 8);
     pw.bq = (float *)take((size_t)nq * w1 * n * 4);
     return pw;
 }
@@ -843,15 +857,16 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
                 launch_pair_counts_zero(pw, k, st);
                 hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, cnt, rank);
             }
-            launch_exclusive_scan(cnt, k, poff, st);
+            launch_exclusive_scan_chunks(cnt, k, poff, ND_PCH, pw.woff, st);
             hipLaunchKernelGGL(k_pair_scatter, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, cells, np, poff,
-                               rank, pairs);
+                               rank, pairs, pw.woff, pw.work, ND_PCH);
         }
         const size_t rows_bytes = (size_t)(n + 1) * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
-        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)(grouped ? (int64_t)k : np)), dim3(256), rows_bytes, st, Q,
-                           D, C, S, n, k, w1, cells, poff, grouped ? pairs : nullptr, np, bq);
+        // grouped: at most np / ND_PCH full chunks and one partial chunk per cell
+        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)(grouped ? np / ND_PCH + k : np)), dim3(256), rows_bytes, st, Q,
+                           D, C, S, n, k, w1, cells, poff, grouped ? pairs : nullptr, np, pw.woff, pw.work, bq);
         bpre = bq;
     }
     int sz = next_pow2(w1 * n);
