@@ -253,6 +253,18 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     f32x16 acc[2][2];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+    // MODE_EMIT over hi parts: the reported columns of the workgroup's 128 rows are collected in the lo pages
+    // of A, which this form never fills (SPT * 8 slots per row; counters in the ring's first lo page), and
+    // appended to the rows' global lists at the end: one global atomic per row and workgroup instead of one
+    // per reported column, and no wait for its return inside the sweep.
+    constexpr bool LBUF = HI && MODE == MODE_EMIT;
+    constexpr int LSLOTS = SPT * 8;
+    int *lcnt = (int *)(lds + (SPT * 2 + 1) * PAGE) + 16; // [BT] (behind the strip maxima)
+    auto lslot = [&](int r, int sl) -> int * { // slot r * LSLOTS + sl of the SPT lo pages (1 024 words each) laid end to end
+        const int flat = r * LSLOTS + sl;
+        return (int *)(lds + (2 * (flat >> 10) + 1) * PAGE) + (flat & 1023);
+    };
+    if (LBUF && tid < BT) lcnt[tid] = 0;
     __syncthreads();
     float hi_band = 0.f; // error bound of e per unit of |b|
     if (HI)
@@ -361,6 +373,13 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
                 const int j = bit >> 5, el = 31 - (bit & 31), i = el >> 4, r = el & 15;
                 const int64_t row = m0 + slot_row(i, r);
                 const int col = (int)n0 + wn + 32 * j + (lane & 31);
+                if (LBUF) {
+                    const int sl = atomicAdd(&lcnt[slot_row(i, r)], 1);
+                    if (sl < LSLOTS) {
+                        *lslot(slot_row(i, r), sl) = col;
+                        continue;
+                    }
+                }
                 const int pos = atomicAdd(&a.ccnt[row], 1);
                 if (first) {
                     pend_row = row;
@@ -374,6 +393,20 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
         }
     }
     if (MODE == MODE_EMIT && pend_row >= 0 && pend_pos < a.cap) a.cidx[pend_row * a.cap + pend_pos] = pend_col;
+    if (LBUF) {
+        __syncthreads();
+        int *lbase = lcnt + BT; // [BT] place of the row's first buffered column in its global list
+        if (tid < BT) {
+            const int nb = min(lcnt[tid], LSLOTS);
+            lbase[tid] = nb > 0 ? atomicAdd(&a.ccnt[m0 + tid], nb) : 0; // (rows past the end report nothing)
+        }
+        __syncthreads();
+        for (int t = tid; t < BT * LSLOTS; t += 256) {
+            const int r = t / LSLOTS, sl = t - r * LSLOTS;
+            const int pos = lbase[r] + sl;
+            if (sl < min(lcnt[r], LSLOTS) && pos < a.cap) a.cidx[(m0 + r) * a.cap + pos] = *lslot(r, sl);
+        }
+    }
 
     if (MODE == MODE_EMIT) return;
     if (MODE == MODE_MIN) {

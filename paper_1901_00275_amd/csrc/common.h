@@ -326,7 +326,8 @@ void launch_pack_labels(const int32_t *cell, const int32_t *edge, int n, int k, 
                         int32_t *bad, hipStream_t st);
 void launch_list_histogram(const int32_t *label, int64_t N, int32_t *cnt, hipStream_t st);
 void launch_exclusive_scan(const int32_t *cnt, int64_t nl, int64_t *off, hipStream_t st);
-// the same, and beside it the exclusive scan of ceil(cnt / chunk) into off2 (nl <= 2^18, cnt 16-byte aligned)
+// the same, and beside it the exclusive scan of ceil(cnt / chunk) into off2 (chunk a power of two, cnt 16-byte
+// aligned, counts adding up to less than 2^31)
 void launch_exclusive_scan_chunks(const int32_t *cnt, int64_t nl, int64_t *off, int chunk, int64_t *off2, hipStream_t st);
 void launch_list_scatter(const int32_t *label, const int32_t *st_ids, const uint8_t *st_codes,
                          const uint8_t *st_lam, int64_t N, int m, const int64_t *off, int32_t *cursor,

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restri
 // 4 096 counts first adds up everything before its tile (read again by every later workgroup: a few
 // hundred KB from L2 at most), then scans its own tile.
 #define XB_TILE 4096
-// With chunk > 0 the scan of ceil(cnt / chunk) goes to off2 beside it (both are summed in one word, the counts
+// With chunk > 0, a power of two, the scan of ceil(cnt / chunk) goes to off2 beside it (both are summed in one word, the counts
 // in the low 32 bits, the chunk counts above them: for counts that add up to less than 2^31).
 __global__ __launch_bounds__(256) void k_exclusive_scan_tiles(const int32_t *__restrict__ cnt, int64_t nl,
                                                               int64_t *__restrict__ off, int chunk,
@@ -116,7 +116,9 @@ __global__ __launch_bounds__(256) void k_exclusive_scan_tiles(const int32_t *__r
     __shared__ int64_t wsum[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t t0 = (int64_t)blockIdx.x * XB_TILE;
-    auto both = [&](int32_t c) { return (int64_t)c + (chunk > 0 ? (int64_t)((c + chunk - 1) / chunk) << 32 : 0); };
+    // (chunk is a power of two)
+    const int csh = chunk > 0 ? 31 - __clz(chunk) : 0;
+    auto both = [&](int32_t c) { return (int64_t)c + (chunk > 0 ? (int64_t)((c + chunk - 1) >> csh) << 32 : 0); };
     const int64_t low = chunk > 0 ? (((int64_t)1 << 32) - 1) : ~(int64_t)0;
     int64_t before = 0;
     for (int64_t i = 4 * tid; i < t0; i += XB_TILE) { // t0 is a multiple of the tile: four loads in flight
