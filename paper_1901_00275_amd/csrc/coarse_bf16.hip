@@ -576,12 +576,25 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
     for (int i = lane; i < G; i += 64) mine[i] = f2ord(gmin[(int64_t)row * G + i]);
     // (the wave reads back only what it wrote itself)
     uint32_t result = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t trial = result | (1u << bit);
-        int below = 0;
-        for (int i = lane; i < G; i += 64) below += __popcll(__ballot(mine[i] < trial));
-        // G is a multiple of 64, so every lane makes the same number of rounds and `below` is uniform
-        if (below < want) result = trial;
+    if (G <= 512) { // the usual case: the minima in registers
+        uint32_t u[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) u[e] = lane + 64 * e < G ? mine[lane + 64 * e] : 0xFFFFFFFFu;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = result | (1u << bit);
+            int below = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) below += __popcll(__ballot(u[e] < trial)); // (a filler is below nothing)
+            if (below < want) result = trial;
+        }
+    } else {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = result | (1u << bit);
+            int below = 0;
+            for (int i = lane; i < G; i += 64) below += __popcll(__ballot(mine[i] < trial));
+            // G is a multiple of 64, so every lane makes the same number of rounds and `below` is uniform
+            if (below < want) result = trial;
+        }
     }
     if (lane == 0) {
         const float tau = ord2f(result);
