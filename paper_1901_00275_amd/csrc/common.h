@@ -250,7 +250,7 @@ struct PairWs {
     int32_t *rank;  // [nq x w1]
     int32_t *pairs; // [nq x w1]
     int64_t *woff;  // [k + 1] work items (a cell's pairs in chunks) before each cell
-    int2 *work;     // [nq x w1 / chunk + k] {cell, chunk}
+    int4 *work;     // [nq x w1 / chunk + k] {cell, place of the chunk's first pair, pairs in the chunk, -}
     float *bq;      // [nq x w1 x n]
 };
 PairWs neighbour_dists_carve(void *ws, int nq, int k, int n, int w1);

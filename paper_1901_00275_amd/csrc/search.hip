@@ -596,16 +596,21 @@ __global__ void k_pair_count(const int32_t *__restrict__ cells, int64_t np, int3
 
 __global__ void k_pair_scatter(const int32_t *__restrict__ cells, int64_t np, const int64_t *__restrict__ poff,
                                const int32_t *__restrict__ rank, int32_t *__restrict__ pairs,
-                               const int64_t *__restrict__ woff, int2 *__restrict__ work, int chunk)
+                               const int64_t *__restrict__ woff, int4 *__restrict__ work, int chunk)
 {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p < np) {
         const int c = cells[p];
         if (c >= 0) {
             const int r = rank[p];
-            pairs[poff[c] + r] = (int32_t)p;
-            // the first pair of every chunk of its cell enters the chunk in the work list
-            if (r % chunk == 0) work[woff[c] + r / chunk] = make_int2(c, r / chunk);
+            const int64_t beg = poff[c];
+            pairs[beg + r] = (int32_t)p;
+            // the first pair of every chunk of its cell enters the chunk in the work list: {cell, place of the
+            // chunk's first pair, pairs in the chunk}
+            if (r % chunk == 0) {
+                const int64_t left = poff[c + 1] - (beg + r);
+                work[woff[c] + r / chunk] = make_int4(c, (int)(beg + r), (int)(left < chunk ? left : chunk), 0);
+            }
         }
     }
 }
@@ -624,7 +629,7 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
                                                          const int64_t *__restrict__ poff,
                                                          const int32_t *__restrict__ pairs, int64_t np_all,
                                                          const int64_t *__restrict__ woff,
-                                                         const int2 *__restrict__ work, float *__restrict__ bq)
+                                                         const int4 *__restrict__ work, float *__restrict__ bq)
 {
     extern __shared__ float nrows[]; // [n][D] edge vectors s_ij - c_i, then [D] the centroid c_i
     __shared__ int sp[ND_PCH];
@@ -635,10 +640,10 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
     int cell;
     if (pairs) {
         if ((int64_t)blockIdx.x >= woff[k]) return;
-        const int2 wi = work[blockIdx.x];
+        const int4 wi = work[blockIdx.x];
         cell = wi.x;
-        pbeg = poff[cell] + (int64_t)wi.y * ND_PCH;
-        pend = min(poff[cell + 1], pbeg + ND_PCH);
+        pbeg = wi.y;
+        pend = pbeg + wi.z;
     } else {
         pbeg = blockIdx.x;
         pend = pbeg + 1;
@@ -656,34 +661,39 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
     if (tid < min((int64_t)ND_PCH, pend - pbeg)) first_p = pairs ? pairs[pbeg + tid] : (int)(pbeg + tid);
     {
         const float *cg = C + (int64_t)cell * D;
-        if (vec) {
-            // eight items per thread and pass, all index loads first, then all row loads, so that a pass
-            // costs two round trips
-            const int d4 = D / 4, items = (n + 1) * d4;
-            for (int t0 = tid; t0 < items; t0 += 256 * 8) {
-                int jj[8], cc[8], ss[8];
+        if (vec && D <= 128) {
+            // half a wave per row, a lane per 16-byte chunk of it (so a thread subtracts the same chunk of the
+            // centroid from all its rows); up to eight rows per thread and pass: their index loads first, then
+            // their row loads, so that a pass costs two round trips
+            const int d4 = D / 4, col = tid & 31, r8 = tid >> 5;
+            const bool colok = col < d4;
+            const f32x4 cvv = colok ? ((const f32x4 *)cg)[col] : zero;
+            if (r8 == 0 && colok) ((f32x4 *)crow)[col] = cvv;
+            for (int j0 = 0; j0 < n; j0 += 64) {
+                int ss[8];
+                f32x4 rv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (j0 + 8 * u < n) ss[u] = S[(int64_t)cell * n + min(j0 + 8 * u + r8, n - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (j0 + 8 * u < n) rv[u] = colok ? ((const f32x4 *)(C + (int64_t)ss[u] * D))[col] : zero;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const int t = t0 + 256 * u;
-                    jj[u] = t / d4;
-                    cc[u] = t - jj[u] * d4;
-                    ss[u] = cell;
-                    if (t < items && jj[u] < n) ss[u] = S[(int64_t)cell * n + jj[u]];
+                    const int j = j0 + 8 * u + r8;
+                    if (j0 + 8 * u < n && j < n && colok) ((f32x4 *)nrows)[j * d4 + col] = rv[u] - cvv;
                 }
-                f32x4 rv[8], cv[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    rv[u] = zero;
-                    cv[u] = zero;
-                    if (t0 + 256 * u < items) {
-                        rv[u] = ((const f32x4 *)(C + (int64_t)ss[u] * D))[cc[u]];
-                        cv[u] = ((const f32x4 *)cg)[cc[u]];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int t = t0 + 256 * u;
-                    if (t < items) ((f32x4 *)nrows)[t] = jj[u] < n ? rv[u] - cv[u] : cv[u];
+            }
+        } else if (vec) {
+            const int d4 = D / 4;
+            for (int t = tid; t < (n + 1) * d4; t += 256) {
+                const int j = t / d4, c = t - j * d4;
+                const f32x4 cv = ((const f32x4 *)cg)[c];
+                if (j < n) {
+                    const int s = S[(int64_t)cell * n + j];
+                    ((f32x4 *)nrows)[t] = ((const f32x4 *)(C + (int64_t)s * D))[c] - cv;
+                } else {
+                    ((f32x4 *)nrows)[t] = cv;
                 }
             }
         } else {
@@ -699,66 +709,92 @@ __global__ __launch_bounds__(256) void k_neighbour_dists(const float *__restrict
         if (tid < e) sp[tid] = ch == pbeg ? first_p : (pairs ? pairs[ch + tid] : (int)(ch + tid));
         __syncthreads();
         if (fast) {
-            // two pairs of the cell per wave where there are that many: a row read from LDS serves both
-            auto run = [&](auto two_c, int pa, int pb) {
-                constexpr bool TWO = decltype(two_c)::value;
+            // A group of 16 lanes takes two pairs of the cell and a block of 16 rows: lane l keeps, for both
+            // pairs, its share of the 16 dot products (the components 4 l .. 4 l + 3 and 64 + 4 l .. of
+            // every row) in 2 x 16 registers, then the 16 x 16 partial sums of a pair are added across the
+            // lanes and transposed at once: register s of lane l belongs to row s ^ g(l), with g chosen so that
+            // each of the four lane-crossing steps of row16_sum (neighbour, other pair of the quad, other quad
+            // of the half, other half) finds the same row in the partner's register s + 1, s + 2, s + 4, s + 8.
+            // Half of the registers are given away at every step: 15 lane-crossing adds per pair instead of
+            // 64, the same additions in the same association as row16_sum, so the sums are the same to the
+            // bit; lane l ends with the sum of row g(l).
+            const int gl = (l16 & 3) ^ ((l16 & 4) ? 7 : 0) ^ ((l16 & 8) ? 12 : 0);
+            const int nb = (n + 15) >> 4;          // blocks of 16 rows
+            const int npp = (e + 1) >> 1;          // pairs of pairs
+            const int combos = npp * nb;
+            for (int c0 = (wave << 2) + sub; c0 < ((combos + 15) & ~15); c0 += 16) {
+                const bool live = c0 < combos;
+                const int c = live ? c0 : 0;
+                const int pp = c / nb, blk = c - pp * nb;
+                const bool two = 2 * pp + 1 < e;
+                const int pa = sp[2 * pp], pb = sp[two ? 2 * pp + 1 : 2 * pp];
                 const float *ya = Q + (int64_t)(pa / w1) * D, *yb = Q + (int64_t)(pb / w1) * D;
                 f32x4 a0 = zero, a1 = zero, b0 = zero, b1 = zero; // y - c_i
                 if (has0) {
                     const f32x4 cc = *(const f32x4 *)(crow + d0);
                     a0 = *(const f32x4 *)(ya + d0) - cc;
-                    if (TWO) b0 = *(const f32x4 *)(yb + d0) - cc;
+                    b0 = *(const f32x4 *)(yb + d0) - cc;
                 }
                 if (has1) {
                     const f32x4 cc = *(const f32x4 *)(crow + d1);
                     a1 = *(const f32x4 *)(ya + d1) - cc;
-                    if (TWO) b1 = *(const f32x4 *)(yb + d1) - cc;
+                    b1 = *(const f32x4 *)(yb + d1) - cc;
                 }
-                for (int j0 = 0; j0 < n; j0 += 4) {
-                    const int j = j0 + sub;
+                float ra[16], rb[16];
+#pragma unroll
+                for (int sreg = 0; sreg < 16; ++sreg) {
+                    const int j = min(blk * 16 + (sreg ^ gl), n - 1); // (rows past the end: computed, not stored)
+                    const float *row = nrows + j * D;
                     float acca = 0.f, accb = 0.f;
-                    if (j < n) {
-                        const float *row = nrows + j * D;
-                        if (has0) {
-                            const f32x4 ev = *(const f32x4 *)(row + d0);
-                            acca = fmaf(a0.x, ev.x, acca);
-                            acca = fmaf(a0.y, ev.y, acca);
-                            acca = fmaf(a0.z, ev.z, acca);
-                            acca = fmaf(a0.w, ev.w, acca);
-                            if (TWO) {
-                                accb = fmaf(b0.x, ev.x, accb);
-                                accb = fmaf(b0.y, ev.y, accb);
-                                accb = fmaf(b0.z, ev.z, accb);
-                                accb = fmaf(b0.w, ev.w, accb);
-                            }
-                        }
-                        if (has1) {
-                            const f32x4 ev = *(const f32x4 *)(row + d1);
-                            acca = fmaf(a1.x, ev.x, acca);
-                            acca = fmaf(a1.y, ev.y, acca);
-                            acca = fmaf(a1.z, ev.z, acca);
-                            acca = fmaf(a1.w, ev.w, acca);
-                            if (TWO) {
-                                accb = fmaf(b1.x, ev.x, accb);
-                                accb = fmaf(b1.y, ev.y, accb);
-                                accb = fmaf(b1.z, ev.z, accb);
-                                accb = fmaf(b1.w, ev.w, accb);
-                            }
-                        }
+                    if (has0) {
+                        const f32x4 ev = *(const f32x4 *)(row + d0);
+                        acca = fmaf(a0.x, ev.x, acca);
+                        acca = fmaf(a0.y, ev.y, acca);
+                        acca = fmaf(a0.z, ev.z, acca);
+                        acca = fmaf(a0.w, ev.w, acca);
+                        accb = fmaf(b0.x, ev.x, accb);
+                        accb = fmaf(b0.y, ev.y, accb);
+                        accb = fmaf(b0.z, ev.z, accb);
+                        accb = fmaf(b0.w, ev.w, accb);
                     }
-                    acca = row16_sum(acca);
-                    if (TWO) accb = row16_sum(accb);
-                    if (l16 == 0 && j < n) {
-                        bq[(int64_t)pa * n + j] = acca;
-                        if (TWO) bq[(int64_t)pb * n + j] = accb;
+                    if (has1) {
+                        const f32x4 ev = *(const f32x4 *)(row + d1);
+                        acca = fmaf(a1.x, ev.x, acca);
+                        acca = fmaf(a1.y, ev.y, acca);
+                        acca = fmaf(a1.z, ev.z, acca);
+                        acca = fmaf(a1.w, ev.w, acca);
+                        accb = fmaf(b1.x, ev.x, accb);
+                        accb = fmaf(b1.y, ev.y, accb);
+                        accb = fmaf(b1.z, ev.z, accb);
+                        accb = fmaf(b1.w, ev.w, accb);
                     }
+                    ra[sreg] = acca;
+                    rb[sreg] = accb;
                 }
-            };
-            for (int pi = i + wave; pi < e; pi += 8) {
-                if (pi + 4 < e)
-                    run(std::true_type{}, sp[pi], sp[pi + 4]);
-                else
-                    run(std::false_type{}, sp[pi], sp[pi]);
+#define VLQ_DPP_GET(x, ctrl) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xF, 0xF, true))
+#pragma unroll
+                for (int u = 0; u < 16; u += 2) { // neighbour in the pair: quad_perm [1, 0, 3, 2]
+                    ra[u] += VLQ_DPP_GET(ra[u + 1], 0xB1);
+                    rb[u] += VLQ_DPP_GET(rb[u + 1], 0xB1);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; u += 4) { // other pair of the quad: quad_perm [2, 3, 0, 1]
+                    ra[u] += VLQ_DPP_GET(ra[u + 2], 0x4E);
+                    rb[u] += VLQ_DPP_GET(rb[u + 2], 0x4E);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; u += 8) { // other quad of the half: row_half_mirror
+                    ra[u] += VLQ_DPP_GET(ra[u + 4], 0x141);
+                    rb[u] += VLQ_DPP_GET(rb[u + 4], 0x141);
+                }
+                ra[0] += VLQ_DPP_GET(ra[8], 0x140); // other half of the row: row_mirror
+                rb[0] += VLQ_DPP_GET(rb[8], 0x140);
+#undef VLQ_DPP_GET
+                const int j = blk * 16 + gl;
+                if (live && j < n) {
+                    bq[(int64_t)pa * n + j] = ra[0];
+                    if (two) bq[(int64_t)pb * n + j] = rb[0];
+                }
             }
         } else
         for (int pi = i + wave; pi < e; pi += 4) {
@@ -808,7 +844,7 @@ size_t neighbour_dists_workspace(int nq, int k, int n, int w1)
     b += (((size_t)nq * w1 * 4) + 255) & ~(size_t)255;             // ranks
     b += (((size_t)nq * w1 * 4) + 255) & ~(size_t)255;             // pairs
     b += (((size_t)(k + 1) * 8) + 255) & ~(size_t)255;             // work offsets
-    b += ((((size_t)nq * w1 / ND_PCH + k + 1) * 8) + 255) & ~(size_t)255; // work list
+    b += ((((size_t)nq * w1 / ND_PCH + k + 1) * 16) + 255) & ~(size_t)255; // work list
     b += (((size_t)nq * w1 * n * 4) + 255) & ~(size_t)255;         // distances
     return b;
 }
@@ -827,7 +863,7 @@ PairWs neighbour_dists_carve(void *ws, int nq, int k, int n, int w1)
     pw.rank = (int32_t *)take((size_t)nq * w1 * 4);
     pw.pairs = (int32_t *)take((size_t)nq * w1 * 4);
     pw.woff = (int64_t *)take((size_t)(k + 1) * 8);
-    pw.work = (int2 *)take(((size_t)nq * w1 / ND_PCH + k + 1) * 8);
+    pw.work = (int4 *)take(((size_t)nq * w1 / ND_PCH + k + 1) * 16);
     pw.bq = (float *)take((size_t)nq * w1 * n * 4);
     return pw;
 }
