@@ -1,10 +1,10 @@
 // First-level quantiser on the bf16 matrix cores (Eq. 2; Alg. 1 "nearest centroid").
 //
-// An fp32 value v is split into two bf16 numbers, hi = rne(v) and lo = rne(v - hi),
-// so that |v - hi - lo| <= 2^-18 |v|.  The inner product of two split vectors is
-// taken as hi.hi + hi.lo + lo.hi with fp32 accumulation on
+// An fp32 value v is split into two bf16 numbers, hi = rne(v) and lo = rne(v - hi); a bf16 number
+// has 8 significant bits, so |v - hi| <= 2^-8 |v| and |v - hi - lo| <= 2^-16 |v|.  The inner product of
+// two split vectors is taken as hi.hi + hi.lo + lo.hi with fp32 accumulation on
 // v_mfma_f32_32x32x16_bf16; the dropped lo.lo term and the representation error
-// together stay below 3 * 2^-18 |x| |c|.  The result only shortlists centroids: every
+// together stay below 3 * 2^-16 |x| |c|.  The result only shortlists centroids: every
 // column whose approximate distance lies within the error band of the row minimum
 // is handed on and re-evaluated there as a direct fp32 sum of squared differences,
 // so the decision itself is taken in fp32 exactly as by the fp32 path.  The two sweeps of the search's
@@ -111,15 +111,15 @@ void launch_split_bf16(const float *X, int64_t rows, int D, const float *mu, voi
 }
 
 // Error budget of one approximate value e = ||b||^2 - 2 <a, b>, D <= 128, worst case:
-//   representation: |v - hi - lo| <= 2^-18 |v| on both operands and the dropped lo.lo term give
-//     3 * 2^-18 |a||b| on the inner product, twice that on e                      (2.3e-5 |a||b|);
+//   representation: |v - hi - lo| <= 2^-16 |v| on both operands and the dropped lo.lo term give
+//     3 * 2^-16 |a||b| on the inner product, twice that on e                      (9.2e-5 |a||b|);
 //   fp32 accumulation of the 3 D products in any order: <= 3 D 2^-24 |a||b| on the inner
 //     product, twice that on e                                                     (4.6e-5 |a||b|);
-//   together < 7e-5 |a||b| <= 3.5e-5 (||a||^2 + ||b||^2).  A comparison involves two values, and
+//   together < 1.4e-4 |a||b| <= 7e-5 (||a||^2 + ||b||^2).  A comparison involves two values, and
 //   ||a||^2 + ||b||^2 <= 3 ||a||^2 + 2 d for a column at distance d, hence the band
-//   7e-5 (3 ||a||^2 + 2 d).  (Typical errors are a factor sqrt(3 D) smaller; the band only
+//   1.4e-4 (3 ||a||^2 + 2 d).  (Typical errors are a factor sqrt(3 D) smaller; the band only
 //   decides how many columns are re-evaluated exactly, never the result.)
-#define BF16_BAND_NORM 7e-5f
+#define BF16_BAND_NORM 1.4e-4f
 // Columns past the end of B get this "norm": finite, so that index bits can be planted
 // in the key, and beyond BF16_NO_KEY, from where on a key counts as absent.
 #define BF16_NO_COLUMN 3e38f
@@ -159,8 +159,8 @@ struct Bf16Args {
 // SPT = D / 16 steps per tile; PDEPTH page pairs of B in flight in registers (divides SPT, so
 // that every register set and ring half has a fixed role in the unrolled tile body).
 // HI: the product of the hi parts alone (search sweeps): lo pages are neither loaded nor multiplied.
-// An operand's hi part differs from it by at most 2^-9 of each component, so <a, b> - <a_h, b_h> =
-// <a - a_h, b> + <a_h, b - b_h> is at most 2^-8 |a||b| (1 + 2^-9) in size, half of that when the rows are their
+// An operand's hi part differs from it by at most 2^-8 of each component, so <a, b> - <a_h, b_h> =
+// <a - a_h, b> + <a_h, b - b_h> is at most 2^-7 |a||b| (1 + 2^-8) in size, half of that when the rows are their
 // own hi parts (integer-valued queries); e takes twice the product's error, and the fp32 accumulation of D <= 128
 // products adds 2 D 2^-24 |a||b|, inside the 2 % the constant is rounded up by.  With |a| taken as the largest
 // of the workgroup's 128 rows the error bound t of a column depends on the column alone and joins its norm:
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(256, 2) void k_coarse_bf16(Bf16Args a)
     float hi_band = 0.f; // error bound of e per unit of |b|
     if (HI)
         hi_band = sqrtf(fmaxf(fmaxf(strip_max[0], strip_max[1]), fmaxf(strip_max[2], strip_max[3]))) *
-                  (*a.a_any_lo ? 0x1p-7f : 0x1p-8f) * 1.02f * (MODE == MODE_MIN ? 1.f : -1.f);
+                  (*a.a_any_lo ? 0x1p-6f : 0x1p-7f) * 1.02f * (MODE == MODE_MIN ? 1.f : -1.f);
     // the hi fragments of the wave's 64 rows for all steps: the same for every tile, kept in registers
     bf16x8 ahr[SPT][2];
 #pragma unroll
