@@ -426,6 +426,37 @@ def test_cell_selection_with_long_column_splits(vlq, oracle_mod, dup):
         vlq.vlq_index_free(idx)
 
 
+@pytest.mark.parametrize("split", [0, 1])
+def test_cell_selection_when_the_bf16_parts_mislead(vlq, oracle_mod, split):
+    """Alg. 3, first loop, on centroids built against the sweeps' arithmetic: every component sits a hair below or
+    above a bf16 rounding boundary, so the hi parts of two kinds of centroids differ by 2^-7 of each component
+    while the centroids themselves differ by 2^-19, and the approximate distances order the kinds, not the
+    centroids.  The error band of the sweeps has to take in nearly every column and hand the decision to the
+    exact ranking: the cells must be the oracle's (ties inside the fp32 resolution of the exact sums aside)."""
+    rng = np.random.default_rng(17)
+    D, k, nq, w1 = 32, 4096, 96, 8
+    pr = problem(N=2000, k=64, n=2, m=8, G=16, nq=8, D=D, iters=1)  # (for the PQ codebooks and base vectors only)
+    base = (rng.choice([-1.0, 1.0], size=D) * 2.0 ** rng.integers(-1, 2, size=D)).astype(np.float64)
+    kind = rng.integers(0, 2, size=(k, 1)) * 2 - 1                      # -1: rounds down, +1: rounds up
+    delta = rng.integers(-2, 3, size=(k, D))
+    C = (base * (1.0 + 2.0 ** -8 + kind * 2.0 ** -20 + delta * 2.0 ** -23)).astype(np.float32)
+    Y = (base * (0.9 + rng.integers(-64, 65, size=(nq, D)) * 2.0 ** -10)).astype(np.float32)
+    pr2 = Problem(pr.kind, pr.X, Y, C, pr.P, 2)
+    idx = make_index(vlq, pr2, base=pr.X[:500])
+    try:
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_COARSE_SPLIT, split)
+        dist = oracle_mod.coarse(C, Y)
+        od, oi, cells, cd, sub, ss = gpu_search(vlq, idx, Y, w1, 2 * w1, 10)
+        for q in range(nq):
+            check_selection(cells[q], dict(enumerate(dist[q])), w1, what=f"query {q} cells")
+            assert np.allclose(cd[q], dist[q][cells[q]], rtol=DTOL, atol=1e-6)
+        # the kinds really are what the hi parts see: without the band the sweeps would pick by kind
+        hi = (C.view(np.uint32) + 0x7FFF + ((C.view(np.uint32) >> 16) & 1)) >> 16 << 16
+        assert len(np.unique(hi.view(np.float32)[:, 0])) == 2
+    finally:
+        vlq.vlq_index_free(idx)
+
+
 def test_neighbour_distances_by_cell_and_by_query_agree(vlq):
     """The distances to the neighbour centroids (Alg. 3, second loop) computed cell by cell over the
     batch and computed inside the per-query kernel are the same sums: every output is identical.
