@@ -90,7 +90,7 @@ enum {
  * changes what is computed, only by which kernel).  Values are 0 / 1 unless stated.
  */
 enum {
-    VLQ_OPT_COARSE_FP32 = 0,      /* 1: cells and nearest centroids from the fp32 contraction, not the bf16 x 3 one */
+    VLQ_OPT_COARSE_FP32 = 0,      /* 1: cells and nearest centroids from the fp32 contraction, not the bf16 one */
     VLQ_OPT_NEIGHBOURS_PER_QUERY, /* 1: distances to the neighbour centroids per query, not cell by cell over the batch */
     VLQ_OPT_SCAN_PACKED,          /* -1 (default): by mean list length; 0: one list per wave at a time; 1: short lists packed */
     VLQ_OPT_SCAN_GENERIC,         /* 1: the scan with per-cell / per-sub-region tables (2m lookups, Sec. 3.3.2) for every shape */
@@ -98,7 +98,7 @@ enum {
     VLQ_OPT_PIPELINE_PARTS,       /* 0 (default): by batch size; 1 .. 8: parts a batch is cut into, the region traversal of
                                      part p + 1 running on a second stream beside the list scan of part p */
     VLQ_OPT_SMALL_BATCH,          /* default 32: batches of up to this many queries take the forms with the fewest kernel
-                                     launches (fp32 distance matrix, neighbour distances per query); 0: never */
+                                     launches (exact distances to all centroids in one pass, neighbour products pair by pair); 0: never */
     VLQ_OPT_COARSE_SPLIT,         /* 1: the two sweeps of the cell selection multiply split operands (two or three bf16
                                      products per fp32 product) instead of the hi parts alone; same cells either way */
     VLQ_OPT_COUNT
