@@ -879,7 +879,7 @@ static int search_impl(vlq_index *idx, const float *d_q, int32_t nq, int32_t w1,
                 c.qflag = b.take<int32_t>(64);
                 c.cws = b.take<uint8_t>(cells_bf16_workspace(nqp, c.csplit, c.ccap, &o0, &o1, &o2, &o3));
             } else {
-                c.dist = b.take<float>((size_t)c.TQ * k);
+                c.dist = b.take<float>((size_t)c.TQ * k + (size_t)c.TQ * 1024); // (room for the small form's group minima)
                 c.qc = b.take<float>((size_t)c.TQ * D);
                 // a handful of queries: exact distances in one pass over the codebook, cells straight from them
                 c.from_matrix = nqp <= idx->opt[VLQ_OPT_SMALL_BATCH] && nqp <= c.TQ && !idx->opt[VLQ_OPT_COARSE_FP32] &&

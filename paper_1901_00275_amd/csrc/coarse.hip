@@ -769,18 +769,22 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
 //
 // k_small_dists: 16 lanes per centroid row (four components per lane and step, the adder's
 // lane-crossing sum: the summation order of every exact distance in this library), four rows per
-// wave and pass, the queries in LDS; a centroid row is read once for all queries.
+// wave and pass, the queries in LDS; a centroid row is read once for all queries.  Beside the
+// distances every workgroup leaves, per query, the smallest distance of its SMALL_ROWS rows.
 // ---------------------------------------------------------------------------
 #define SMALL_NQ 32   // most queries of the form
-#define SMALL_ROWS 64 // centroid rows per workgroup
+#define SMALL_ROWS 64 // centroid rows per workgroup (one group of the selection below)
 
 __global__ __launch_bounds__(256) void k_small_dists(const float *__restrict__ Q, int nq, int D,
-                                                     const float *__restrict__ C, int k, float *__restrict__ dist)
+                                                     const float *__restrict__ C, int k, float *__restrict__ dist,
+                                                     float *__restrict__ gmin)
 {
     extern __shared__ float yq[]; // [nq][D]
+    __shared__ uint32_t smin[SMALL_NQ];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub16 = lane >> 4, l16 = lane & 15;
     for (int i = tid; i < nq * D; i += 256) yq[i] = Q[i];
+    if (tid < SMALL_NQ) smin[tid] = 0xFFFFFFFFu;
     __syncthreads();
     const bool vec = (D % 4 == 0) && (((uintptr_t)C) % 16 == 0);
     const int r0 = blockIdx.x * SMALL_ROWS;
@@ -806,63 +810,75 @@ __global__ __launch_bounds__(256) void k_small_dists(const float *__restrict__ Q
                 }
             }
             acc = row16_sum(acc);
-            if (l16 == 0 && i < k) dist[(int64_t)q * k + i] = acc;
+            if (l16 == 0 && i < k) {
+                dist[(int64_t)q * k + i] = acc;
+                atomicMin(&smin[q], f2ord(acc));
+            }
         }
     }
+    __syncthreads();
+    if (tid < nq) gmin[(int64_t)tid * gridDim.x + blockIdx.x] = ord2f(smin[tid]);
 }
 
-// One workgroup per query: the row of exact distances in registers; the w-th smallest of the
-// 1 024 per-thread minima bounds the w-th smallest distance from above (tightly: the nearest
-// columns rarely share a thread); the columns at or below it are ranked by (distance, index) by
-// counting.  A row with more than SMALL_CAP such columns (masses of coinciding distances) is
-// ranked by repeated selection over the whole row instead.
+// One workgroup per query.  The w-th smallest of the group minima (a group = the SMALL_ROWS rows of one
+// workgroup above; at most 1 024 groups) bounds the w-th smallest distance from above, tightly: the nearest
+// columns rarely share a group.  Only the groups whose minimum is at or below it can hold a wanted column:
+// their rows are read again (about w groups of the k / SMALL_ROWS), the columns at or below the bound are
+// ranked by (distance, index) by counting.  A query with more than SMALL_CAP such columns (masses of
+// coinciding distances) is ranked by repeated selection over its whole row instead.
 #define SMALL_CAP 1024
 
-template <int VPT>
-__global__ __launch_bounds__(1024) void k_small_cells(const float *__restrict__ dist, int k, int w,
-                                                      int32_t *__restrict__ cells, float *__restrict__ cell_dist)
+__global__ __launch_bounds__(1024) void k_small_cells(const float *__restrict__ dist, const float *__restrict__ gmin,
+                                                      int k, int w, int32_t *__restrict__ cells,
+                                                      float *__restrict__ cell_dist)
 {
     __shared__ uint32_t mins[1024];
     __shared__ uint64_t keys[2 * SMALL_CAP];
+    __shared__ int glist[1024];
     __shared__ uint32_t sh_tau;
-    __shared__ int sh_n;
+    __shared__ int sh_n, sh_g;
     __shared__ unsigned long long sh_cut;
     const int tid = threadIdx.x, lane = tid & 63, row = blockIdx.x;
+    const int G = (k + SMALL_ROWS - 1) / SMALL_ROWS; // <= 1 024
     const float *drow = dist + (int64_t)row * k;
-    float v[VPT];
-#pragma unroll
-    for (int e = 0; e < VPT; ++e) {
-        const int i = tid + 1024 * e;
-        v[e] = i < k ? drow[i] : INFINITY;
+    const uint32_t mymin = tid < G ? f2ord(gmin[(int64_t)row * G + tid]) : 0xFFFFFFFFu;
+    mins[tid] = mymin;
+    if (tid == 0) {
+        sh_n = 0;
+        sh_g = 0;
     }
-    float mn = INFINITY;
-#pragma unroll
-    for (int e = 0; e < VPT; ++e) mn = fminf(mn, v[e]);
-    mins[tid] = f2ord(mn);
-    if (tid == 0) sh_n = 0;
     __syncthreads();
-    if (tid < 64) { // one wave: the w-th smallest of the 1 024 minima, bit by bit from the top (ballot counts)
+    if (tid < 64) { // one wave: the w-th smallest of the minima, bit by bit from the top (ballot counts)
         uint32_t u[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) u[e] = mins[lane + 64 * e];
         uint32_t result = 0;
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t trial = result | (1u << bit);
-            int below = 0;
+        if (w > G) result = 0xFFFFFFFEu; // fewer groups than cells wanted: every group is looked at
+        else
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = result | (1u << bit);
+                int below = 0;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) below += __popcll(__ballot(u[e] < trial));
-            if (below < w) result = trial;
-        }
+                for (int e = 0; e < 16; ++e) below += __popcll(__ballot(u[e] < trial));
+                if (below < w) result = trial;
+            }
         if (lane == 0) sh_tau = result;
     }
     __syncthreads();
     const uint32_t tau = sh_tau;
-#pragma unroll
-    for (int e = 0; e < VPT; ++e)
-        if (f2ord(v[e]) <= tau && tid + 1024 * e < k) {
-            const int pos = atomicAdd(&sh_n, 1);
-            if (pos < SMALL_CAP) keys[pos] = make_key(v[e], (uint32_t)(tid + 1024 * e));
+    if (tid < G && mymin <= tau) glist[atomicAdd(&sh_g, 1)] = tid;
+    __syncthreads();
+    const int ng = sh_g;
+    for (int t = tid; t < ng * SMALL_ROWS; t += 1024) {
+        const int i = glist[t / SMALL_ROWS] * SMALL_ROWS + (t % SMALL_ROWS);
+        if (i < k) {
+            const float v = drow[i];
+            if (f2ord(v) <= tau) {
+                const int pos = atomicAdd(&sh_n, 1);
+                if (pos < SMALL_CAP) keys[pos] = make_key(v, (uint32_t)i);
+            }
         }
+    }
     __syncthreads();
     int cnt = sh_n;
     if (cnt <= SMALL_CAP) {
@@ -874,20 +890,21 @@ __global__ __launch_bounds__(1024) void k_small_cells(const float *__restrict__ 
         if (tid < cnt) keys[rank] = mine;
         __syncthreads();
     } else {
-        // repeated selection: keys below the current w-th smallest are collected over the whole row; a full
-        // buffer is sorted and cut back to w
+        // repeated selection: keys below the current w-th smallest are collected over the whole row, 1 024
+        // columns a round; a full buffer is sorted and cut back to w
         unsigned long long cut = KEY_MAX;
         if (tid == 0) sh_n = 0;
         __syncthreads();
-#pragma unroll 1
-        for (int e = 0; e < VPT; ++e) {
-            const int i = tid + 1024 * e;
-            const uint64_t key = make_key(v[e], (uint32_t)i);
-            if (i < k && key < cut) keys[atomicAdd(&sh_n, 1)] = key; // at most w + 1 024 keys: w from the last cut
+        for (int i0 = 0; i0 < k; i0 += 1024) {
+            const int i = i0 + tid;
+            if (i < k) {
+                const uint64_t key = make_key(drow[i], (uint32_t)i);
+                if (key < cut) keys[atomicAdd(&sh_n, 1)] = key; // at most w + 1 024 keys: w from the last cut
+            }
             __syncthreads();
             const int n = sh_n;
             __syncthreads();
-            if (n > SMALL_CAP || e == VPT - 1) {
+            if (n > SMALL_CAP || i0 + 1024 >= k) {
                 const int sz = next_pow2_dev(n);
                 for (int c = n + tid; c < sz; c += 1024) keys[c] = KEY_MAX;
                 __syncthreads();
@@ -915,18 +932,17 @@ bool cells_small_supported(int nq, int k, int D, int w1)
     return nq <= SMALL_NQ && k >= 4096 && k <= 65536 && w1 <= 128 && (size_t)nq * D * 4 <= 65536;
 }
 
-void launch_cells_small(const float *Q, int nq, int D, const float *C, int k, int w1, float *dist, int32_t *cells,
+size_t cells_small_workspace_floats(int nq, int k) { return (size_t)nq * k + (size_t)nq * ((k + SMALL_ROWS - 1) / SMALL_ROWS); }
+
+void launch_cells_small(const float *Q, int nq, int D, const float *C, int k, int w1, float *ws, int32_t *cells,
                         float *cell_dist, hipStream_t st)
 {
     const size_t smem = (size_t)nq * D * 4;
+    float *dist = ws, *gmin = ws + (size_t)nq * k;
     (void)hipFuncSetAttribute((const void *)k_small_dists, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    hipLaunchKernelGGL(k_small_dists, dim3((unsigned)((k + SMALL_ROWS - 1) / SMALL_ROWS)), dim3(256), smem, st, Q, nq, D, C, k, dist);
-    if (k <= 4 * 1024)
-        hipLaunchKernelGGL(k_small_cells<4>, dim3((unsigned)nq), dim3(1024), 0, st, dist, k, w1, cells, cell_dist);
-    else if (k <= 16 * 1024)
-        hipLaunchKernelGGL(k_small_cells<16>, dim3((unsigned)nq), dim3(1024), 0, st, dist, k, w1, cells, cell_dist);
-    else
-        hipLaunchKernelGGL(k_small_cells<64>, dim3((unsigned)nq), dim3(1024), 0, st, dist, k, w1, cells, cell_dist);
+    hipLaunchKernelGGL(k_small_dists, dim3((unsigned)((k + SMALL_ROWS - 1) / SMALL_ROWS)), dim3(256), smem, st, Q, nq, D, C, k,
+                       dist, gmin);
+    hipLaunchKernelGGL(k_small_cells, dim3((unsigned)nq), dim3(1024), 0, st, dist, gmin, k, w1, cells, cell_dist);
 }
 
 void launch_select_cells(const float *dist, int64_t ld, int rows, int k, const float *Q, int D,

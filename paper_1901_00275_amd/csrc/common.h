@@ -219,10 +219,12 @@ void launch_cells_bf16_exact(const float *Q, int nq, int D, const float *C, int 
                              int nsplit, int32_t *cells, float *cell_dist, int32_t *pair_cnt, int32_t *pair_rank,
                              hipStream_t st);
 
-// A handful of queries: exact distances to all centroids in one pass over the codebook (dist [nq x k],
-// scratch), then the w1 nearest of every query, ascending by (distance, index), from those values.
+// A handful of queries: exact distances to all centroids in one pass over the codebook, then the w1 nearest of
+// every query, ascending by (distance, index), from those values.  ws: cells_small_workspace_floats(nq, k) floats
+// of scratch (the distances and, per query, the minima of groups of 64 centroids).
 bool cells_small_supported(int nq, int k, int D, int w1);
-void launch_cells_small(const float *Q, int nq, int D, const float *C, int k, int w1, float *dist, int32_t *cells,
+size_t cells_small_workspace_floats(int nq, int k);
+void launch_cells_small(const float *Q, int nq, int D, const float *C, int k, int w1, float *ws, int32_t *cells,
                         float *cell_dist, hipStream_t st);
 
 // w smallest entries of each row of dist [rows x k] (GEMM-form values), re-evaluated
