@@ -781,6 +781,7 @@ __global__ __launch_bounds__(256) void k_small_dists(const float *__restrict__ Q
 {
     extern __shared__ float yq[]; // [nq][D]
     __shared__ uint32_t smin[SMALL_NQ];
+    __shared__ float tile[SMALL_NQ][SMALL_ROWS]; // the workgroup's distances, written out in full rows at the end
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub16 = lane >> 4, l16 = lane & 15;
     for (int i = tid; i < nq * D; i += 256) yq[i] = Q[i];
@@ -791,6 +792,57 @@ __global__ __launch_bounds__(256) void k_small_dists(const float *__restrict__ Q
     for (int rr = wave * 4; rr < SMALL_ROWS; rr += 16) {
         const int i = r0 + rr + sub16;
         const float *rowp = C + (int64_t)min(i, k - 1) * D;
+        if (nq >= 8 && vec && D <= 128) {
+            // sixteen queries at a time: the row's components stay in registers, the 16 x 16 partial sums of a
+            // lane group are added across its lanes and transposed at once (register s of lane l belongs to query
+            // s ^ g(l); every step of row16_sum finds the same query in the partner's register): 15 lane-crossing
+            // adds instead of 64, the same additions in the same association, so the same sums to the bit
+            const int gl = (l16 & 3) ^ ((l16 & 4) ? 7 : 0) ^ ((l16 & 8) ? 12 : 0);
+            const int d0 = l16 * 4, d1 = 64 + l16 * 4;
+            const bool has0 = d0 < D, has1 = d1 < D;
+            const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+            const f32x4 c0 = has0 ? *(const f32x4 *)(rowp + d0) : zero4, c1 = has1 ? *(const f32x4 *)(rowp + d1) : zero4;
+            for (int q0 = 0; q0 < nq; q0 += 16) {
+                float r[16];
+#pragma unroll
+                for (int sreg = 0; sreg < 16; ++sreg) {
+                    const float *yv = yq + min(q0 + (sreg ^ gl), nq - 1) * D; // (queries past the end: computed, not kept)
+                    float acc = 0.f;
+                    if (has0) {
+                        const f32x4 y = *(const f32x4 *)(yv + d0);
+                        const float t0 = y.x - c0.x, t1 = y.y - c0.y, t2 = y.z - c0.z, t3 = y.w - c0.w;
+                        acc = fmaf(t0, t0, acc);
+                        acc = fmaf(t1, t1, acc);
+                        acc = fmaf(t2, t2, acc);
+                        acc = fmaf(t3, t3, acc);
+                    }
+                    if (has1) {
+                        const f32x4 y = *(const f32x4 *)(yv + d1);
+                        const float t0 = y.x - c1.x, t1 = y.y - c1.y, t2 = y.z - c1.z, t3 = y.w - c1.w;
+                        acc = fmaf(t0, t0, acc);
+                        acc = fmaf(t1, t1, acc);
+                        acc = fmaf(t2, t2, acc);
+                        acc = fmaf(t3, t3, acc);
+                    }
+                    r[sreg] = acc;
+                }
+#define VLQ_DPP_GET(x, ctrl) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xF, 0xF, true))
+#pragma unroll
+                for (int u = 0; u < 16; u += 2) r[u] += VLQ_DPP_GET(r[u + 1], 0xB1);  // quad_perm [1, 0, 3, 2]
+#pragma unroll
+                for (int u = 0; u < 16; u += 4) r[u] += VLQ_DPP_GET(r[u + 2], 0x4E);  // quad_perm [2, 3, 0, 1]
+#pragma unroll
+                for (int u = 0; u < 16; u += 8) r[u] += VLQ_DPP_GET(r[u + 4], 0x141); // row_half_mirror
+                r[0] += VLQ_DPP_GET(r[8], 0x140);                                     // row_mirror
+#undef VLQ_DPP_GET
+                const int q = q0 + gl;
+                if (q < nq && i < k) {
+                    tile[q][rr + sub16] = r[0];
+                    atomicMin(&smin[q], f2ord(r[0]));
+                }
+            }
+            continue;
+        }
         for (int q = 0; q < nq; ++q) {
             const float *yv = yq + q * D;
             float acc = 0.f;
@@ -811,12 +863,16 @@ __global__ __launch_bounds__(256) void k_small_dists(const float *__restrict__ Q
             }
             acc = row16_sum(acc);
             if (l16 == 0 && i < k) {
-                dist[(int64_t)q * k + i] = acc;
+                tile[q][rr + sub16] = acc;
                 atomicMin(&smin[q], f2ord(acc));
             }
         }
     }
     __syncthreads();
+    for (int t = tid; t < nq * SMALL_ROWS; t += 256) {
+        const int q = t / SMALL_ROWS, r = t % SMALL_ROWS;
+        if (r0 + r < k) dist[(int64_t)q * k + r0 + r] = tile[q][r];
+    }
     if (tid < nq) gmin[(int64_t)tid * gridDim.x + blockIdx.x] = ord2f(smin[tid]);
 }
 
