@@ -97,7 +97,7 @@ enum {
     VLQ_OPT_ENCODE_WAVE,          /* 1: the wave-per-vector encode kernel for every shape */
     VLQ_OPT_PIPELINE_PARTS,       /* 0 (default): by batch size; 1 .. 8: parts a batch is cut into, the region traversal of
                                      part p + 1 running on a second stream beside the list scan of part p */
-    VLQ_OPT_SMALL_BATCH,          /* default 32: batches of up to this many queries take the forms with the fewest kernel
+    VLQ_OPT_SMALL_BATCH,          /* default 64: batches of up to this many queries take the forms with the fewest kernel
                                      launches (exact distances to all centroids in one pass, neighbour products pair by pair); 0: never */
     VLQ_OPT_COARSE_SPLIT,         /* 1: the two sweeps of the cell selection multiply split operands (two or three bf16
                                      products per fp32 product) instead of the hi parts alone; same cells either way */

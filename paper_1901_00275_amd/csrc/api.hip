@@ -93,7 +93,7 @@ struct vlq_index {
     //   cn   [k] ||c - mu_c||^2;  Cc [k x D] c - mu_c, the operand of the fp32 contraction.
     float *mu = nullptr, *mu_c = nullptr, *cn = nullptr, *Cc = nullptr;
     // kernel choices (vlq_index_set_option) and the query-side lambda range
-    int opt[VLQ_OPT_COUNT] = {0, 0, -1, 0, 0, 0, 32, 0};
+    int opt[VLQ_OPT_COUNT] = {0, 0, -1, 0, 0, 0, 64, 0};
     // second stream (default priority) and the events that order it against the caller's stream
     hipStream_t side = nullptr;
     hipEvent_t ev_go[VLQ_MAX_PARTS] = {}, ev_done[VLQ_MAX_PARTS] = {};

@@ -772,7 +772,7 @@ __global__ __launch_bounds__(SEL2_NT) void k_select_cells_reg(const float *__res
 // wave and pass, the queries in LDS; a centroid row is read once for all queries.  Beside the
 // distances every workgroup leaves, per query, the smallest distance of its SMALL_ROWS rows.
 // ---------------------------------------------------------------------------
-#define SMALL_NQ 32   // most queries of the form
+#define SMALL_NQ 64   // most queries of the form
 #define SMALL_ROWS 64 // centroid rows per workgroup (one group of the selection below)
 
 __global__ __launch_bounds__(256) void k_small_dists(const float *__restrict__ Q, int nq, int D,

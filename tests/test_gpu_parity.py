@@ -504,7 +504,7 @@ def test_batch_parts_and_small_batch_forms_agree(vlq, name):
         assert np.allclose(a[0], b[0], rtol=1e-6) and np.allclose(a[3], b[3], rtol=1e-6)
         # the two sweeps of the cell selection with split operands instead of the hi parts alone: the candidate
         # lists differ, the exact ranking of them does not
-        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SMALL_BATCH, 32)
+        vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_SMALL_BATCH, 64)
         vlq.vlq_index_set_option(idx, vlq.VLQ_OPT_COARSE_SPLIT, 1)
         got = gpu_search(vlq, idx, pr.Y, w1, w2, K)
         for x, y in zip(ref, got):
