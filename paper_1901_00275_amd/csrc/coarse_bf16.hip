@@ -587,6 +587,17 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
             for (int e = 0; e < 8; ++e) below += __popcll(__ballot(u[e] < trial)); // (a filler is below nothing)
             if (below < want) result = trial;
         }
+    } else if (G <= 4096) { // small batches have many column splits: still in registers
+        uint32_t u[64];
+#pragma unroll
+        for (int e = 0; e < 64; ++e) u[e] = lane + 64 * e < G ? mine[lane + 64 * e] : 0xFFFFFFFFu;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = result | (1u << bit);
+            int below = 0;
+#pragma unroll
+            for (int e = 0; e < 64; ++e) below += __popcll(__ballot(u[e] < trial));
+            if (below < want) result = trial;
+        }
     } else {
         for (int bit = 31; bit >= 0; --bit) {
             const uint32_t trial = result | (1u << bit);

@@ -900,8 +900,9 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         const size_t rows_bytes = (size_t)(n + 1) * D * 4;
         (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)rows_bytes);
-        // grouped: at most np / ND_PCH full chunks and one partial chunk per cell
-        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)(grouped ? np / ND_PCH + k : np)), dim3(256), rows_bytes, st, Q,
+        // grouped: at most np / ND_PCH full chunks and one partial chunk per probed cell
+        const int64_t most_cells = np < (int64_t)k ? np : (int64_t)k;
+        hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)(grouped ? np / ND_PCH + most_cells : np)), dim3(256), rows_bytes, st, Q,
                            D, C, S, n, k, w1, cells, poff, grouped ? pairs : nullptr, np, pw.woff, pw.work, bq);
         bpre = bq;
     }
