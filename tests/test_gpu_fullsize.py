@@ -14,7 +14,9 @@ its inputs come from the seeded generators (raw vectors are regenerated from the
    raw vector of that id, rebuilds the approximated point and its distance to the query, and checks
    that the point's list was visited;
  * completeness probe: the exact nearest neighbour of a sampled query, if its list is visited and
-   its ADC distance beats the K-th result, must be among the results.
+   its ADC distance beats the K-th result, must be among the results;
+ * batches of 1 to 3 000 of the same queries (which take the small- and medium-batch kernels) return the
+   rows of the full batch bit for bit.
 """
 import numpy as np
 import pytest
@@ -108,6 +110,15 @@ def test_full_size_configurations_sampled(vlq, oracle_mod, name):
         vlq.vlq_search_debug(wl.idx, wl.Y, nq, w1, w2, K, od, oi, cells, cd, sub, ss)
         torch.cuda.synchronize()
         assert datagen.recall_at(oi[:GT_ROWS], wl.gt[:GT_ROWS], 100) > 0.2  # sanity: the index finds neighbours
+        # a query's result does not depend on the batch it arrives in: smaller batches take other kernels (one-pass
+        # exact cell selection up to 64 queries, pairwise neighbour products, more column splits and a wider
+        # threshold search, scans split over workgroups and merged) and must return the same rows bit for bit
+        for nb in (1, 40, 64, 65, 700, 3000):
+            bd = torch.full((nb, K), -1.0, device=DEV)
+            bi = torch.full((nb, K), -7, dtype=torch.int32, device=DEV)
+            vlq.vlq_search(wl.idx, wl.Y[:nb].contiguous(), nb, w1, w2, K, bd, bi)
+            torch.cuda.synchronize()
+            assert torch.equal(bi, oi[:nb]) and torch.equal(bd, od[:nb]), f"batch of {nb} differs from the full batch"
         qs = np.sort(rng.choice(GT_ROWS, 24, replace=False))
         # the lists these queries visited, as the library stores them, for the oracle's scan
         qs_dev = torch.as_tensor(qs, device=DEV)
