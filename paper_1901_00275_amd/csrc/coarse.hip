@@ -995,7 +995,8 @@ void launch_cells_small(const float *Q, int nq, int D, const float *C, int k, in
 {
     const size_t smem = (size_t)nq * D * 4;
     float *dist = ws, *gmin = ws + (size_t)nq * k;
-    (void)hipFuncSetAttribute((const void *)k_small_dists, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (smem > 49152) // (48 KB of dynamic LDS beside the static part need no asking)
+        (void)hipFuncSetAttribute((const void *)k_small_dists, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_small_dists, dim3((unsigned)((k + SMALL_ROWS - 1) / SMALL_ROWS)), dim3(256), smem, st, Q, nq, D, C, k,
                        dist, gmin);
     hipLaunchKernelGGL(k_small_cells, dim3((unsigned)nq), dim3(1024), 0, st, dist, gmin, k, w1, cells, cell_dist);

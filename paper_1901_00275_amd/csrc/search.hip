@@ -898,8 +898,8 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
                                rank, pairs, pw.woff, pw.work, ND_PCH);
         }
         const size_t rows_bytes = (size_t)(n + 1) * D * 4;
-        (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)rows_bytes);
+        if (rows_bytes > 49152) // (48 KB of dynamic LDS beside the static part need no asking)
+            (void)hipFuncSetAttribute((const void *)k_neighbour_dists, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rows_bytes);
         // grouped: at most np / ND_PCH full chunks and one partial chunk per probed cell
         const int64_t most_cells = np < (int64_t)k ? np : (int64_t)k;
         hipLaunchKernelGGL(k_neighbour_dists, dim3((unsigned)(grouped ? np / ND_PCH + most_cells : np)), dim3(256), rows_bytes, st, Q,
@@ -926,7 +926,8 @@ void launch_subregions(const float *Q, int nq, int D, const float *C, const int3
         return;
     }
     size_t smem = lean ? (size_t)sz * (8 + 4) : (size_t)sz * (8 + 4 + 2 + 4) + (size_t)D * 4;
-    (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (smem > 49152) // (48 KB of dynamic LDS beside the static part need no asking)
+        (void)hipFuncSetAttribute((const void *)k_subregions, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_subregions, dim3((unsigned)nq), dim3(256), smem, st, Q, D, C, S, E, n, cells,
                        cell_dist, w1, w2, lam_min, lam_max, sz, sub, sub_score, scan_label, scan_g, off, desc, bpre);
 }
@@ -1130,7 +1131,8 @@ void launch_scan(const ScanArgs &a, hipStream_t st)
     int KP, SZ;
     scan_sizes(a.K, &KP, &SZ);
     size_t smem = (size_t)SZ * 8 + (size_t)a.m * 256 * 8 + (size_t)a.D * 4 * 3;
-    (void)hipFuncSetAttribute((const void *)k_scan, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (smem > 49152) // (48 KB of dynamic LDS beside the static part need no asking)
+        (void)hipFuncSetAttribute((const void *)k_scan, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_scan, dim3((unsigned)(a.nq * a.nsplit)), dim3(SCAN_NT), smem, st, a, KP, SZ);
 }
 
@@ -1184,6 +1186,7 @@ void launch_merge(const uint64_t *partial, int nq, int nsplit, int K, float *out
 {
     if (nq <= 0) return;
     size_t smem = (size_t)(nsplit + 1) * K * 8;
-    (void)hipFuncSetAttribute((const void *)k_merge, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (smem > 49152) // (48 KB of dynamic LDS beside the static part need no asking)
+        (void)hipFuncSetAttribute((const void *)k_merge, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k_merge, dim3((unsigned)nq), dim3(256), smem, st, partial, nsplit, K, out_dist, out_ids);
 }
