@@ -572,14 +572,13 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = blockIdx.x * 4 + wave;
     if (row >= nq) return;
-    uint32_t *mine = tkeys + wave * G;
-    for (int i = lane; i < G; i += 64) mine[i] = f2ord(gmin[(int64_t)row * G + i]);
-    // (the wave reads back only what it wrote itself)
+    uint32_t *mine = tkeys + wave * G; // (a wave reads back only what it wrote itself)
+    const float *grow = gmin + (int64_t)row * G;
     uint32_t result = 0;
-    if (G <= 512) { // the usual case: the minima in registers
+    if (G <= 512) { // the usual case: the minima in registers, all loads in flight together
         uint32_t u[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) u[e] = lane + 64 * e < G ? mine[lane + 64 * e] : 0xFFFFFFFFu;
+        for (int e = 0; e < 8; ++e) u[e] = lane + 64 * e < G ? f2ord(grow[lane + 64 * e]) : 0xFFFFFFFFu;
         for (int bit = 31; bit >= 0; --bit) {
             const uint32_t trial = result | (1u << bit);
             int below = 0;
@@ -590,15 +589,58 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
     } else if (G <= 4096) { // small batches have many column splits: still in registers
         uint32_t u[64];
 #pragma unroll
-        for (int e = 0; e < 64; ++e) u[e] = lane + 64 * e < G ? mine[lane + 64 * e] : 0xFFFFFFFFu;
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t trial = result | (1u << bit);
-            int below = 0;
+        for (int e = 0; e < 64; ++e) u[e] = lane + 64 * e < G ? f2ord(grow[lane + 64 * e]) : 0xFFFFFFFFu;
+        // Most of the minima cannot matter: the want-th smallest of the 64 per-lane minima bounds the answer from
+        // above, the few values at or below it are compacted and searched eight to a lane.
+        bool pruned = false;
+        if (want <= 64) {
+            uint32_t lm = 0xFFFFFFFFu;
 #pragma unroll
-            for (int e = 0; e < 64; ++e) below += __popcll(__ballot(u[e] < trial));
-            if (below < want) result = trial;
+            for (int e = 0; e < 64; ++e) lm = min(lm, u[e]);
+            uint32_t bound = 0;
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = bound | (1u << bit);
+                if (__popcll(__ballot(lm < trial)) < want) bound = trial;
+            }
+            int keep = 0;
+#pragma unroll
+            for (int e = 0; e < 64; ++e) keep += u[e] <= bound;
+            int at = keep;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(at, o, 64);
+                if (lane >= o) at += t;
+            }
+            const int total = __shfl(at, 63, 64);
+            if (total <= 512) {
+                at -= keep;
+#pragma unroll
+                for (int e = 0; e < 64; ++e)
+                    if (u[e] <= bound) mine[at++] = u[e];
+                __builtin_amdgcn_wave_barrier();
+                uint32_t v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = lane + 64 * e < total ? mine[lane + 64 * e] : 0xFFFFFFFFu;
+                for (int bit = 31; bit >= 0; --bit) {
+                    const uint32_t trial = result | (1u << bit);
+                    int below = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) below += __popcll(__ballot(v[e] < trial));
+                    if (below < want) result = trial;
+                }
+                pruned = true;
+            }
         }
+        if (!pruned)
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = result | (1u << bit);
+                int below = 0;
+#pragma unroll
+                for (int e = 0; e < 64; ++e) below += __popcll(__ballot(u[e] < trial));
+                if (below < want) result = trial;
+            }
     } else {
+        for (int i = lane; i < G; i += 64) mine[i] = f2ord(grow[i]);
         for (int bit = 31; bit >= 0; --bit) {
             const uint32_t trial = result | (1u << bit);
             int below = 0;
