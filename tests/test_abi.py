@@ -39,6 +39,34 @@ def test_binding_has_the_same_names(vlq):
         assert hasattr(vlq, name), name
 
 
+def test_binding_has_the_same_constants(vlq):
+    """Options, stages and error codes of the header agree with the binding's constants."""
+    src = open(os.path.join(ROOT, "include", "vlq.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    opts, stages = 0, []
+    for body in re.findall(r"enum\s*\{(.*?)\}", src, flags=re.S):
+        value = -1
+        for item in body.split(","):
+            item = item.strip()
+            if not item:
+                continue
+            m = re.match(r"(VLQ_[A-Z0-9_]+)\s*(?:=\s*(-?\d+))?$", item)
+            assert m, item
+            value = int(m.group(2)) if m.group(2) is not None else value + 1
+            name = m.group(1)
+            if name.endswith("_COUNT"):
+                continue
+            if name.startswith("VLQ_STAGE_"):
+                assert value == len(stages)
+                stages.append(name[len("VLQ_STAGE_"):].lower())
+            else:
+                assert getattr(vlq, name) == value, name
+                opts += 1
+    assert opts >= 8 and tuple(stages) == tuple(vlq.STAGES)
+    for name, value in re.findall(r"#define\s+(VLQ_(?:OK|E[A-Z]+))\s+\(?(-?\d+)\)?", src):
+        assert getattr(vlq, name) == int(value), name
+
+
 @pytest.mark.parametrize("d,nlist,n,m,lo,hi", [
     (0, 16, 4, 1, 0, 0), (128, 16, 4, 7, 0, 0), (128, 4, 4, 8, 0, 0), (128, 16, 0, 8, 0, 0),
     (128, 16, 4, 8, 0.1, 0.5), (128, 16, 4, 8, -0.3, 0.5), (2048, 16, 4, 8, 0, 0), (128, 16, 4, 128, 0, 0),
