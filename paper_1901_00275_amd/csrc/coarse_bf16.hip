@@ -578,7 +578,10 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
     if (G <= 512) { // the usual case: the minima in registers, all loads in flight together
         uint32_t u[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) u[e] = lane + 64 * e < G ? f2ord(grow[lane + 64 * e]) : 0xFFFFFFFFu;
+        for (int e = 0; e < 8; ++e) { // (clamped, not branched: the loads go out back to back)
+            const float gv = grow[min(lane + 64 * e, G - 1)];
+            u[e] = lane + 64 * e < G ? f2ord(gv) : 0xFFFFFFFFu;
+        }
         for (int bit = 31; bit >= 0; --bit) {
             const uint32_t trial = result | (1u << bit);
             int below = 0;
@@ -589,18 +592,25 @@ __global__ __launch_bounds__(256) void k_cell_threshold(const float *__restrict_
     } else if (G <= 4096) { // small batches have many column splits: still in registers
         uint32_t u[64];
 #pragma unroll
-        for (int e = 0; e < 64; ++e) u[e] = lane + 64 * e < G ? f2ord(grow[lane + 64 * e]) : 0xFFFFFFFFu;
-        // Most of the minima cannot matter: the want-th smallest of the 64 per-lane minima bounds the answer from
-        // above, the few values at or below it are compacted and searched eight to a lane.
+        for (int e = 0; e < 64; ++e) {
+            const float gv = grow[min(lane + 64 * e, G - 1)];
+            u[e] = lane + 64 * e < G ? f2ord(gv) : 0xFFFFFFFFu;
+        }
+        // Most of the minima cannot matter: the want-th smallest of the two smallest values of every lane (128
+        // of the values) bounds the answer from above, and closely, since the smallest values are spread over the
+        // lanes; the few values at or below it are compacted and searched eight to a lane.
         bool pruned = false;
-        if (want <= 64) {
-            uint32_t lm = 0xFFFFFFFFu;
+        if (want <= 128) {
+            uint32_t m1 = 0xFFFFFFFFu, m2 = 0xFFFFFFFFu;
 #pragma unroll
-            for (int e = 0; e < 64; ++e) lm = min(lm, u[e]);
+            for (int e = 0; e < 64; ++e) {
+                m2 = min(m2, max(m1, u[e]));
+                m1 = min(m1, u[e]);
+            }
             uint32_t bound = 0;
             for (int bit = 31; bit >= 0; --bit) {
                 const uint32_t trial = bound | (1u << bit);
-                if (__popcll(__ballot(lm < trial)) < want) bound = trial;
+                if (__popcll(__ballot(m1 < trial)) + __popcll(__ballot(m2 < trial)) < want) bound = trial;
             }
             int keep = 0;
 #pragma unroll
